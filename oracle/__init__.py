@@ -1,0 +1,186 @@
+"""TEST INFRASTRUCTURE ONLY: ctypes front end of the plain fp64 CPU oracle.
+
+The oracle states, from the paper's definitions (Sec. 3.1 gate / average,
+Sec. 3.2 neuron-level masks, App. A column loads), what the masked SwiGLU MLP
+path computes.  It shares nothing with the GPU library and must never be
+imported by it: only tests, the smoke check and the benchmark's cpu_baseline
+leg use this module.
+
+All floating-point inputs are widened exactly to fp64 before the C code sees
+them; no intermediate is rounded.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sdp_oracle.c")
+_LIB = os.path.join(_HERE, "libsdp_oracle.so")
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (fp64, -O2, OpenMP on outer loops)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fno-fast-math", "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.orc_mix64.restype = ctypes.c_uint64
+        L.orc_mix64.argtypes = [ctypes.c_uint64]
+        L.orc_rand64.restype = ctypes.c_uint64
+        L.orc_rand64.argtypes = [ctypes.c_uint64] * 3
+        L.orc_rand_below.restype = ctypes.c_uint64
+        L.orc_rand_below.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64), ctypes.c_uint64]
+        L.orc_make_masks.restype = ctypes.c_int
+        L.orc_make_masks.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_int, _u8p]
+        L.orc_index_masks.restype = None
+        L.orc_index_masks.argtypes = [ctypes.c_int, ctypes.c_int64, _u8p, _i32p, ctypes.c_int64, _i32p, _i32p, _u8p]
+        L.orc_mlp_fwd.restype = None
+        L.orc_mlp_fwd.argtypes = [ctypes.c_int64] * 3 + [_f64p] * 8
+        L.orc_mlp_bwd.restype = None
+        L.orc_mlp_bwd.argtypes = [ctypes.c_int64] * 3 + [_f64p] * 14
+        L.orc_worker_step.restype = ctypes.c_int64
+        L.orc_worker_step.argtypes = [ctypes.c_int] + [ctypes.c_int64] * 3 + [_u8p] + [_f64p] * 12
+        L.orc_gated_average.restype = None
+        L.orc_gated_average.argtypes = [
+            ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+            ctypes.POINTER(ctypes.c_void_p), _u8p, _f64p, _u8p,
+        ]
+        L.orc_rho2.restype = ctypes.c_double
+        L.orc_rho2.argtypes = [ctypes.c_int, ctypes.c_int64, _u8p]
+        _lib = L
+    return _lib
+
+
+def _p(a, t):
+    return a.ctypes.data_as(t)
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def mix64(z):
+    return int(lib().orc_mix64(ctypes.c_uint64(z & (2**64 - 1))))
+
+
+def rand64(seed, stream, ctr):
+    return int(lib().orc_rand64(seed, stream, ctr))
+
+
+def rand_below(seed, stream, ctr, n):
+    """Returns (value, next counter)."""
+    c = ctypes.c_uint64(ctr)
+    v = lib().orc_rand_below(seed, stream, ctypes.byref(c), n)
+    return int(v), int(c.value)
+
+
+def make_masks(K, F, p, seed, require_cover=True):
+    """Mask matrix m[K][F] (uint8) with row sums p; see orc_make_masks."""
+    mask = np.zeros((K, F), dtype=np.uint8)
+    rc = lib().orc_make_masks(K, F, p, seed, int(bool(require_cover)), _p(mask, _u8p))
+    if rc != 0:
+        raise ValueError(f"orc_make_masks failed with {rc}")
+    return mask
+
+
+def index_masks(mask, idx_ld=None):
+    """(idx[K][idx_ld], pos[K][F], count[K], cov[F]) of a 0/1 mask matrix."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, F = mask.shape
+    if idx_ld is None:
+        idx_ld = int(mask.astype(np.int64).sum(axis=1).max()) if K else 0
+    idx = np.empty((K, idx_ld), dtype=np.int32)
+    pos = np.empty((K, F), dtype=np.int32)
+    count = np.empty((K,), dtype=np.int32)
+    cov = np.empty((F,), dtype=np.uint8)
+    lib().orc_index_masks(K, F, _p(mask, _u8p), _p(idx, _i32p), idx_ld, _p(pos, _i32p), _p(count, _i32p), _p(cov, _u8p))
+    return idx, pos, count, cov
+
+
+def mlp_fwd(X, W1, W3, W2T):
+    """Dense SwiGLU MLP forward -> dict(G, U, A, Y), all fp64."""
+    X, W1, W3, W2T = map(_f64, (X, W1, W3, W2T))
+    T, d = X.shape
+    F = W1.shape[0]
+    assert W1.shape == (F, d) and W3.shape == (F, d) and W2T.shape == (F, d)
+    G = np.empty((T, F)); U = np.empty((T, F)); A = np.empty((T, F)); Y = np.empty((T, d))
+    lib().orc_mlp_fwd(T, d, F, *[_p(a, _f64p) for a in (X, W1, W3, W2T, G, U, A, Y)])
+    return dict(G=G, U=U, A=A, Y=Y)
+
+
+def mlp_bwd(X, dY, W1, W3, W2T, G, U, A):
+    """Dense SwiGLU MLP backward -> dict(dG, dU, dX, dW1, dW3, dW2T), all fp64."""
+    X, dY, W1, W3, W2T, G, U, A = map(_f64, (X, dY, W1, W3, W2T, G, U, A))
+    T, d = X.shape
+    F = W1.shape[0]
+    dG = np.empty((T, F)); dU = np.empty((T, F)); dX = np.empty((T, d))
+    dW1 = np.empty((F, d)); dW3 = np.empty((F, d)); dW2T = np.empty((F, d))
+    lib().orc_mlp_bwd(T, d, F, *[_p(a, _f64p) for a in (X, dY, W1, W3, W2T, G, U, A, dG, dU, dX, dW1, dW3, dW2T)])
+    return dict(dG=dG, dU=dU, dX=dX, dW1=dW1, dW3=dW3, dW2T=dW2T)
+
+
+def worker_step(mode, mask_k, X, dY, W1, W3, W2T):
+    """One worker's forward + backward under forward ('fm') or backward ('bm') masking.
+
+    Returns full-size fp64 arrays G, U [T][F]; Y, dX [T][d]; dW1, dW3, dW2T [F][d]
+    and `nonzero_off_mask` (count of off-mask gradient entries that were not
+    exactly zero before any gradient masking; the paper's Sec. 3.1 remark says
+    it is 0 under forward masking).
+    """
+    m = {"fm": 0, "bm": 1}[mode]
+    mask_k = np.ascontiguousarray(mask_k, dtype=np.uint8)
+    X, dY, W1, W3, W2T = map(_f64, (X, dY, W1, W3, W2T))
+    T, d = X.shape
+    F = W1.shape[0]
+    assert mask_k.shape == (F,)
+    G = np.empty((T, F)); U = np.empty((T, F)); Y = np.empty((T, d)); dX = np.empty((T, d))
+    dW1 = np.empty((F, d)); dW3 = np.empty((F, d)); dW2T = np.empty((F, d))
+    nz = lib().orc_worker_step(
+        m, T, d, F, _p(mask_k, _u8p),
+        *[_p(a, _f64p) for a in (X, dY, W1, W3, W2T, G, U, Y, dX, dW1, dW3, dW2T)],
+    )
+    return dict(G=G, U=U, Y=Y, dX=dX, dW1=dW1, dW3=dW3, dW2T=dW2T, nonzero_off_mask=int(nz))
+
+
+def gated_average(g_list, mask):
+    """Coverage-normalised average of K gradient buffers [R][D].
+
+    `g_list` holds K numpy arrays of dtype float32, float64 or uint16 (bf16
+    bit patterns); `mask` is uint8 [K][R].  Returns (out fp64 [R][D], cov u8 [R]).
+    """
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, R = mask.shape
+    assert len(g_list) == K
+    g_list = [np.ascontiguousarray(g) for g in g_list]
+    D = g_list[0].shape[1]
+    dt = g_list[0].dtype
+    gtype = {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float64): 2}[dt]
+    for g in g_list:
+        assert g.shape == (R, D) and g.dtype == dt
+    ptrs = (ctypes.c_void_p * K)(*[g.ctypes.data for g in g_list])
+    out = np.empty((R, D), dtype=np.float64)
+    cov = np.empty((R,), dtype=np.uint8)
+    lib().orc_gated_average(K, R, D, gtype, ptrs, _p(mask, _u8p), _p(out, _f64p), _p(cov, _u8p))
+    return out, cov
+
+
+def rho2(mask):
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, F = mask.shape
+    return float(lib().orc_rho2(K, F, _p(mask, _u8p)))

@@ -1,0 +1,333 @@
+/*
+ * sdp_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64 CPU statement of what the Subnetwork-Data-Parallel (SDP)
+ * masked SwiGLU MLP path computes, written out from the paper's definitions.
+ * It shares no code with the GPU library and is never called by it.  Only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may use it.
+ *
+ * Notation follows the paper: n = K workers, m = F components (hidden neurons),
+ * p = per-worker budget, mask[k][j] = m_{k,j} (Sec. 3.1), c_j = column load
+ * (App. A).  The MLP is the bias-free SwiGLU block
+ *     G = X W1^T,  U = X W3^T,  A = silu(G) * U,  Y = A W2^T
+ * with every weight stored neuron-major: W1[F][d], W3[F][d], W2T[F][d]
+ * (W2T[j][:] is column j of W2), so that hidden neuron j owns row j of each.
+ *
+ * No blocking, no fusion, no reordering: every loop below is the definition.
+ * OpenMP is applied to outermost independent loops only.
+ *
+ * Parity pins (see tests/test_oracle_*.py): the finaliser against the published
+ * SplitMix64 sequence; the sampler by its invariants and a uniformity test;
+ * index/coverage against brute force; the dense MLP forward against a library
+ * einsum; its gradients against central finite differences; forward masking
+ * against the compact-slice route and the zero-gradient property; backward
+ * masking and the gated average against their C = 1 (DDP) reductions.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------- */
+/* Counter-based random numbers.  The 64-bit finaliser is the output function */
+/* of SplitMix64 (Steele, Lea, Flood 2014).  A stream is (seed, stream id);   */
+/* its c-th draw is a pure function of (seed, stream, c).                     */
+/* ------------------------------------------------------------------------- */
+#define ORC_GOLDEN 0x9E3779B97F4A7C15ULL
+
+uint64_t orc_mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+uint64_t orc_rand64(uint64_t seed, uint64_t stream, uint64_t ctr) {
+    uint64_t key = orc_mix64(seed + ORC_GOLDEN * (stream + 1));
+    return orc_mix64(key + ORC_GOLDEN * (ctr + 1));
+}
+
+typedef struct {
+    uint64_t seed, stream, ctr;
+} orc_rng;
+
+static uint64_t rng_next(orc_rng* r) { return orc_rand64(r->seed, r->stream, r->ctr++); }
+
+/* Uniform integer in [0, n): draws below 2^64 mod n are rejected, so every   */
+/* residue has exactly floor(2^64 / n) accepted preimages.                    */
+static uint64_t rng_below(orc_rng* r, uint64_t n) {
+    uint64_t reject_below = (0 - n) % n;
+    for (;;) {
+        uint64_t x = rng_next(r);
+        if (x >= reject_below) return x % n;
+    }
+}
+
+/* Exposed so that a test can check the bounded draw on its own. */
+uint64_t orc_rand_below(uint64_t seed, uint64_t stream, uint64_t* ctr, uint64_t n) {
+    orc_rng r = {seed, stream, *ctr};
+    uint64_t v = rng_below(&r, n);
+    *ctr = r.ctr;
+    return v;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Mask matrix m in {0,1}^{K x F} (Sec. 3.1), exact row budget sum_j m_kj = p  */
+/* (App. A).  Uniform sampler: worker k draws p distinct neurons by a partial */
+/* Fisher-Yates shuffle on stream k.  With require_cover, every neuron left   */
+/* with column load 0 is then handed to a worker that gives up a neuron of    */
+/* load >= 2 (stream K drives the repair), which keeps every row sum at p.    */
+/* Returns 0, or -1 on bad arguments, -4 if coverage is impossible (K p < F). */
+/* ------------------------------------------------------------------------- */
+int orc_make_masks(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask) {
+    if (K < 1 || F < 1 || p < 0 || p > F || !mask) return -1;
+    if (require_cover && (int64_t)K * p < F) return -4;
+    memset(mask, 0, (size_t)K * F);
+    int32_t* perm = (int32_t*)malloc(sizeof(int32_t) * (size_t)F);
+    for (int k = 0; k < K; ++k) {
+        orc_rng r = {seed, (uint64_t)k, 0};
+        for (int j = 0; j < F; ++j) perm[j] = j;
+        for (int i = 0; i < p; ++i) {
+            int j = i + (int)rng_below(&r, (uint64_t)(F - i));
+            int32_t tmp = perm[i];
+            perm[i] = perm[j];
+            perm[j] = tmp;
+            mask[(size_t)k * F + perm[i]] = 1;
+        }
+    }
+    free(perm);
+    if (!require_cover) return 0;
+
+    int32_t* load = (int32_t*)calloc((size_t)F, sizeof(int32_t));
+    int32_t* donors = (int32_t*)malloc(sizeof(int32_t) * (size_t)F);
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < F; ++j) load[j] += mask[(size_t)k * F + j];
+    orc_rng r = {seed, (uint64_t)K, 0};
+    for (int j = 0; j < F; ++j) {
+        if (load[j] != 0) continue;
+        int first = (int)rng_below(&r, (uint64_t)K);
+        for (int s = 0; s < K; ++s) {
+            int k = (first + s) % K;
+            int nd = 0;
+            for (int q = 0; q < F; ++q)
+                if (mask[(size_t)k * F + q] && load[q] >= 2) donors[nd++] = q;
+            if (nd == 0) continue;
+            int q = donors[rng_below(&r, (uint64_t)nd)];
+            mask[(size_t)k * F + q] = 0;
+            load[q] -= 1;
+            mask[(size_t)k * F + j] = 1;
+            load[j] = 1;
+            break;
+        }
+    }
+    free(load);
+    free(donors);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Index form of a mask: idx[k][i] = i-th active neuron of worker k in         */
+/* ascending order (entries past count[k] are -1; row stride idx_ld),          */
+/* pos[k][j] = rank of j inside worker k's active set or -1,                   */
+/* count[k] = row sum, cov[j] = c_j = sum_k m_kj (App. A).                     */
+/* ------------------------------------------------------------------------- */
+void orc_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t idx_ld,
+                     int32_t* pos, int32_t* count, uint8_t* cov) {
+    for (int k = 0; k < K; ++k) {
+        int32_t seen = 0;
+        for (int64_t i = 0; i < idx_ld; ++i) idx[k * idx_ld + i] = -1;
+        for (int64_t j = 0; j < F; ++j) {
+            if (mask[k * F + j]) {
+                if (seen < idx_ld) idx[k * idx_ld + seen] = (int32_t)j;
+                pos[k * F + j] = seen;
+                seen += 1;
+            } else {
+                pos[k * F + j] = -1;
+            }
+        }
+        count[k] = seen;
+    }
+    for (int64_t j = 0; j < F; ++j) {
+        int c = 0;
+        for (int k = 0; k < K; ++k) c += mask[k * F + j] ? 1 : 0;
+        cov[j] = (uint8_t)c;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Dense SwiGLU MLP, forward.  All arrays row-major fp64.                      */
+/*   X[T][d], W1/W3/W2T[F][d] -> G,U,A[T][F], Y[T][d]                          */
+/* ------------------------------------------------------------------------- */
+static double sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+void orc_mlp_fwd(int64_t T, int64_t d, int64_t F, const double* X, const double* W1,
+                 const double* W3, const double* W2T, double* G, double* U, double* A, double* Y) {
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t j = 0; j < F; ++j) {
+            double g = 0.0, u = 0.0;
+            for (int64_t e = 0; e < d; ++e) {
+                g += X[t * d + e] * W1[j * d + e];
+                u += X[t * d + e] * W3[j * d + e];
+            }
+            G[t * F + j] = g;
+            U[t * F + j] = u;
+            A[t * F + j] = g * sigmoid(g) * u;
+        }
+        /* Y[t][e] = sum_j A[t][j] W2T[j][e], the sum over j taken in neuron order. */
+        for (int64_t e = 0; e < d; ++e) Y[t * d + e] = 0.0;
+        for (int64_t j = 0; j < F; ++j)
+            for (int64_t e = 0; e < d; ++e) Y[t * d + e] += A[t * F + j] * W2T[j * d + e];
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Dense SwiGLU MLP, backward of L = <dY, Y>.  Needs G, U, A from the forward. */
+/*   dA = dY W2;  dU = dA silu(G);  dG = dA U silu'(G),                        */
+/*   silu'(z) = s(z) (1 + z (1 - s(z)));                                       */
+/*   dW2T[j] = sum_t A[t][j] dY[t];  dW1[j] = sum_t dG[t][j] X[t];             */
+/*   dW3[j] = sum_t dU[t][j] X[t];   dX = dG W1 + dU W3.                       */
+/* dGbuf/dUbuf are [T][F] outputs (returned so that tests can look at them).   */
+/* Every sum over t runs in token order for its (j, e).                        */
+/* ------------------------------------------------------------------------- */
+void orc_mlp_bwd(int64_t T, int64_t d, int64_t F, const double* X, const double* dY,
+                 const double* W1, const double* W3, const double* W2T, const double* G,
+                 const double* U, const double* A, double* dGbuf, double* dUbuf, double* dX,
+                 double* dW1, double* dW3, double* dW2T) {
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t j = 0; j < F; ++j) {
+            double da = 0.0;
+            for (int64_t e = 0; e < d; ++e) da += dY[t * d + e] * W2T[j * d + e];
+            double g = G[t * F + j], u = U[t * F + j];
+            double s = sigmoid(g);
+            dUbuf[t * F + j] = da * (g * s);
+            dGbuf[t * F + j] = da * u * (s * (1.0 + g * (1.0 - s)));
+        }
+        /* dX[t][e] = sum_j (dG[t][j] W1[j][e] + dU[t][j] W3[j][e]), j in neuron order. */
+        for (int64_t e = 0; e < d; ++e) dX[t * d + e] = 0.0;
+        for (int64_t j = 0; j < F; ++j)
+            for (int64_t e = 0; e < d; ++e)
+                dX[t * d + e] += dGbuf[t * F + j] * W1[j * d + e] + dUbuf[t * F + j] * W3[j * d + e];
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < F; ++j) {
+        for (int64_t e = 0; e < d; ++e) dW1[j * d + e] = dW3[j * d + e] = dW2T[j * d + e] = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            double dg = dGbuf[t * F + j], du = dUbuf[t * F + j], a = A[t * F + j];
+            for (int64_t e = 0; e < d; ++e) {
+                dW1[j * d + e] += dg * X[t * d + e];
+                dW3[j * d + e] += du * X[t * d + e];
+                dW2T[j * d + e] += a * dY[t * d + e];
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gated parameters (eq. "gate"): theta_k = m_k (.) theta.  For the neuron     */
+/* mask of Sec. 3.2 this zeroes row j of W1, W3 and column j of W2 (row j of   */
+/* W2T) for every neuron j with m_kj = 0.                                      */
+/* ------------------------------------------------------------------------- */
+void orc_gate_rows(int64_t F, int64_t d, const uint8_t* mask_k, const double* W, double* Wg) {
+    for (int64_t j = 0; j < F; ++j)
+        for (int64_t e = 0; e < d; ++e) Wg[j * d + e] = mask_k[j] ? W[j * d + e] : 0.0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* One worker's step under either masking regime (Sec. 3.1).                   */
+/*   mode 0, forward masking:  m_fwd = m_bwd = m.  Loss and gradient are       */
+/*     evaluated at the gated parameters; the gradient is then zero off-mask.  */
+/*   mode 1, backward masking: m_fwd = all ones, m_bwd = m.  Loss and dX come  */
+/*     from the full parameters; the weight gradient is kept on the mask only. */
+/* Outputs are full size: G,U[T][F], Y,dX[T][d], dW*[F][d].                    */
+/* Returns the number of off-mask weight-gradient entries that are not exactly */
+/* zero BEFORE any masking of the gradient (must be 0 in mode 0).              */
+/* ------------------------------------------------------------------------- */
+int64_t orc_worker_step(int mode, int64_t T, int64_t d, int64_t F, const uint8_t* mask_k,
+                        const double* X, const double* dY, const double* W1, const double* W3,
+                        const double* W2T, double* G, double* U, double* Y, double* dX,
+                        double* dW1, double* dW3, double* dW2T) {
+    size_t wn = (size_t)F * d, an = (size_t)T * F;
+    double* A = (double*)malloc(sizeof(double) * an);
+    double* dGb = (double*)malloc(sizeof(double) * an);
+    double* dUb = (double*)malloc(sizeof(double) * an);
+    int64_t nonzero_off_mask = 0;
+    if (mode == 0) {
+        double* W1g = (double*)malloc(sizeof(double) * wn);
+        double* W3g = (double*)malloc(sizeof(double) * wn);
+        double* W2g = (double*)malloc(sizeof(double) * wn);
+        orc_gate_rows(F, d, mask_k, W1, W1g);
+        orc_gate_rows(F, d, mask_k, W3, W3g);
+        orc_gate_rows(F, d, mask_k, W2T, W2g);
+        orc_mlp_fwd(T, d, F, X, W1g, W3g, W2g, G, U, A, Y);
+        orc_mlp_bwd(T, d, F, X, dY, W1g, W3g, W2g, G, U, A, dGb, dUb, dX, dW1, dW3, dW2T);
+        for (int64_t j = 0; j < F; ++j)
+            if (!mask_k[j])
+                for (int64_t e = 0; e < d; ++e)
+                    nonzero_off_mask += (dW1[j * d + e] != 0.0) + (dW3[j * d + e] != 0.0) +
+                                        (dW2T[j * d + e] != 0.0);
+        free(W1g);
+        free(W3g);
+        free(W2g);
+    } else {
+        orc_mlp_fwd(T, d, F, X, W1, W3, W2T, G, U, A, Y);
+        orc_mlp_bwd(T, d, F, X, dY, W1, W3, W2T, G, U, A, dGb, dUb, dX, dW1, dW3, dW2T);
+        for (int64_t j = 0; j < F; ++j)
+            if (!mask_k[j])
+                for (int64_t e = 0; e < d; ++e)
+                    dW1[j * d + e] = dW3[j * d + e] = dW2T[j * d + e] = 0.0;
+    }
+    free(A);
+    free(dGb);
+    free(dUb);
+    return nonzero_off_mask;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gated average (eq. "average") with the per-coordinate load:                 */
+/*   out_j = (1 / c_j) sum_{k : m_kj = 1} (g_k)_j,   c_j = sum_k m_kj,         */
+/* the mask being constant along a neuron row of D parameters.  Off-mask       */
+/* entries are not read (the mask selects, it does not multiply); c_j = 0      */
+/* gives out_j = 0.  Summation runs in worker order k = 0..K-1.                */
+/* gtype: 0 = fp32, 1 = bf16 bit patterns (uint16), 2 = fp64.                  */
+/* ------------------------------------------------------------------------- */
+static double widen(const void* base, int gtype, int64_t i) {
+    if (gtype == 0) return (double)((const float*)base)[i];
+    if (gtype == 2) return ((const double*)base)[i];
+    uint32_t bits = ((uint32_t)((const uint16_t*)base)[i]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+void orc_gated_average(int K, int64_t R, int64_t D, int gtype, const void* const* g,
+                       const uint8_t* mask, double* out, uint8_t* cov) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r) {
+        int c = 0;
+        for (int k = 0; k < K; ++k) c += mask[(int64_t)k * R + r] ? 1 : 0;
+        cov[r] = (uint8_t)c;
+        for (int64_t e = 0; e < D; ++e) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k)
+                if (mask[(int64_t)k * R + r]) s += widen(g[k], gtype, r * D + e);
+            out[r * D + e] = c ? s / (double)c : 0.0;
+        }
+    }
+}
+
+/* Squared Frobenius distance to uniform masking (Thm. 3.1) with per-column    */
+/* loads:  rho^2 = sum_{k,j} (1/K - m_kj / c_j)^2, columns with c_j = 0 give   */
+/* K (1/K)^2.                                                                  */
+double orc_rho2(int K, int64_t F, const uint8_t* mask) {
+    double acc = 0.0;
+    for (int64_t j = 0; j < F; ++j) {
+        int c = 0;
+        for (int k = 0; k < K; ++k) c += mask[(int64_t)k * F + j] ? 1 : 0;
+        for (int k = 0; k < K; ++k) {
+            double v = 1.0 / K - ((c && mask[(int64_t)k * F + j]) ? 1.0 / c : 0.0);
+            acc += v * v;
+        }
+    }
+    return acc;
+}
