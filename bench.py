@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the SDP masked-MLP hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of seeded synthetic input, everything resident
+in HBM: mask -> index compaction, then for each of the K simulated workers (run back to back on one
+stream) the masked SwiGLU MLP forward and backward writing its weight gradients into that worker's
+full-size bf16 gradient buffer, then the coverage-normalised average of the K buffers.
+
+Prints ONE JSON line.  `value` is active TFLOP/s (18 T d p per worker and step under forward
+masking; the dense work the method avoids is not counted).  `roofline` is for the kernel that takes
+most of the step; `grad_avg` reports the HBM-bound average alone at 1B-parameter scale;
+`cpu_baseline` is the fp64 oracle timed on this host on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s)
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak (published: 8 TB/s)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config2_bf16_fm_500M")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-grad-avg-1b", action="store_true", help="skip the 1B-parameter average measurement")
+    ap.add_argument("--avg-steps", type=int, default=20)
+    ap.add_argument("--events", type=int, default=1, help="1: per-kernel HIP events recorded during the timed steps")
+    return ap.parse_args()
+
+
+def flops_per_launch(name, w):
+    n = w.p if w.mode == "fm" else w.F
+    return {
+        "mlp_gate_up": 4 * w.T * w.d * n,
+        "mlp_down": 2 * w.T * w.d * n,
+        "mlp_dact": 2 * w.T * w.d * n,
+        "mlp_dx": 4 * w.T * w.d * n,
+        "mlp_dw": 2 * w.T * w.d * w.p,
+    }.get(name)
+
+
+def cpu_baseline(w):
+    """The oracle as it stands, timed on this host on a bounded token slice of worker 0's batch."""
+    import oracle
+    import workloads
+
+    rows = min(w.T, 512)
+    W = [workloads.to_f64(t) for t in workloads.mlp_weights(w)]
+    X, dY = workloads.mlp_batch(w, 0, rows=rows)
+    mask = oracle.make_masks(w.K, w.F, w.p, w.mask_seed, True)[0]
+    X, dY = workloads.to_f64(X), workloads.to_f64(dY)
+    t0 = time.perf_counter()
+    oracle.worker_step(w.mode, mask, X, dY, *W)
+    dt = time.perf_counter() - t0
+    flop = w.active_flop_per_worker * rows / w.T
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+        "sample": f"worker 0, first {rows} of {w.T} token rows, full d and F, fp64, {dt:.2f} s; active flops counted as for the GPU",
+    }
+
+
+def bench_grad_avg_1b(sdp, torch, steps):
+    import workloads
+
+    c = workloads.CONFIG5
+    mask_host = sdp.sample_masks_host(c.K, c.R, c.p, c.mask_seed, False)
+    mask = mask_host.cuda()
+    grads = workloads.grad_buffers(c.K, c.R, c.D, c.sigma, "bf16", device="cuda")
+    out = torch.empty((c.R, c.D), dtype=torch.float32, device="cuda")
+    cov = torch.empty((c.R,), dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        sdp.coverage_grad_avg(grads, mask, out=out, cov=cov)
+    torch.cuda.synchronize()
+    sdp.profile_reset()
+    sdp.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        sdp.coverage_grad_avg(grads, mask, out=out, cov=cov)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    prof = sdp.profile_read()
+    sdp.profile_enable(False)
+    calls, ms = prof["coverage_grad_avg"]
+    kern = ms / calls * 1e-3
+    gbs = c.algorithmic_bytes / kern / 1e9
+    return {
+        "workload": c.name, "K": c.K, "rows": c.R, "row_len": c.D, "covered_rows_per_worker": c.p,
+        "algorithmic_bytes": c.algorithmic_bytes, "ms_per_call": kern * 1e3, "ms_per_call_wall": wall * 1e3,
+        "value": gbs, "unit": "GB/s",
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                     "traffic": None},
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU only (K workers are simulated back to back on it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2507_09029_amd as sdp
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    sdp.lib()
+    torch.cuda.set_device(0)
+    w = workloads.MLP_CONFIGS[a.workload]
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    dev = "cuda"
+
+    # ---- resident inputs ----
+    Wd = [t.cuda() for t in workloads.mlp_weights(w)]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.BASE_SEED)
+    Xs = [torch.randn((w.T, w.d), generator=gen, device=dev, dtype=torch.float32).to(tdt) for _ in range(w.K)]
+    dYs = [torch.randn((w.T, w.d), generator=gen, device=dev, dtype=torch.float32).to(tdt) for _ in range(w.K)]
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.F, w.p, w.mask_seed, True)
+    row_mask = mask.repeat(1, 3).contiguous()
+    n = w.p if w.mode == "fm" else w.F
+    Y = torch.empty((w.T, w.d), dtype=tdt, device=dev)
+    G = torch.empty((w.T, n), dtype=tdt, device=dev)
+    U = torch.empty((w.T, n), dtype=tdt, device=dev)
+    dX = torch.empty((w.T, w.d), dtype=tdt, device=dev)
+    bufs = [torch.zeros((3 * w.F, w.d), dtype=tdt, device=dev) for _ in range(w.K)]
+    avg = torch.empty((3 * w.F, w.d), dtype=torch.float32, device=dev)
+    avg_cov = torch.empty((3 * w.F,), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(sdp.masked_mlp_fwd_workspace_bytes(w.mode, tdt, w.T, w.d, w.F, w.p), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(sdp.masked_mlp_bwd_workspace_bytes(w.mode, tdt, w.T, w.d, w.F, w.p), dtype=torch.uint8, device=dev)
+    ws_i = torch.empty(max(sdp.index_masks_workspace_bytes(w.K, w.F), 256), dtype=torch.uint8, device=dev)
+    idx2 = torch.empty_like(idx)
+    pos2 = torch.empty_like(pos)
+    cnt2 = torch.empty((w.K,), dtype=torch.int32, device=dev)
+    cov2 = torch.empty_like(cov)
+    L = sdp.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        st = L.sdp_index_masks(w.K, w.F, mask.data_ptr(), idx2.data_ptr(), w.p, pos2.data_ptr(), cnt2.data_ptr(),
+                               cov2.data_ptr(), ws_i.data_ptr(), ws_i.numel(), stream)
+        assert st == 0, st
+        for k in range(w.K):
+            b = bufs[k]
+            sdp.masked_mlp_fwd(w.mode, Xs[k], *Wd, idx2[k], out=(Y, G, U), ws=ws_f)
+            sdp.masked_mlp_bwd(w.mode, Xs[k], dYs[k], *Wd, idx2[k], G, U, dw_layout="scatter",
+                               out=(dX, b[: w.F], b[w.F: 2 * w.F], b[2 * w.F:]), ws=ws_b)
+        sdp.coverage_grad_avg(bufs, row_mask, out=avg, cov=avg_cov)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    sdp.profile_reset()
+    sdp.profile_enable(bool(a.events))
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = sdp.profile_read() if a.events else {}
+    sdp.profile_enable(False)
+
+    ms_per_step = elapsed / a.steps * 1e3
+    flop_step = w.K * w.active_flop_per_worker
+    value = flop_step / (ms_per_step * 1e-3) / 1e12
+
+    kernels = {}
+    for name, (calls, ms) in prof.items():
+        f = flops_per_launch(name, w)
+        avg_ms = ms / calls
+        kernels[name] = {"launches_per_step": calls / a.steps, "avg_ms": avg_ms, "share_of_step": ms / a.steps / ms_per_step}
+        if f:
+            kernels[name]["tflops"] = f / (avg_ms * 1e-3) / 1e12
+    roofline = None
+    gemm = {k: v for k, v in kernels.items() if "tflops" in v}
+    if gemm:
+        dom = max(gemm, key=lambda k: gemm[k]["share_of_step"])
+        ach = gemm[dom]["tflops"]
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_launch_ms": gemm[dom]["avg_ms"],
+                    "flop_per_launch": flops_per_launch(dom, w)}
+
+    rec = {
+        "metric": "masked-MLP fwd+bwd active TFLOP/s (% bf16 MFMA peak) + grad-avg GB/s (% HBM)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "mode": w.mode, "tokens": w.T, "d_model": w.d, "d_ff": w.F, "active_neurons": w.p,
+                   "workers_simulated": w.K, "active_flop_per_step": flop_step},
+        "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not a.no_grad_avg_1b:
+        del Xs, dYs, bufs, avg, ws_b, ws_f
+        torch.cuda.empty_cache()
+        rec["grad_avg"] = bench_grad_avg_1b(sdp, torch, a.avg_steps)
+    if not a.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

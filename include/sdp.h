@@ -1,0 +1,167 @@
+/*
+ * sdp.h -- C ABI of the Subnetwork-Data-Parallel (SDP) masked-MLP hot path for
+ * AMD MI355X (gfx950).
+ *
+ * SDP (the paper's Sec. 3) trains, on each of n = K workers, a structurally
+ * complete subnetwork chosen by a fixed binary mask matrix m in {0,1}^{K x F}
+ * (Sec. 3.1).  This library instantiates the neuron-level variant (Sec. 3.2)
+ * on a bias-free SwiGLU transformer MLP
+ *
+ *     G = X W1^T,  U = X W3^T,  A = silu(G) * U,  Y = A W2^T,   silu(z) = z / (1 + e^-z)
+ *
+ * where hidden neuron j owns row j of W1 and W3 and column j of W2.
+ *
+ * Conventions common to every entry point
+ *   - Layout: all matrices are dense row-major.  The three weights are stored
+ *     NEURON-MAJOR, [F][d] each: W1[j][:], W3[j][:] and W2T[j][:] (= column j of
+ *     W2) are the d parameters of neuron j.  Weight gradients use the same layout.
+ *   - Pointers are DEVICE pointers unless a parameter says "host".  The caller
+ *     owns all memory; the library keeps no pointer after a call returns and
+ *     allocates no device memory.  Scratch comes from the caller's workspace
+ *     `ws` (device, 256-byte aligned), at least the matching
+ *     *_workspace_bytes() large.
+ *   - Every call only enqueues work on `stream` (a hipStream_t, NULL = the
+ *     default stream) and returns; outputs are complete once the stream reaches
+ *     that point.  Outputs are fully overwritten, never accumulated into.
+ *   - dtype SDP_F32: all tensors fp32.  dtype SDP_BF16: all tensors bf16,
+ *     products accumulated in fp32, intermediates that feed a later
+ *     contraction rounded once to bf16 (round to nearest even).
+ *   - Errors: argument errors are found on the host before any launch and
+ *     returned as a negative sdp_status; nothing is enqueued in that case.
+ *     No call aborts or throws.
+ */
+#ifndef SDP_H
+#define SDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SDP_OK = 0,
+    SDP_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, unknown enum value, misaligned pointer */
+    SDP_ERR_SHAPE = -2,       /* sizes inconsistent with each other or beyond a stated limit          */
+    SDP_ERR_WORKSPACE = -3,   /* ws is NULL or ws_bytes too small                                      */
+    SDP_ERR_UNCOVERED = -4,   /* require_cover set but K * p < F: some neuron cannot be covered        */
+    SDP_ERR_UNSUPPORTED = -5, /* combination not implemented                                           */
+    SDP_ERR_HIP = -6          /* a HIP runtime call failed (launch, copy)                              */
+} sdp_status;
+
+typedef enum { SDP_F32 = 0, SDP_BF16 = 1 } sdp_dtype;
+typedef enum { SDP_MASK_FORWARD = 0, SDP_MASK_BACKWARD = 1 } sdp_mode;
+typedef enum { SDP_DW_COMPACT = 0, SDP_DW_SCATTER = 1 } sdp_dw_layout;
+
+#define SDP_MAX_WORKERS 64 /* largest K accepted anywhere */
+
+const char* sdp_status_string(int status);
+
+/* ---------------------------------------------------------------------------------------------
+ * Masks (Sec. 3.1: m_{k,j} = 1 iff worker k is responsible for coordinate j; App. A: exact row
+ * budget sum_j m_{k,j} = p, column loads c_j = sum_k m_{k,j}).
+ *
+ * sdp_make_masks draws the K x F mask matrix on the host from `seed`, copies it to the device and
+ * derives its index form there (see sdp_index_masks).  Sampler: worker k takes p distinct neurons
+ * uniformly (partial Fisher-Yates on the counter-based stream k); with require_cover != 0 every
+ * neuron left with load 0 is then given to a worker that hands back a neuron of load >= 2, so all
+ * row sums stay p and every c_j >= 1.  The draw is a pure function of (K, F, p, seed,
+ * require_cover).
+ *   mask  [K][F] u8 out     idx [K][p] i32 out     pos [K][F] i32 out     cov [F] u8 out
+ *   ws: sdp_index_masks_workspace_bytes(K, F).
+ * The call synchronises `stream` before returning (the host staging buffer is freed).
+ * Errors: INVALID_ARG (null, K < 1, K > SDP_MAX_WORKERS, F < 1, p < 0), SHAPE (p > F),
+ * UNCOVERED (require_cover and K p < F), WORKSPACE, HIP.
+ * ------------------------------------------------------------------------------------------- */
+int sdp_make_masks(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask, int32_t* idx,
+                   int32_t* pos, uint8_t* cov, void* ws, size_t ws_bytes, void* stream);
+
+/* Host-only variant of the sampler: fills mask_host[K][F]; no device work. */
+int sdp_sample_masks_host(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask_host);
+
+/* ---------------------------------------------------------------------------------------------
+ * Mask -> index compaction (prefix sum over each worker's mask row) and coverage counts.
+ *   mask  [K][F] u8 in, any non-zero byte counts as 1
+ *   idx   [K][idx_ld] i32 out: idx[k][i] = i-th active neuron of worker k, ascending; entries
+ *         from count[k] on are -1; active neurons of rank >= idx_ld are dropped
+ *   pos   [K][F] i32 out: rank of neuron j in worker k's active set, or -1 if m_{k,j} = 0
+ *   count [K] i32 out (may be NULL): row sums
+ *   cov   [F] u8 out: c_j, the number of workers covering neuron j, which is the count of
+ *         every parameter in neuron row j
+ * Limits: 1 <= K <= SDP_MAX_WORKERS, 1 <= F < 2^31, 1 <= idx_ld <= F.
+ * ------------------------------------------------------------------------------------------- */
+size_t sdp_index_masks_workspace_bytes(int K, int64_t F);
+int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t idx_ld, int32_t* pos,
+                    int32_t* count, uint8_t* cov, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * One worker's MLP forward under either regime of Sec. 3.1.
+ *   SDP_MASK_FORWARD  (m_fwd = m): the block is evaluated at the gated parameters, i.e. as the
+ *     smaller dense MLP made of the worker's p active neurons idx_k[0..p) (Sec. 3.2):
+ *     G = X W1[S]^T, U = X W3[S]^T [T][p];  Y = (silu(G) * U) W2T[S]  [T][d].
+ *   SDP_MASK_BACKWARD (m_fwd = all ones): the dense block over all F neurons; idx_k is ignored
+ *     and p is ignored; G, U are [T][F].
+ *   X [T][d] in;  W1, W3, W2T [F][d] in;  idx_k [p] i32 in (strictly ascending, in [0, F))
+ *   Y [T][d] out; G_save, U_save [T][n] out with n = p (forward) or F (backward): pre-activations
+ *   kept for sdp_masked_mlp_bwd.
+ *   ws: sdp_masked_mlp_fwd_workspace_bytes(mode, dtype, T, d, F, p).
+ * Limits: d, F, p multiples of 8 for SDP_BF16 (16-byte rows); pointers 16-byte aligned.
+ * The index values are trusted (they come from sdp_index_masks); an index outside [0, F) is
+ * undefined behaviour.
+ * ------------------------------------------------------------------------------------------- */
+size_t sdp_masked_mlp_fwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p);
+int sdp_masked_mlp_fwd(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* W1,
+                       const void* W3, const void* W2T, const int32_t* idx_k, void* Y, void* G_save,
+                       void* U_save, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * One worker's MLP backward for upstream gradient dY = dL/dY (Sec. 3.1).
+ *   SDP_MASK_FORWARD : gradients of the compact network: dX [T][d] through the p active neurons;
+ *     dW1, dW3, dW2T for the active neurons only (all others are exactly zero by Sec. 3.1 and are
+ *     not materialised).
+ *   SDP_MASK_BACKWARD: dX through the full block (all F neurons); the weight gradient is
+ *     computed ONLY on the worker's mask (m_bwd = m): rows idx_k of the dense dW1, dW3, dW2T.
+ *   G_save, U_save: what sdp_masked_mlp_fwd stored for the same mode and shapes.
+ *   dw_layout SDP_DW_COMPACT: dW1, dW3, dW2T are [p][d], row i belongs to neuron idx_k[i].
+ *   dw_layout SDP_DW_SCATTER: they are full [F][d] buffers; row idx_k[i] is written, rows off the
+ *     mask are left untouched (sdp_coverage_grad_avg never reads them).
+ *   ws: sdp_masked_mlp_bwd_workspace_bytes(mode, dtype, T, d, F, p).
+ * Limits as for the forward call, and additionally T a multiple of 8 for SDP_BF16.
+ * ------------------------------------------------------------------------------------------- */
+size_t sdp_masked_mlp_bwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p);
+int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* dY,
+                       const void* W1, const void* W3, const void* W2T, const int32_t* idx_k,
+                       const void* G_save, const void* U_save, void* dX, void* dW1, void* dW3, void* dW2T,
+                       int dw_layout, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Gated average of K workers' gradients (Sec. 3.1, eq. "average"), normalised per coordinate by
+ * the number of workers that cover it:
+ *     out[r][e] = (1 / c_r) * sum_{k : mask[k][r] != 0} g_k[r][e],   c_r = sum_k mask[k][r],
+ * the mask being constant along a neuron row of D parameters.  The mask SELECTS: rows a worker
+ * does not cover are never read (they may hold anything).  c_r = 0 gives out = 0.  The sum is
+ * taken in fp32 in worker order k = 0..K-1, then divided once; the result does not depend on
+ * launch geometry.
+ *   g     HOST array of K DEVICE pointers, each [R][D] of gdtype (SDP_F32 or SDP_BF16)
+ *   mask  [K][R] u8 in;   out [R][D] fp32 out;   cov [R] u8 out (may be NULL)
+ * Limits: 1 <= K <= SDP_MAX_WORKERS, R >= 0, D >= 1; buffers 16-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+int sdp_coverage_grad_avg(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
+                          float* out, uint8_t* cov, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Per-kernel timing.  With profiling on, every kernel launch is bracketed by HIP events on its
+ * stream.  sdp_profile_read synchronises those events and returns, for up to `cap` distinct
+ * kernel names, the launch count and total milliseconds since the last reset.
+ *   names  host array of cap pointers, set to static strings owned by the library
+ *   calls, ms host arrays of cap entries.   Returns the number of entries filled, or < 0.
+ * ------------------------------------------------------------------------------------------- */
+int sdp_profile_enable(int on);
+int sdp_profile_reset(void);
+int sdp_profile_read(int cap, const char** names, int64_t* calls, double* ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDP_H */

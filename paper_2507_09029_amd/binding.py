@@ -1,0 +1,235 @@
+"""ctypes binding of the C ABI in include/sdp.h.
+
+Argument marshalling only: every function here checks tensor dtypes / devices, passes raw device
+pointers and torch's current HIP stream to the library call of the same name and raises SdpError on
+a negative status.  PyTorch supplies device memory and streams; no step of the path runs in torch.
+There is no fallback: if libsdp_hip.so is missing or fails to load, importing `lib()` raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsdp_hip.so")
+
+F32, BF16 = 0, 1
+MASK_FORWARD, MASK_BACKWARD = 0, 1
+DW_COMPACT, DW_SCATTER = 0, 1
+MAX_WORKERS = 64
+
+_MODES = {"fm": MASK_FORWARD, "bm": MASK_BACKWARD, MASK_FORWARD: MASK_FORWARD, MASK_BACKWARD: MASK_BACKWARD}
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
+
+
+class SdpError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {lib().sdp_status_string(status).decode()} ({status})")
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Loads libsdp_hip.so (building it first if it is absent and hipcc is available)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+
+        _build.build_library()
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_size_t
+    L.sdp_status_string.restype = ctypes.c_char_p
+    L.sdp_status_string.argtypes = [i32]
+    L.sdp_make_masks.restype = i32
+    L.sdp_make_masks.argtypes = [i32, i32, i32, u64, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.sdp_sample_masks_host.restype = i32
+    L.sdp_sample_masks_host.argtypes = [i32, i32, i32, u64, i32, vp]
+    L.sdp_index_masks_workspace_bytes.restype = sz
+    L.sdp_index_masks_workspace_bytes.argtypes = [i32, i64]
+    L.sdp_index_masks.restype = i32
+    L.sdp_index_masks.argtypes = [i32, i64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.sdp_masked_mlp_fwd_workspace_bytes.restype = sz
+    L.sdp_masked_mlp_fwd_workspace_bytes.argtypes = [i32] * 6
+    L.sdp_masked_mlp_bwd_workspace_bytes.restype = sz
+    L.sdp_masked_mlp_bwd_workspace_bytes.argtypes = [i32] * 6
+    L.sdp_masked_mlp_fwd.restype = i32
+    L.sdp_masked_mlp_fwd.argtypes = [i32] * 6 + [vp] * 9 + [sz, vp]
+    L.sdp_masked_mlp_bwd.restype = i32
+    L.sdp_masked_mlp_bwd.argtypes = [i32] * 6 + [vp] * 12 + [i32, vp, sz, vp]
+    L.sdp_coverage_grad_avg.restype = i32
+    L.sdp_coverage_grad_avg.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp]
+    L.sdp_profile_enable.restype = i32
+    L.sdp_profile_enable.argtypes = [i32]
+    L.sdp_profile_reset.restype = i32
+    L.sdp_profile_reset.argtypes = []
+    L.sdp_profile_read.restype = i32
+    L.sdp_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    _lib = L
+    return L
+
+
+def _check(status, what):
+    if status < 0:
+        raise SdpError(status, what)
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def sample_masks_host(K, F, p, seed, require_cover=True):
+    """The library's host sampler alone: uint8 [K][F] CPU tensor."""
+    mask = torch.zeros((K, F), dtype=torch.uint8)
+    _check(lib().sdp_sample_masks_host(K, F, p, seed, int(bool(require_cover)), mask.data_ptr()), "sdp_sample_masks_host")
+    return mask
+
+
+def index_masks_workspace_bytes(K, F):
+    return int(lib().sdp_index_masks_workspace_bytes(K, F))
+
+
+def make_masks(K, F, p, seed, require_cover=True, device="cuda"):
+    """-> (mask u8 [K][F], idx i32 [K][p], pos i32 [K][F], cov u8 [F]) on the GPU."""
+    mask = torch.empty((K, F), dtype=torch.uint8, device=device)
+    idx = torch.empty((K, max(p, 0)), dtype=torch.int32, device=device)
+    pos = torch.empty((K, F), dtype=torch.int32, device=device)
+    cov = torch.empty((F,), dtype=torch.uint8, device=device)
+    ws = _ws(index_masks_workspace_bytes(K, F), device)
+    st = lib().sdp_make_masks(K, F, p, seed, int(bool(require_cover)), mask.data_ptr(), idx.data_ptr(), pos.data_ptr(),
+                              cov.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_make_masks")
+    return mask, idx, pos, cov
+
+
+def index_masks(mask, idx_ld=None, ws=None):
+    """mask u8 [K][F] (GPU) -> (idx i32 [K][idx_ld], pos i32 [K][F], count i32 [K], cov u8 [F])."""
+    mptr = _dev(mask, torch.uint8, "mask")
+    K, F = mask.shape
+    if idx_ld is None:
+        idx_ld = F
+    idx = torch.empty((K, idx_ld), dtype=torch.int32, device=mask.device)
+    pos = torch.empty((K, F), dtype=torch.int32, device=mask.device)
+    count = torch.empty((K,), dtype=torch.int32, device=mask.device)
+    cov = torch.empty((F,), dtype=torch.uint8, device=mask.device)
+    if ws is None:
+        ws = _ws(index_masks_workspace_bytes(K, F), mask.device)
+    st = lib().sdp_index_masks(K, F, mptr, idx.data_ptr(), idx_ld, pos.data_ptr(), count.data_ptr(), cov.data_ptr(),
+                               ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_index_masks")
+    return idx, pos, count, cov
+
+
+def masked_mlp_fwd_workspace_bytes(mode, dtype, T, d, F, p):
+    return int(lib().sdp_masked_mlp_fwd_workspace_bytes(_MODES[mode], _DTYPES[dtype], T, d, F, p))
+
+
+def masked_mlp_bwd_workspace_bytes(mode, dtype, T, d, F, p):
+    return int(lib().sdp_masked_mlp_bwd_workspace_bytes(_MODES[mode], _DTYPES[dtype], T, d, F, p))
+
+
+def masked_mlp_fwd(mode, X, W1, W3, W2T, idx_k, out=None, ws=None):
+    """One worker's forward. Returns (Y [T][d], G_save, U_save [T][n]); n = p ('fm') or F ('bm')."""
+    m = _MODES[mode]
+    dt = X.dtype
+    T, d = X.shape
+    F = W1.shape[0]
+    p = int(idx_k.numel()) if idx_k is not None else F
+    n = p if m == MASK_FORWARD else F
+    for name, w in (("W1", W1), ("W3", W3), ("W2T", W2T)):
+        if tuple(w.shape) != (F, d):
+            raise ValueError(f"{name}: expected shape {(F, d)}")
+    if out is None:
+        out = (torch.empty((T, d), dtype=dt, device=X.device), torch.empty((T, n), dtype=dt, device=X.device),
+               torch.empty((T, n), dtype=dt, device=X.device))
+    Y, G, U = out
+    if ws is None:
+        ws = _ws(masked_mlp_fwd_workspace_bytes(m, dt, T, d, F, p), X.device)
+    st = lib().sdp_masked_mlp_fwd(
+        m, _DTYPES[dt], T, d, F, p, _dev(X, dt, "X"), _dev(W1, dt, "W1"), _dev(W3, dt, "W3"), _dev(W2T, dt, "W2T"),
+        _dev(idx_k, torch.int32, "idx_k") if idx_k is not None else None, _dev(Y, dt, "Y"), _dev(G, dt, "G_save"),
+        _dev(U, dt, "U_save"), ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_masked_mlp_fwd")
+    return Y, G, U
+
+
+def masked_mlp_bwd(mode, X, dY, W1, W3, W2T, idx_k, G_save, U_save, dw_layout="compact", out=None, ws=None):
+    """One worker's backward. Returns (dX [T][d], dW1, dW3, dW2T); [p][d] compact or [F][d] scattered."""
+    m = _MODES[mode]
+    dt = X.dtype
+    T, d = X.shape
+    F = W1.shape[0]
+    p = int(idx_k.numel())
+    lay = {"compact": DW_COMPACT, "scatter": DW_SCATTER}[dw_layout]
+    if out is None:
+        rows = p if lay == DW_COMPACT else F
+        out = (torch.empty((T, d), dtype=dt, device=X.device),) + tuple(
+            torch.empty((rows, d), dtype=dt, device=X.device) for _ in range(3))
+    dX, dW1, dW3, dW2T = out
+    if ws is None:
+        ws = _ws(masked_mlp_bwd_workspace_bytes(m, dt, T, d, F, p), X.device)
+    st = lib().sdp_masked_mlp_bwd(
+        m, _DTYPES[dt], T, d, F, p, _dev(X, dt, "X"), _dev(dY, dt, "dY"), _dev(W1, dt, "W1"), _dev(W3, dt, "W3"),
+        _dev(W2T, dt, "W2T"), _dev(idx_k, torch.int32, "idx_k"), _dev(G_save, dt, "G_save"), _dev(U_save, dt, "U_save"),
+        _dev(dX, dt, "dX"), _dev(dW1, dt, "dW1"), _dev(dW3, dt, "dW3"), _dev(dW2T, dt, "dW2T"), lay,
+        ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_masked_mlp_bwd")
+    return dX, dW1, dW3, dW2T
+
+
+def coverage_grad_avg(grads, mask, out=None, cov=None):
+    """grads: K GPU tensors [R][D] (fp32 or bf16); mask u8 [K][R] -> (out fp32 [R][D], cov u8 [R])."""
+    K = len(grads)
+    if K < 1 or K > MAX_WORKERS:
+        raise SdpError(-1, "sdp_coverage_grad_avg")
+    dt = grads[0].dtype
+    R, D = grads[0].shape
+    ptrs = (ctypes.c_void_p * K)(*[_dev(g, dt, f"grads[{i}]") for i, g in enumerate(grads)])
+    for g in grads:
+        if tuple(g.shape) != (R, D):
+            raise ValueError("all gradient buffers must share one shape")
+    if tuple(mask.shape) != (K, R):
+        raise ValueError("mask must be [K][R]")
+    if out is None:
+        out = torch.empty((R, D), dtype=torch.float32, device=grads[0].device)
+    if cov is None:
+        cov = torch.empty((R,), dtype=torch.uint8, device=grads[0].device)
+    st = lib().sdp_coverage_grad_avg(K, R, D, _DTYPES[dt], ptrs, _dev(mask, torch.uint8, "mask"),
+                                     _dev(out, torch.float32, "out"), _dev(cov, torch.uint8, "cov"), _stream())
+    _check(st, "sdp_coverage_grad_avg")
+    return out, cov
+
+
+def profile_enable(on=True):
+    _check(lib().sdp_profile_enable(int(bool(on))), "sdp_profile_enable")
+
+
+def profile_reset():
+    _check(lib().sdp_profile_reset(), "sdp_profile_reset")
+
+
+def profile_read(cap=64):
+    """-> {kernel name: (launches, total ms)} since the last reset (waits for the recorded events)."""
+    names = (ctypes.c_char_p * cap)()
+    calls = (ctypes.c_int64 * cap)()
+    ms = (ctypes.c_double * cap)()
+    n = lib().sdp_profile_read(cap, names, calls, ms)
+    _check(n, "sdp_profile_read")
+    return {names[i].decode(): (int(calls[i]), float(ms[i])) for i in range(n)}

@@ -1,0 +1,84 @@
+// Internal declarations shared by the translation units of libsdp_hip.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sdp.h"
+
+namespace sdp {
+
+// ---- per-kernel event timing (sdp_profile_*) -------------------------------------------------
+bool profiling_on();
+void profile_begin(const char* name, hipStream_t s);
+void profile_end(hipStream_t s);
+
+struct ProfileScope {
+    hipStream_t s;
+    bool on;
+    ProfileScope(const char* name, hipStream_t stream) : s(stream), on(profiling_on()) {
+        if (on) profile_begin(name, s);
+    }
+    ~ProfileScope() {
+        if (on) profile_end(s);
+    }
+};
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? SDP_OK : SDP_ERR_HIP; }
+inline int launch_status() { return hip_status(hipGetLastError()); }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- contraction descriptor --------------------------------------------------------------------
+// C[M][N] = sum_k A(m,k) * B(k,n), fp32 accumulation.
+//   A(m,k) = A[ra(m) * lda + k]                          (rows contiguous along k)
+//   B(k,n) = b_kn ? B[rb(k) * ldb + n] : B[rb(n) * ldb + k]
+// ra / rb are the identity when the gather pointer is null, else a lookup in an int32 table.
+// A second operand pair (A2, B2) with the same shapes, strides and gathers is used by two of the
+// epilogues below.
+enum Epilogue {
+    EPI_STORE = 0,       // C[rc(m) * ldc + n] = acc                      (rc: optional row scatter)
+    EPI_DUAL_ACC = 1,    // as STORE with acc = A.B + A2.B2
+    EPI_SWIGLU_FWD = 2,  // g = A.B, u = A.B2: G = g, U = u, Act = silu(g) * u, all [M][N] (ld = ldc)
+    EPI_SWIGLU_BWD = 3   // da = A.B; with g = Gin[m][n], u = Uin[m][n]:
+                         //   dU = da silu(g), dG = da u silu'(g), act = silu(g) u
+                         //   written row-major [M][N] (dG, dU; ld = ldc) and transposed [N][M]
+                         //   (dGT, dUT, ActT; ld = ldt)
+};
+
+struct GemmDesc {
+    int M = 0, N = 0, K = 0;
+    const void* A = nullptr;
+    const void* A2 = nullptr;
+    int64_t lda = 0;
+    const int32_t* a_gather = nullptr;
+    const void* B = nullptr;
+    const void* B2 = nullptr;
+    int64_t ldb = 0;
+    const int32_t* b_gather = nullptr;
+    int b_kn = 0;
+    int epilogue = EPI_STORE;
+    // outputs
+    void* C = nullptr;  // STORE / DUAL_ACC: C.  SWIGLU_FWD: G.  SWIGLU_BWD: dG
+    void* C2 = nullptr; // SWIGLU_FWD: U.  SWIGLU_BWD: dU
+    void* C3 = nullptr; // SWIGLU_FWD: Act
+    int64_t ldc = 0;
+    const int32_t* c_scatter = nullptr;
+    // SWIGLU_BWD extra
+    const void* Gin = nullptr;
+    const void* Uin = nullptr;
+    int64_t ldg = 0;
+    void* T1 = nullptr; // dGT
+    void* T2 = nullptr; // dUT
+    void* T3 = nullptr; // ActT
+    int64_t ldt = 0;
+    const char* name = "gemm";
+};
+
+// Plain LDS-tiled FMA contraction, any shape; element type float or bf16 (dtype as sdp_dtype).
+int gemm_simple(int dtype, const GemmDesc& g, hipStream_t s);
+// bf16 MFMA contraction; returns SDP_ERR_UNSUPPORTED when the shape / alignment does not fit.
+int gemm_mfma_bf16(const GemmDesc& g, hipStream_t s);
+bool gemm_mfma_supported(const GemmDesc& g);
+
+} // namespace sdp

@@ -1,0 +1,258 @@
+// Mask sampling (host) and mask -> index compaction + coverage counts (gfx950 kernels).
+//
+// Mask matrix m in {0,1}^{K x F}: Sec. 3.1 of the paper; exact row budget p and column loads c_j:
+// App. A.  The index form (ascending gather indices, ranks, per-neuron coverage) is what lets a
+// forward-masked worker run as the physically smaller dense network of Sec. 3.2.
+#include <vector>
+
+#include "sdp_internal.h"
+
+namespace {
+
+// ---- counter-based generator: draw c of stream s is finalise(finalise(seed + g (s+1)) + g (c+1)),
+// finalise = SplitMix64's output function.
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+
+inline uint64_t finalise(uint64_t z) {
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+class Stream {
+  public:
+    Stream(uint64_t seed, uint64_t id) : key_(finalise(seed + kGamma * (id + 1))), n_(0) {}
+    uint64_t next() {
+        ++n_;
+        return finalise(key_ + kGamma * n_);
+    }
+    // unbiased integer in [0, bound): raw draws under 2^64 mod bound are thrown away
+    uint64_t below(uint64_t bound) {
+        const uint64_t tail = (~bound + 1) % bound;
+        uint64_t x;
+        do {
+            x = next();
+        } while (x < tail);
+        return x % bound;
+    }
+
+  private:
+    uint64_t key_, n_;
+};
+
+int sample_masks(int K, int F, int p, uint64_t seed, bool cover, uint8_t* m) {
+    std::fill(m, m + (size_t)K * F, (uint8_t)0);
+    std::vector<int32_t> order(F);
+    for (int k = 0; k < K; ++k) {
+        Stream rng(seed, (uint64_t)k);
+        for (int j = 0; j < F; ++j) order[j] = j;
+        uint8_t* row = m + (size_t)k * F;
+        for (int i = 0; i < p; ++i) {
+            const int pick = i + (int)rng.below((uint64_t)(F - i));
+            std::swap(order[i], order[pick]);
+            row[order[i]] = 1;
+        }
+    }
+    if (!cover) return SDP_OK;
+
+    std::vector<int32_t> c(F, 0);
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < F; ++j) c[j] += m[(size_t)k * F + j];
+    Stream rng(seed, (uint64_t)K);
+    std::vector<int32_t> cand;
+    cand.reserve(F);
+    for (int j = 0; j < F; ++j) {
+        if (c[j] > 0) continue;
+        const int k0 = (int)rng.below((uint64_t)K);
+        for (int step = 0; step < K; ++step) {
+            uint8_t* row = m + (size_t)((k0 + step) % K) * F;
+            cand.clear();
+            for (int q = 0; q < F; ++q)
+                if (row[q] && c[q] > 1) cand.push_back(q);
+            if (cand.empty()) continue;
+            const int give = cand[rng.below((uint64_t)cand.size())];
+            row[give] = 0;
+            --c[give];
+            row[j] = 1;
+            c[j] = 1;
+            break;
+        }
+    }
+    return SDP_OK;
+}
+
+// ---- device side ---------------------------------------------------------------------------
+constexpr int kScanThreads = 256;
+constexpr int kPerThread = 8;
+constexpr int kChunk = kScanThreads * kPerThread; // mask bytes per workgroup
+
+__device__ inline int block_exclusive_scan(int v, int* total, int* lds /*[kScanThreads/64 + 1]*/) {
+    // inclusive scan inside the wave by shuffles, then across the (at most 4) waves through LDS
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) lds[wave] = inc;
+    __syncthreads();
+    int base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / 64; ++w) {
+        int t = lds[w];
+        if (w < wave) base += t;
+        sum += t;
+    }
+    __syncthreads();
+    *total = sum;
+    return base + inc - v;
+}
+
+// grid (chunks, K): number of non-zero mask bytes in each chunk of each worker's row
+__global__ __launch_bounds__(kScanThreads) void chunk_count_kernel(const uint8_t* __restrict__ mask, int64_t F,
+                                                                   int nchunks, int32_t* __restrict__ chunk_cnt) {
+    __shared__ int lds[kScanThreads / 64 + 1];
+    const int k = blockIdx.y, c = blockIdx.x;
+    const int64_t j0 = (int64_t)c * kChunk + (int64_t)threadIdx.x * kPerThread;
+    const uint8_t* row = mask + (int64_t)k * F;
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+        if (j0 + i < F) n += row[j0 + i] != 0;
+    int total;
+    block_exclusive_scan(n, &total, lds);
+    if (threadIdx.x == 0) chunk_cnt[(int64_t)k * nchunks + c] = total;
+}
+
+// grid (chunks, K): ranks inside the chunk + sum of the preceding chunks' counts -> idx, pos, count
+__global__ __launch_bounds__(kScanThreads) void compact_kernel(const uint8_t* __restrict__ mask, int64_t F,
+                                                               int nchunks, const int32_t* __restrict__ chunk_cnt,
+                                                               int32_t* __restrict__ idx, int64_t idx_ld,
+                                                               int32_t* __restrict__ pos, int32_t* __restrict__ count) {
+    __shared__ int lds[kScanThreads / 64 + 1];
+    const int k = blockIdx.y, c = blockIdx.x;
+    const int32_t* cnt = chunk_cnt + (int64_t)k * nchunks;
+    // every workgroup needs (a) the count of all chunks before its own, (b) the row total
+    int before = 0, all = 0;
+    for (int i = threadIdx.x; i < nchunks; i += kScanThreads) {
+        int t = cnt[i];
+        all += t;
+        if (i < c) before += t;
+    }
+    int row_total, base;
+    block_exclusive_scan(all, &row_total, lds);
+    block_exclusive_scan(before, &base, lds);
+
+    const int64_t j0 = (int64_t)c * kChunk + (int64_t)threadIdx.x * kPerThread;
+    const uint8_t* row = mask + (int64_t)k * F;
+    uint8_t bits[kPerThread];
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        bits[i] = (j0 + i < F) ? (row[j0 + i] != 0) : 0;
+        n += bits[i];
+    }
+    int dummy;
+    int rank = base + block_exclusive_scan(n, &dummy, lds);
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        if (j0 + i >= F) break;
+        if (bits[i]) {
+            pos[(int64_t)k * F + j0 + i] = rank;
+            if (rank < idx_ld) idx[(int64_t)k * idx_ld + rank] = (int32_t)(j0 + i);
+            ++rank;
+        } else {
+            pos[(int64_t)k * F + j0 + i] = -1;
+        }
+    }
+    // the tail of the idx row (entries row_total .. idx_ld) is -1; chunk c fills its own slice of it
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int64_t t = j0 + i;
+        if (t < idx_ld && t >= row_total) idx[(int64_t)k * idx_ld + t] = -1;
+    }
+    if (c == 0 && threadIdx.x == 0 && count) count[k] = row_total;
+}
+
+// coverage c_j = sum_k [m_kj != 0]
+__global__ __launch_bounds__(256) void coverage_kernel(const uint8_t* __restrict__ mask, int K, int64_t F,
+                                                       uint8_t* __restrict__ cov) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= F) return;
+    int c = 0;
+    for (int k = 0; k < K; ++k) c += mask[(int64_t)k * F + j] != 0;
+    cov[j] = (uint8_t)c;
+}
+
+int check_index_args(int K, int64_t F, const void* mask, const void* idx, int64_t idx_ld, const void* pos,
+                     const void* cov, const void* ws, size_t ws_bytes) {
+    if (!mask || !idx || !pos || !cov) return SDP_ERR_INVALID_ARG;
+    if (K < 1 || K > SDP_MAX_WORKERS || F < 1) return SDP_ERR_INVALID_ARG;
+    if (F >= ((int64_t)1 << 31) || idx_ld < 1 || idx_ld > F) return SDP_ERR_SHAPE;
+    if (!ws || ws_bytes < sdp_index_masks_workspace_bytes(K, F)) return SDP_ERR_WORKSPACE;
+    return SDP_OK;
+}
+
+} // namespace
+
+extern "C" size_t sdp_index_masks_workspace_bytes(int K, int64_t F) {
+    if (K < 1 || F < 1) return 0;
+    const int64_t nchunks = (F + kChunk - 1) / kChunk;
+    return sdp::round_up((size_t)K * (size_t)nchunks * sizeof(int32_t), 256);
+}
+
+extern "C" int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t idx_ld, int32_t* pos,
+                               int32_t* count, uint8_t* cov, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_index_args(K, F, mask, idx, idx_ld, pos, cov, ws, ws_bytes);
+    if (rc != SDP_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const int nchunks = (int)((F + kChunk - 1) / kChunk);
+    int32_t* chunk_cnt = (int32_t*)ws;
+    {
+        sdp::ProfileScope ps("mask_chunk_count", s);
+        chunk_count_kernel<<<dim3(nchunks, K), kScanThreads, 0, s>>>(mask, F, nchunks, chunk_cnt);
+    }
+    {
+        sdp::ProfileScope ps("mask_compact", s);
+        compact_kernel<<<dim3(nchunks, K), kScanThreads, 0, s>>>(mask, F, nchunks, chunk_cnt, idx, idx_ld, pos, count);
+    }
+    {
+        sdp::ProfileScope ps("mask_coverage", s);
+        coverage_kernel<<<dim3((unsigned)((F + 255) / 256)), 256, 0, s>>>(mask, K, F, cov);
+    }
+    return sdp::launch_status();
+}
+
+extern "C" int sdp_sample_masks_host(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask_host) {
+    if (!mask_host || K < 1 || K > SDP_MAX_WORKERS || F < 1 || p < 0) return SDP_ERR_INVALID_ARG;
+    if (p > F) return SDP_ERR_SHAPE;
+    if (require_cover && (int64_t)K * p < F) return SDP_ERR_UNCOVERED;
+    return sample_masks(K, F, p, seed, require_cover != 0, mask_host);
+}
+
+extern "C" int sdp_make_masks(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask, int32_t* idx,
+                              int32_t* pos, uint8_t* cov, void* ws, size_t ws_bytes, void* stream) {
+    if (!mask || !idx || !pos || !cov) return SDP_ERR_INVALID_ARG;
+    if (K < 1 || K > SDP_MAX_WORKERS || F < 1 || p < 0) return SDP_ERR_INVALID_ARG;
+    if (p > F) return SDP_ERR_SHAPE;
+    if (require_cover && (int64_t)K * p < F) return SDP_ERR_UNCOVERED;
+    if (!ws || ws_bytes < sdp_index_masks_workspace_bytes(K, F)) return SDP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<uint8_t> host((size_t)K * F);
+    int rc = sample_masks(K, F, p, seed, require_cover != 0, host.data());
+    if (rc != SDP_OK) return rc;
+    if (hipMemcpyAsync(mask, host.data(), host.size(), hipMemcpyHostToDevice, s) != hipSuccess) return SDP_ERR_HIP;
+    if (p > 0) {
+        rc = sdp_index_masks(K, F, mask, idx, p, pos, nullptr, cov, ws, ws_bytes, stream);
+    } else {
+        // empty budget: no idx entries exist; pos is all -1 and cov all 0
+        if (hipMemsetAsync(pos, 0xFF, (size_t)K * F * sizeof(int32_t), s) != hipSuccess) return SDP_ERR_HIP;
+        if (hipMemsetAsync(cov, 0, (size_t)F, s) != hipSuccess) return SDP_ERR_HIP;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return SDP_ERR_HIP;
+    return rc;
+}

@@ -1,0 +1,147 @@
+// One worker's masked SwiGLU MLP forward and backward (the paper's Sec. 3.1 regimes applied to the
+// neuron-level masks of Sec. 3.2), expressed as a fixed sequence of contractions.
+//
+// With n = p and gather = idx_k under forward masking, n = F and no gather under backward masking:
+//   forward   gate_up : [G | U] = X . [W1 | W3][S]^T        (T x n, depth d)  + SwiGLU epilogue -> Act
+//             down    : Y  = Act . W2T[S]                    (T x d, depth n)
+//   backward  dact    : dA = dY . W2T[S]^T                   (T x n, depth d)  + SwiGLU-backward epilogue
+//                        -> dG, dU (row-major) and dG^T, dU^T, Act^T (neuron-major)
+//             dx      : dX = dG . W1[S] + dU . W3[S]         (T x d, depth 2n)
+//             dw1/3/2 : dW1[S] = dG^T . X, dW3[S] = dU^T . X, dW2T[S] = Act^T . dY   (p x d, depth T)
+// Under backward masking the three weight-gradient contractions read only rows idx_k of the
+// neuron-major dG^T, dU^T, Act^T: the gradient is computed on the worker's mask and nowhere else.
+#include "sdp_internal.h"
+
+namespace {
+
+using namespace sdp;
+
+size_t esize(int dtype) { return dtype == SDP_F32 ? 4 : 2; }
+
+int check_common(int mode, int dtype, int T, int d, int F, int p) {
+    if (mode != SDP_MASK_FORWARD && mode != SDP_MASK_BACKWARD) return SDP_ERR_INVALID_ARG;
+    if (dtype != SDP_F32 && dtype != SDP_BF16) return SDP_ERR_INVALID_ARG;
+    if (T < 1 || d < 1 || F < 1) return SDP_ERR_INVALID_ARG;
+    if (p < 1 || p > F) return SDP_ERR_SHAPE;
+    if ((int64_t)T * F >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
+    if (dtype == SDP_BF16 && (d % 8 || F % 8 || p % 8)) return SDP_ERR_SHAPE;
+    return SDP_OK;
+}
+
+int run(int dtype, const GemmDesc& g, hipStream_t s) {
+    if (dtype == SDP_BF16 && gemm_mfma_supported(g)) return gemm_mfma_bf16(g, s);
+    return gemm_simple(dtype, g, s);
+}
+
+} // namespace
+
+extern "C" size_t sdp_masked_mlp_fwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p) {
+    if (check_common(mode, dtype, T, d, F, mode == SDP_MASK_BACKWARD ? F : p) != SDP_OK) return 0;
+    const size_t n = mode == SDP_MASK_FORWARD ? p : F;
+    return round_up((size_t)T * n * esize(dtype), 256);
+}
+
+extern "C" size_t sdp_masked_mlp_bwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p) {
+    if (check_common(mode, dtype, T, d, F, p) != SDP_OK) return 0;
+    const size_t n = mode == SDP_MASK_FORWARD ? p : F;
+    return 5 * round_up((size_t)T * n * esize(dtype), 256);
+}
+
+extern "C" int sdp_masked_mlp_fwd(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* W1,
+                                  const void* W3, const void* W2T, const int32_t* idx_k, void* Y, void* G_save,
+                                  void* U_save, void* ws, size_t ws_bytes, void* stream) {
+    if (mode == SDP_MASK_BACKWARD) p = F;
+    int rc = check_common(mode, dtype, T, d, F, p);
+    if (rc != SDP_OK) return rc;
+    if (!X || !W1 || !W3 || !W2T || !Y || !G_save || !U_save) return SDP_ERR_INVALID_ARG;
+    if (mode == SDP_MASK_FORWARD && !idx_k) return SDP_ERR_INVALID_ARG;
+    for (const void* q : {X, W1, W3, W2T, (const void*)Y, (const void*)G_save, (const void*)U_save})
+        if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_mlp_fwd_workspace_bytes(mode, dtype, T, d, F, p))
+        return SDP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int n = mode == SDP_MASK_FORWARD ? p : F;
+    const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
+
+    GemmDesc gu;
+    gu.name = "mlp_gate_up";
+    gu.M = T, gu.N = n, gu.K = d;
+    gu.A = X, gu.lda = d;
+    gu.B = W1, gu.B2 = W3, gu.ldb = d, gu.b_gather = gather, gu.b_kn = 0;
+    gu.epilogue = EPI_SWIGLU_FWD;
+    gu.C = G_save, gu.C2 = U_save, gu.C3 = ws, gu.ldc = n;
+    rc = run(dtype, gu, s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc dn;
+    dn.name = "mlp_down";
+    dn.M = T, dn.N = d, dn.K = n;
+    dn.A = ws, dn.lda = n;
+    dn.B = W2T, dn.ldb = d, dn.b_gather = gather, dn.b_kn = 1;
+    dn.epilogue = EPI_STORE;
+    dn.C = Y, dn.ldc = d;
+    return run(dtype, dn, s);
+}
+
+extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* dY,
+                                  const void* W1, const void* W3, const void* W2T, const int32_t* idx_k,
+                                  const void* G_save, const void* U_save, void* dX, void* dW1, void* dW3, void* dW2T,
+                                  int dw_layout, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_common(mode, dtype, T, d, F, p);
+    if (rc != SDP_OK) return rc;
+    if (dtype == SDP_BF16 && T % 8) return SDP_ERR_SHAPE;
+    if (dw_layout != SDP_DW_COMPACT && dw_layout != SDP_DW_SCATTER) return SDP_ERR_INVALID_ARG;
+    if (!X || !dY || !W1 || !W3 || !W2T || !idx_k || !G_save || !U_save || !dX || !dW1 || !dW3 || !dW2T)
+        return SDP_ERR_INVALID_ARG;
+    for (const void* q : {X, dY, W1, W3, W2T, G_save, U_save, (const void*)dX, (const void*)dW1, (const void*)dW3,
+                          (const void*)dW2T})
+        if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_mlp_bwd_workspace_bytes(mode, dtype, T, d, F, p))
+        return SDP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int n = mode == SDP_MASK_FORWARD ? p : F;
+    const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
+    const size_t part = round_up((size_t)T * n * esize(dtype), 256);
+    char* w = (char*)ws;
+    void *dG = w, *dU = w + part, *dGT = w + 2 * part, *dUT = w + 3 * part, *ActT = w + 4 * part;
+
+    GemmDesc da;
+    da.name = "mlp_dact";
+    da.M = T, da.N = n, da.K = d;
+    da.A = dY, da.lda = d;
+    da.B = W2T, da.ldb = d, da.b_gather = gather, da.b_kn = 0;
+    da.epilogue = EPI_SWIGLU_BWD;
+    da.Gin = G_save, da.Uin = U_save, da.ldg = n;
+    da.C = dG, da.C2 = dU, da.ldc = n;
+    da.T1 = dGT, da.T2 = dUT, da.T3 = ActT, da.ldt = T;
+    rc = run(dtype, da, s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc dx;
+    dx.name = "mlp_dx";
+    dx.M = T, dx.N = d, dx.K = n;
+    dx.A = dG, dx.A2 = dU, dx.lda = n;
+    dx.B = W1, dx.B2 = W3, dx.ldb = d, dx.b_gather = gather, dx.b_kn = 1;
+    dx.epilogue = EPI_DUAL_ACC;
+    dx.C = dX, dx.ldc = d;
+    rc = run(dtype, dx, s);
+    if (rc != SDP_OK) return rc;
+
+    const void* lhs[3] = {dGT, dUT, ActT};
+    const void* rhs[3] = {X, X, dY};
+    void* outp[3] = {dW1, dW3, dW2T};
+    for (int i = 0; i < 3; ++i) {
+        GemmDesc dw;
+        dw.name = "mlp_dw";
+        dw.M = p, dw.N = d, dw.K = T;
+        dw.A = lhs[i], dw.lda = T;
+        dw.a_gather = mode == SDP_MASK_BACKWARD ? idx_k : nullptr; // rows of the neuron-major operand on the mask
+        dw.B = rhs[i], dw.ldb = d, dw.b_kn = 1;
+        dw.epilogue = EPI_STORE;
+        dw.C = outp[i], dw.ldc = d;
+        dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
+        rc = run(dtype, dw, s);
+        if (rc != SDP_OK) return rc;
+    }
+    return SDP_OK;
+}

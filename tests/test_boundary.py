@@ -1,0 +1,113 @@
+"""Host-only checks of the C-ABI library: it loads, exports everything include/sdp.h declares,
+rejects bad arguments before launching anything, and its host mask sampler matches the oracle's
+independent implementation of the same sampler bit for bit."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2507_09029_amd as sdp
+from paper_2507_09029_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)  # non-null, 16-byte aligned, never dereferenced: errors precede any launch
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sdp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sdp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sdp.lib()
+    names = declared_functions()
+    assert {"sdp_make_masks", "sdp_masked_mlp_fwd", "sdp_masked_mlp_bwd", "sdp_coverage_grad_avg"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    L = sdp.lib()
+    seen = {L.sdp_status_string(s) for s in range(0, -7, -1)}
+    assert len(seen) == 7 and L.sdp_status_string(-99) == b"unknown status"
+
+
+def test_workspace_queries():
+    assert sdp.index_masks_workspace_bytes(4, 1024) >= 4 * 1 * 4
+    assert sdp.index_masks_workspace_bytes(8, 488282) >= 8 * 239 * 4
+    assert sdp.index_masks_workspace_bytes(0, 10) == 0
+    import torch
+    fw = sdp.masked_mlp_fwd_workspace_bytes("fm", torch.bfloat16, 8192, 1536, 4096, 2048)
+    assert fw >= 8192 * 2048 * 2
+    bw = sdp.masked_mlp_bwd_workspace_bytes("bm", torch.bfloat16, 16384, 2048, 5504, 4128)
+    assert bw >= 5 * 16384 * 5504 * 2
+    assert sdp.masked_mlp_fwd_workspace_bytes("fm", torch.bfloat16, 8, 12, 16, 8) == 0  # d not a multiple of 8
+    assert sdp.masked_mlp_fwd_workspace_bytes("fm", torch.float32, 8, 12, 16, 7) > 0
+
+
+def test_argument_errors_are_caught_on_the_host():
+    L = sdp.lib()
+    big = ctypes.c_size_t(1 << 40)
+    # make_masks
+    assert L.sdp_make_masks(4, 16, 8, 1, 1, None, FAKE, FAKE, FAKE, FAKE, big, None) == -1
+    assert L.sdp_make_masks(0, 16, 8, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == -1
+    assert L.sdp_make_masks(65, 16, 8, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == -1
+    assert L.sdp_make_masks(4, 16, 17, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == -2
+    assert L.sdp_make_masks(2, 16, 7, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == -4
+    assert L.sdp_make_masks(4, 16, 8, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_size_t(0), None) == -3
+    assert L.sdp_make_masks(4, 16, 8, 1, 1, FAKE, FAKE, FAKE, FAKE, None, big, None) == -3
+    # index_masks
+    assert L.sdp_index_masks(4, 16, FAKE, FAKE, 17, FAKE, None, FAKE, FAKE, big, None) == -2
+    assert L.sdp_index_masks(4, 16, FAKE, FAKE, 0, FAKE, None, FAKE, FAKE, big, None) == -2
+    assert L.sdp_index_masks(4, 16, None, FAKE, 8, FAKE, None, FAKE, FAKE, big, None) == -1
+    assert L.sdp_index_masks(4, 16, FAKE, FAKE, 8, FAKE, None, FAKE, FAKE, ctypes.c_size_t(8), None) == -3
+    # forward
+    def fwd(mode=0, dt=1, T=16, d=16, F=32, p=16, X=FAKE, idx=FAKE, ws=FAKE, wsb=big):
+        return L.sdp_masked_mlp_fwd(mode, dt, T, d, F, p, X, FAKE, FAKE, FAKE, idx, FAKE, FAKE, FAKE, ws, wsb, None)
+    assert fwd(mode=2) == -1 and fwd(dt=5) == -1 and fwd(T=0) == -1 and fwd(X=None) == -1
+    assert fwd(p=40) == -2 and fwd(p=0) == -2 and fwd(d=12) == -2 and fwd(p=12) == -2
+    assert fwd(idx=None) == -1 and fwd(ws=None) == -3 and fwd(wsb=ctypes.c_size_t(16)) == -3
+    assert fwd(X=ctypes.c_void_p(0x1004)) == -1  # misaligned
+    # backward
+    def bwd(mode=0, dt=1, T=16, d=16, F=32, p=16, dY=FAKE, lay=0, ws=FAKE, wsb=big):
+        return L.sdp_masked_mlp_bwd(mode, dt, T, d, F, p, FAKE, dY, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                    FAKE, lay, ws, wsb, None)
+    assert bwd(mode=-1) == -1 and bwd(dY=None) == -1 and bwd(lay=2) == -1
+    assert bwd(T=12) == -2 and bwd(p=33) == -2 and bwd(wsb=ctypes.c_size_t(1024)) == -3
+    # average
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    assert L.sdp_coverage_grad_avg(0, 4, 8, 1, ptrs, FAKE, FAKE, FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, 4, 0, 1, ptrs, FAKE, FAKE, FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, 4, 8, 7, ptrs, FAKE, FAKE, FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, 4, 8, 1, None, FAKE, FAKE, FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, -1, 8, 1, ptrs, FAKE, FAKE, FAKE, None) == -1
+    bad = (ctypes.c_void_p * 2)(0x1000, 0)
+    assert L.sdp_coverage_grad_avg(2, 4, 8, 1, bad, FAKE, FAKE, FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, 4, 8, 1, ptrs, None, FAKE, FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, 4, 8, 1, ptrs, FAKE, ctypes.c_void_p(0x1008), FAKE, None) == -1
+    assert L.sdp_coverage_grad_avg(2, 0, 8, 1, ptrs, FAKE, FAKE, FAKE, None) == 0  # empty input: nothing to do
+
+
+def test_binding_raises_sdp_error():
+    with pytest.raises(sdp.SdpError) as e:
+        sdp.sample_masks_host(2, 16, 7, 1, True)
+    assert e.value.status == -4
+
+
+@pytest.mark.parametrize("K,F,p,cover", [
+    (4, 1024, 512, True), (4, 4096, 2048, True), (8, 5504, 4128, True), (8, 5504, 4128, False),
+    (3, 7, 3, True), (2, 10, 5, True), (1, 5, 5, True), (8, 64, 8, True), (5, 33, 1, False), (8, 20000, 13800, False),
+])
+def test_host_sampler_matches_oracle_bit_for_bit(orc, K, F, p, cover):
+    for seed in (20250709, 1, 2**63 + 12345):
+        got = sdp.sample_masks_host(K, F, p, seed, cover).numpy()
+        want = orc.make_masks(K, F, p, seed, cover)
+        assert (got == want).all()
+
+
+def test_binding_module_does_not_touch_the_oracle():
+    src = open(binding.__file__).read() + open(os.path.join(os.path.dirname(binding.__file__), "__init__.py")).read()
+    assert "oracle" not in src

@@ -1,0 +1,71 @@
+"""GPU parity of the coverage-normalised gradient average against the oracle (fp64)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import assert_close
+
+pytestmark = pytest.mark.gpu
+
+TOL_SUM = 1e-5  # fp32 sum of at most 64 terms and one division, against fp64
+
+
+@pytest.fixture(scope="module")
+def sdp():
+    import paper_2507_09029_amd as m
+
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _np_inputs(grads):
+    if grads[0].dtype == torch.bfloat16:
+        return [workloads.bf16_bits(g) for g in grads]
+    return [g.cpu().numpy() for g in grads]
+
+
+@pytest.mark.parametrize("K,R,D,p,dtype", [
+    (4, 300, 256, 150, "bf16"), (8, 1000, 2048, 690, "bf16"), (8, 257, 1536, 100, "f32"), (3, 50, 520, 20, "bf16"),
+    (2, 64, 8, 32, "f32"), (5, 40, 7, 20, "bf16"), (5, 40, 13, 20, "f32"), (1, 10, 512, 4, "bf16"), (64, 33, 1024, 3, "bf16"),
+    (8, 3072, 256, 1536, "f32"),
+])
+def test_avg_matches_oracle_with_poisoned_off_mask_rows(sdp, orc, K, R, D, p, dtype):
+    print(f"avg K={K} R={R} D={D} p={p} {dtype}", flush=True)
+    mask = orc.make_masks(K, R, p, 77, False)
+    tmask = torch.from_numpy(mask)
+    grads = workloads.grad_buffers(K, R, D, 1e-3, dtype, poison_mask=tmask)
+    dev = [g.cuda() for g in grads]
+    out, cov = sdp.coverage_grad_avg(dev, tmask.cuda())
+    torch.cuda.synchronize()
+    want, wcov = orc.gated_average(_np_inputs(grads), mask)
+    assert (cov.cpu().numpy() == wcov).all()                       # counts: bit exact
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()                                  # NaN in uncovered rows was never read
+    assert (got[wcov == 0] == 0.0).all()                           # nobody covers the row: 0, not NaN
+    assert_close(got, want, TOL_SUM, "avg")
+    # the clean run gives the same bits
+    clean = workloads.grad_buffers(K, R, D, 1e-3, dtype)
+    out2, _ = sdp.coverage_grad_avg([g.cuda() for g in clean], tmask.cuda())
+    assert torch.equal(out2, out)
+
+
+def test_avg_full_coverage_is_the_mean_and_single_worker_is_identity(sdp):
+    K, R, D = 8, 100, 1024
+    grads = [g.cuda() for g in workloads.grad_buffers(K, R, D, 1.0, "f32")]
+    ones = torch.ones((K, R), dtype=torch.uint8, device="cuda")
+    out, cov = sdp.coverage_grad_avg(grads, ones)
+    ref = torch.stack([g.double() for g in grads]).mean(0)
+    assert (cov == K).all()
+    assert_close(out.cpu().numpy(), ref.cpu().numpy(), TOL_SUM, "mean")
+    out1, cov1 = sdp.coverage_grad_avg(grads[:1], ones[:1].contiguous())
+    assert torch.equal(out1, grads[0]) and (cov1 == 1).all()
+
+
+def test_avg_empty_input_and_binding_errors(sdp):
+    g = [torch.empty((0, 64), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    out, cov = sdp.coverage_grad_avg(g, torch.empty((2, 0), dtype=torch.uint8, device="cuda"))
+    assert out.shape == (0, 64) and cov.shape == (0,)
+    with pytest.raises(sdp.SdpError):
+        sdp.coverage_grad_avg([], torch.empty((0, 0), dtype=torch.uint8, device="cuda"))
