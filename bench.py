@@ -53,7 +53,7 @@ def cpu_baseline(w):
     import oracle
     import workloads
 
-    rows = min(w.T, 512)
+    rows = min(w.T, 8192)
     W = [workloads.to_f64(t) for t in workloads.mlp_weights(w)]
     X, dY = workloads.mlp_batch(w, 0, rows=rows)
     mask = oracle.make_masks(w.K, w.F, w.p, w.mask_seed, True)[0]
