@@ -1,0 +1,115 @@
+"""GPU parity at the full benchmark sizes (configs 2-5), on sampled outputs.
+
+The oracle cannot compute 1e12-1e13 fp64 flop in a test, but every output element it is asked for
+it computes exactly as at small size:
+  - a token row of Y, dX, G, U depends only on that row of X, dY: the oracle runs the whole
+    worker step on a sample of rows (first / last rows of the first and last tiles included);
+  - the weight-gradient rows of neuron j depend only on neuron j's weights (and all tokens): the
+    oracle runs the dense block restricted to a sample of the worker's active neurons over all T
+    tokens (first / last active neurons and the ragged last tile included).
+The launch configuration is the one bench.py times (same entry points, same layouts).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import assert_close
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def sdp():
+    import paper_2507_09029_amd as m
+
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _sample(n, count, rng, always):
+    pick = set(int(x) for x in always if 0 <= x < n)
+    pick.update(int(x) for x in rng.choice(n, size=min(count, n), replace=False))
+    return np.array(sorted(pick))
+
+
+def _fullsize_worker(sdp, orc, w, k, Wd, W64, idx, want_mask, dw_layout):
+    rng = np.random.default_rng(1000 + k)
+    X, dY = workloads.mlp_batch(w, k)
+    Xd, dYd = X.cuda(), dY.cuda()
+    Y, G, U = sdp.masked_mlp_fwd(w.mode, Xd, *Wd, idx[k])
+    dX, dW1, dW3, dW2T = sdp.masked_mlp_bwd(w.mode, Xd, dYd, *Wd, idx[k], G, U, dw_layout=dw_layout)
+    torch.cuda.synchronize()
+    S = np.flatnonzero(want_mask[k])
+
+    # token-row sample: tile edges (tiles of 128 / 256 rows), the very last rows, random rows
+    rows = _sample(w.T, 160, rng, [0, 1, 127, 128, 255, 256, w.T - 257, w.T - 256, w.T - 129, w.T - 128, w.T - 2, w.T - 1])
+    X64, dY64 = workloads.to_f64(X), workloads.to_f64(dY)
+    ref = orc.worker_step(w.mode, want_mask[k], X64[rows], dY64[rows], *W64)
+    cols = S if w.mode == "fm" else np.arange(w.F)
+    trows = torch.from_numpy(rows).cuda()
+    assert_close(workloads.to_f64(Y[trows]), ref["Y"], TOL_BF16, f"{w.name} Y[{k}]")
+    assert_close(workloads.to_f64(dX[trows]), ref["dX"], TOL_BF16, f"{w.name} dX[{k}]")
+    assert_close(workloads.to_f64(G[trows]), ref["G"][:, cols], TOL_BF16, f"{w.name} G[{k}]")
+    assert_close(workloads.to_f64(U[trows]), ref["U"][:, cols], TOL_BF16, f"{w.name} U[{k}]")
+
+    # neuron sample among the worker's active neurons, by rank: tile edges and the ragged tail
+    p = len(S)
+    ranks = _sample(p, 48, rng, [0, 1, 31, 32, 127, 128, 255, 256, p - 130, p - 129, p - 33, p - 32, p - 2, p - 1])
+    neurons = S[ranks]
+    f = orc.mlp_fwd(X64, W64[0][neurons], W64[1][neurons], W64[2][neurons])
+    b = orc.mlp_bwd(X64, dY64, W64[0][neurons], W64[1][neurons], W64[2][neurons], f["G"], f["U"], f["A"])
+    sel = torch.from_numpy(neurons if dw_layout == "scatter" else ranks).cuda()
+    for name, got in (("dW1", dW1), ("dW3", dW3), ("dW2T", dW2T)):
+        assert_close(workloads.to_f64(got[sel]), b[name], TOL_BF16, f"{w.name} {name}[{k}]")
+    del Y, G, U, dX, dW1, dW3, dW2T, Xd, dYd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("w,workers,layout", [
+    (workloads.CONFIG2, [0, 3], "compact"),
+    (workloads.CONFIG3, [0, 7], "scatter"),
+    (workloads.CONFIG4, [1], "compact"),
+], ids=["config2", "config3", "config4"])
+def test_fullsize_mlp_sampled(sdp, orc, w, workers, layout):
+    W = workloads.mlp_weights(w)
+    Wd = [t.cuda() for t in W]
+    W64 = [workloads.to_f64(t) for t in W]
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.F, w.p, w.mask_seed, True)
+    want_mask = orc.make_masks(w.K, w.F, w.p, w.mask_seed, True)
+    assert (mask.cpu().numpy() == want_mask).all()
+    widx, wpos, wcount, wcov = orc.index_masks(want_mask, idx_ld=w.p)
+    assert (idx.cpu().numpy() == widx).all() and (cov.cpu().numpy() == wcov).all()
+    for k in workers:
+        print(f"  {w.name}: worker {k}, layout {layout}", flush=True)
+        _fullsize_worker(sdp, orc, w, k, Wd, W64, idx, want_mask, layout)
+
+
+def test_fullsize_config5_average_sampled(sdp, orc):
+    c = workloads.CONFIG5
+    print(f"  {c.name}: K={c.K} R={c.R} D={c.D} p={c.p}", flush=True)
+    want_mask = orc.make_masks(c.K, c.R, c.p, c.mask_seed, False)
+    mask = sdp.sample_masks_host(c.K, c.R, c.p, c.mask_seed, False)
+    assert (mask.numpy() == want_mask).all()
+    dmask = mask.cuda()
+    # off-mask rows hold NaN: a correct average never reads them
+    grads = workloads.grad_buffers(c.K, c.R, c.D, c.sigma, "bf16", device="cuda", poison_mask=dmask)
+    out, cov = sdp.coverage_grad_avg(grads, dmask)
+    torch.cuda.synchronize()
+    _, _, wcount, wcov = orc.index_masks(want_mask, idx_ld=1)
+    assert (wcount == c.p).all()
+    assert (cov.cpu().numpy() == wcov).all()                       # every count, bit exact
+    assert bool(torch.isfinite(out).all())                         # at full size: nothing off-mask was read
+    uncovered = np.flatnonzero(wcov == 0)
+    assert len(uncovered) > 0                                      # the workload does exercise c = 0
+    assert bool((out[torch.from_numpy(uncovered).cuda()] == 0).all())
+    rng = np.random.default_rng(5)
+    rows = _sample(c.R, 1500, rng, list(uncovered[:50]) + [0, 1, 2, 3, 4, c.R - 4, c.R - 3, c.R - 2, c.R - 1])
+    trows = torch.from_numpy(rows).cuda()
+    sub = [workloads.bf16_bits(g[trows]) for g in grads]
+    want, wc = orc.gated_average(sub, want_mask[:, rows])
+    assert (wc == wcov[rows]).all()
+    assert_close(out[trows].cpu().numpy(), want, 1e-5, "config5 average (sampled rows)")
