@@ -2,40 +2,58 @@
 //
 //   C[M][N] = sum_k A(m,k) B(k,n),  bf16 operands, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
 //
-// Workgroup: 256 threads = 4 waves (2 x 2), output tile 128 x 128, depth step 64.  Each wave owns a
-// 64 x 64 sub-tile = 2 x 2 MFMA tiles of 32 x 32 (64 accumulator registers per lane).
-// Global -> registers -> LDS, two LDS stages, one barrier per depth step; the loads of step t+1 are
-// issued before the MFMAs of step t.
+// Tile: BM x BN outputs per workgroup, depth step 64, WAVES_M x WAVES_N waves of 64 lanes, each wave
+// owning (BM/WAVES_M) x (BN/WAVES_N) outputs as 32 x 32 MFMA tiles.  The flagship shape is
+// 256 x 256 with 8 waves (2 x 4): 128 accumulator registers per lane, two waves per SIMD.
 //
-// Operand tiles in LDS are stored in 16-byte chunks (8 bf16) exactly as they arrive from HBM:
-//   "row tile"  [128 rows][64 k]   : A always; B when it is stored [N][K].  A lane's MFMA operand is
-//                one chunk -> one ds_read_b128.  Chunk (r, c) sits at r*8 + (c ^ ((r >> 1) & 7)).
-//   "k tile"    [64 k][128 cols]   : B when it is stored [K][N] (the gathered-row weights of the
-//                down / dX contractions, X and dY of the weight-gradient contractions).  The MFMA
-//                operand needs 8 consecutive k of one column, i.e. a transpose: two
-//                ds_read_b64_tr_b16 per fragment.  Chunk (k, c) sits at k*16 + (c ^ ((k & 3) << 2)).
-// Both XOR patterns make the per-cycle lane groups of the reads hit distinct banks.
+// HBM/L2 -> LDS: direct loads (global_load_lds_dwordx4).  One wave instruction moves 64 chunks of
+// 16 bytes (8 bf16) into 1 KB of consecutive LDS; which global chunk a lane fetches is free, so the
+// LDS layout below is produced by choosing the global address per lane.  No registers, no
+// ds_write instructions are spent on staging.  Two LDS stages; per depth step: wait for this wave's
+// loads of the step, one barrier, issue the next step's loads, run the MFMAs.
 //
-// Row gathers (active-neuron indices) are applied when forming global addresses: a gathered row
-// is still one contiguous run of K (or N) elements, so every global access stays a 16-byte load.
+// LDS layouts (positions in 16-byte chunks):
+//   "row tile"  [R rows][64 k]      : A always; B when stored [N][K].  Chunk (r, c) sits at
+//                r*8 + (c ^ ((r >> 1) & 7)).  A lane's MFMA operand (8 consecutive k of one row)
+//                is one chunk: one ds_read_b128.
+//   "k tile"    [64 k][BN cols]     : B when stored [K][N] (gathered weight rows of the down / dX
+//                contractions, X and dY of the weight-gradient contractions).  Chunk (k, c) sits at
+//                k*(BN/8) + (c + 4 (k & 3)) mod (BN/8).  The MFMA operand needs 8 consecutive k
+//                of one column, i.e. a transpose: two ds_read_b64_tr_b16 per fragment.
+// Both patterns spread the lanes served in one LDS cycle over distinct banks.
+//
+// Row gathers (active-neuron indices) are applied when forming global addresses: a gathered row is
+// one contiguous run of K (or N) elements, so every global access stays a 16-byte chunk.
+//
+// Workgroup -> tile mapping is XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs
+// (each with its own L2), so ids are first regrouped per XCD and each XCD then walks a compact
+// block of tiles (GROUP_M tile-rows at a time) whose operand tiles are shared through that L2.
+//
+// Batching: the three weight-gradient contractions of one worker (same M x N x K, different operands)
+// run as one launch of 3 x tiles workgroups, so that their few, deep tiles fill the CUs together.
 #include "sdp_internal.h"
 #include "sdp_swiglu.h"
+
+#include <cstdlib>
+#include <type_traits>
 
 namespace sdp {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* glb_void_ptr;
 
-constexpr int BM = 128, BN = 128, BK = 64, NTHREADS = 256;
-constexpr int A_TILE_BYTES = BM * BK * 2;          // 16 KB
-constexpr int B_TILE_BYTES = BN * BK * 2;          // 16 KB
-constexpr int STAGE_BYTES = A_TILE_BYTES + B_TILE_BYTES;
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;         // 64 KB: two workgroups per CU
+constexpr int BK = 64;
+constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;
 
 struct Dev {
     int M, N, K;
@@ -48,183 +66,262 @@ struct Dev {
     int64_t ldg;
     uint16_t *T1, *T2, *T3;
     int64_t ldt;
-    int tiles_m, tiles_n;
+    int tiles_m, tiles_n, ntiles;
+    // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
+    const uint16_t *Ab[3], *Bb[3];
+    uint16_t* Cb[3];
 };
-
-__device__ inline u32x4 ldg16(const uint16_t* p) { return *(const u32x4*)p; }
-
-__device__ inline int row_chunk(int r, int c) { return r * 8 + (c ^ ((r >> 1) & 7)); }
-__device__ inline int k_chunk(int k, int c) { return k * 16 + (c ^ ((k & 3) << 2)); }
 
 __device__ inline uint32_t pack_bf16(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
-// B_KN: 0 = B stored [N][K] (row tile), 1 = B stored [K][N] (k tile).
-template <int B_KN, int EPI>
-__global__ __launch_bounds__(NTHREADS, 2) void gemm_mfma_kernel(Dev g) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+// s_waitcnt vmcnt(n) alone (expcnt / lgkmcnt left at their maxima), gfx9 encoding
+#define SDP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int B_KN, int EPI, int OP>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev g) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 32, FN = WN / 32;
     constexpr bool kFwd = EPI == EPI_SWIGLU_FWD;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+    constexpr int SA = (BM / 8) / NW;          // A slabs (1 KB) per wave per step
+    constexpr int SB = (BN / 8) / NW;          // B slabs per wave per step (both layouts: BN*64*2/1024 = BN/8)
+    constexpr int BCH = BN / 8;                // chunks per k-tile row
+    static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "slabs must divide among the waves");
+    static_assert(!kFwd || FN % 2 == 0, "gate/up fragments come in pairs");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    const int tile_n = blockIdx.x % g.tiles_n, tile_m = blockIdx.x / g.tiles_n;
-    const int m0 = tile_m * BM;
-    // SWIGLU_FWD: the 128 tile columns are 64 neurons x {gate, up}
-    const int n0 = kFwd ? tile_n * (BN / 2) : tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: keeps everything derived from it scalar
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int l32 = lane & 31, lhi = lane >> 5;
 
-    // ---- per-thread global load coordinates (fixed over the depth loop where possible) ----
-    // row tile: 1024 chunks, thread -> rows tid/8 + 32 i, chunk tid%8
-    const int lr = tid >> 3, lc = tid & 7;
-    const uint16_t* a_row[4];
-    const uint16_t* a2_row[4];
-    const uint16_t* b_row[4];  // B_KN == 0 only
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int m = m0 + lr + 32 * i;
-        m = m < g.M ? m : g.M - 1;
-        const int64_t row = g.ag ? g.ag[m] : m;
-        a_row[i] = g.A + row * g.lda + lc * 8;
-        a2_row[i] = EPI == EPI_DUAL_ACC ? g.A2 + row * g.lda + lc * 8 : nullptr;
-        if (!B_KN) {
-            const int r = lr + 32 * i; // tile row 0..127
-            int n;
-            const uint16_t* base = g.B;
-            if (kFwd) {
-                n = n0 + (r & 63);
-                if (r >= 64) base = g.B2;
-            } else {
-                n = n0 + r;
-            }
-            n = n < g.N ? n : g.N - 1;
-            const int64_t brow = g.bg ? g.bg[n] : n;
-            b_row[i] = base + brow * g.ldb + lc * 8;
-        }
+    // ---- workgroup -> (problem of the batch, tile), XCD-aware ----
+    int bid = blockIdx.x;
+    const int batch = bid / g.ntiles;
+    bid -= batch * g.ntiles;
+    const uint16_t* gA = g.A;
+    const uint16_t* gB = g.B;
+    uint16_t* gC = g.C;
+    if (OP == OP_DW) {
+        gA = batch == 0 ? g.Ab[0] : (batch == 1 ? g.Ab[1] : g.Ab[2]);
+        gB = batch == 0 ? g.Bb[0] : (batch == 1 ? g.Bb[1] : g.Bb[2]);
+        gC = batch == 0 ? g.Cb[0] : (batch == 1 ? g.Cb[1] : g.Cb[2]);
     }
-    // k tile: 1024 chunks, thread -> k rows tid/16 + 16 i, chunk tid%16
-    const int kr = tid >> 4, kc = tid & 15;
-    const bool kcol_ok = B_KN ? (n0 + kc * 8 < g.N) : true;
+    {
+        // ids congruent mod 8 share an XCD: give XCD x the contiguous range [start_x, start_x + count_x)
+        const int x = bid % NUM_XCD, j = bid / NUM_XCD;
+        const int base = g.ntiles / NUM_XCD, rem = g.ntiles % NUM_XCD;
+        bid = x * base + (x < rem ? x : rem) + j;
+    }
+    int tile_m, tile_n;
+    {
+        const int per_group = GROUP_M * g.tiles_n;
+        const int grp = bid / per_group;
+        const int first_m = grp * GROUP_M;
+        const int gm = g.tiles_m - first_m < GROUP_M ? g.tiles_m - first_m : GROUP_M;
+        const int in = bid - grp * per_group;
+        tile_m = first_m + in % gm;
+        tile_n = in / gm;
+    }
+    const int m0 = tile_m * BM;
+    const int n0 = kFwd ? tile_n * (BN / 2) : tile_n * BN; // SWIGLU_FWD: BN columns = BN/2 neurons x {gate, up}
 
+    // ---- depth steps: nfull whole steps, then at most one partial step (K % 64 in {16, 32, 48}) ----
+    const int nfull = g.K / BK;
     const int nk1 = (g.K + BK - 1) / BK;
     const int nk = EPI == EPI_DUAL_ACC ? 2 * nk1 : nk1;
 
-    u32x4 ra[4], rb[4];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    // ---- per-lane global source of every slab this wave fills: byte offsets from a uniform base.
+    // Row and column indices beyond the matrix are clamped to the last valid one: such lanes fetch
+    // valid memory whose products only reach outputs that are never stored.
+    // row tile, slab s: rows 8s .. 8s+7; lane -> row 8s + lane/8, stored position lane%8
+    uint32_t a_off[SA];
+#pragma unroll
+    for (int i = 0; i < SA; ++i) {
+        const int r = 8 * (wave + NW * i) + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        int m = m0 + r;
+        m = m < g.M ? m : g.M - 1;
+        const int64_t row = g.ag ? g.ag[m] : m;
+        a_off[i] = (uint32_t)((row * g.lda + c * 8) * 2);
+    }
+    uint32_t b_off[SB]; // B_KN == 0: row offset + chunk; B_KN == 1: column chunk offset (row added per step)
+    int b_k[SB];        // B_KN == 1: k row inside the tile
+#pragma unroll
+    for (int i = 0; i < SB; ++i) {
+        if (!B_KN) {
+            const int r = 8 * (wave + NW * i) + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
+            int n = kFwd ? n0 + (r % (BN / 2)) : n0 + r;
+            n = n < g.N ? n : g.N - 1;
+            const int64_t row = g.bg ? g.bg[n] : n;
+            b_off[i] = (uint32_t)((row * g.ldb + c * 8) * 2);
+            b_k[i] = 0;
+        } else {
+            const int q = 64 * (wave + NW * i) + lane; // chunk slot inside the k tile
+            const int k = q / BCH, pos = q % BCH;
+            b_k[i] = k;
+            int col = n0 + ((pos + BCH - 4 * (k & 3)) % BCH) * 8; // inverse of the stored rotation
+            col = col < g.N ? col : g.N - 8;
+            b_off[i] = (uint32_t)(col * 2);
+        }
+    }
 
-    auto load_tile = [&](int kt) {
+    // CHECK = false: a whole step.  CHECK = true: the partial last step; chunks at k >= K are
+    // zero-filled with an ordinary LDS store so that the MFMAs can always run all four sub-steps.
+    auto issue_loads = [&](int kt, int stage, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
         const bool second = EPI == EPI_DUAL_ACC && kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BK;
+        unsigned char* sa = smem + stage * STAGE;
+        unsigned char* sb = sa + A_BYTES;
+        const unsigned char* abase = (const unsigned char*)(second ? g.A2 : gA) + (int64_t)k0 * 2;
+        const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const bool ok = k0 + lc * 8 < g.K;
-            const uint16_t* p = (second ? a2_row[i] : a_row[i]) + k0;
-            ra[i] = ok ? ldg16(p) : zero4;
+        for (int i = 0; i < SA; ++i) {
+            unsigned char* dst = sa + (wave + NW * i) * 1024;
+            if (!CHECK || k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K)
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(abase + a_off[i]), (lds_void_ptr)dst, 16, 0, 0);
+            else
+                *(u32x4*)(dst + lane * 16) = zero4;
         }
         if (!B_KN) {
+            const unsigned char* bbase0 = (const unsigned char*)gB + (int64_t)k0 * 2;
+            const unsigned char* bbase1 = (const unsigned char*)g.B2 + (int64_t)k0 * 2;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const bool ok = k0 + lc * 8 < g.K;
-                rb[i] = ok ? ldg16(b_row[i] + k0) : zero4;
+            for (int i = 0; i < SB; ++i) {
+                unsigned char* dst = sb + (wave + NW * i) * 1024;
+                // SWIGLU_FWD: tile rows BN/2.. hold the up-projection rows (second matrix)
+                const bool up = kFwd && 8 * (wave + NW * i) >= BN / 2;
+                const unsigned char* base = up ? bbase1 : bbase0;
+                if (!CHECK || k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K)
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(base + b_off[i]), (lds_void_ptr)dst, 16, 0, 0);
+                else
+                    *(u32x4*)(dst + lane * 16) = zero4;
             }
         } else {
-            const uint16_t* base = second ? g.B2 : g.B;
+            const unsigned char* bbase = (const unsigned char*)(second ? g.B2 : gB);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = k0 + kr + 16 * i;
-                const bool ok = kcol_ok && k < g.K;
-                const int kk = k < g.K ? k : g.K - 1;
-                const int64_t row = g.bg ? g.bg[kk] : kk;
-                rb[i] = ok ? ldg16(base + row * g.ldb + n0 + kc * 8) : zero4;
+            for (int i = 0; i < SB; ++i) {
+                unsigned char* dst = sb + (wave + NW * i) * 1024;
+                const int k = k0 + b_k[i];
+                if (!CHECK || k < g.K) {
+                    const int64_t row = g.bg ? g.bg[k] : k;
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(bbase + row * g.ldb * 2 + b_off[i]), (lds_void_ptr)dst, 16,
+                                                     0, 0);
+                } else {
+                    *(u32x4*)(dst + lane * 16) = zero4;
+                }
             }
         }
     };
-    auto store_tile = [&](int stage) {
-        unsigned char* sa = smem + stage * STAGE_BYTES;
-        unsigned char* sb = sa + A_TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(u32x4*)(sa + row_chunk(lr + 32 * i, lc) * 16) = ra[i];
-            if (!B_KN)
-                *(u32x4*)(sb + row_chunk(lr + 32 * i, lc) * 16) = rb[i];
-            else
-                *(u32x4*)(sb + k_chunk(kr + 16 * i, kc) * 16) = rb[i];
-        }
+    auto issue = [&](int kt, int stage) {
+        const int k_in_pair = (EPI == EPI_DUAL_ACC && kt >= nk1) ? kt - nk1 : kt;
+        if (k_in_pair < nfull)
+            issue_loads(kt, stage, std::false_type{});
+        else
+            issue_loads(kt, stage, std::true_type{});
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // tile rows / columns of this wave's fragments
-    const int l32 = lane & 31, lhi = lane >> 5;
-    int bfrag[2];
-    bfrag[0] = kFwd ? 32 * wn : 64 * wn;
-    bfrag[1] = kFwd ? 64 + 32 * wn : 64 * wn + 32;
+    // tile row (row tile) or column (k tile) where fragment j of this wave starts (wave-uniform)
+    int bfrag[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        if (kFwd)
+            bfrag[j] = (j & 1) * (BN / 2) + (WN / 2) * wn + 32 * (j >> 1);
+        else
+            bfrag[j] = WN * wn + 32 * j;
+    }
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
+    // ---- LDS read addresses.  Everything that depends on the lane is folded into a few byte
+    // offsets; fragment index, depth sub-step and stage only add compile-time constants.
+    // row tile: chunk (r, c) at r*8 + (c ^ ((r >> 1) & 7)); for r = base + lane%32 with base a
+    // multiple of 32 the XOR term is (lane%32 >> 1) & 7 for every fragment.
+    int row_off[BK / 16];  // byte offset of this lane's chunk inside its row, per depth sub-step
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) row_off[s] = (((2 * s + lhi) ^ ((l32 >> 1) & 7)) * 16) + l32 * 128;
+    const int a_base = WM * wm * 128;
+    // k tile: lane i of a 16-lane block addresses row k + i/4, 4 columns starting at 4 (i%4) of the
+    // block's 16 columns; k & 3 == (i/4) & 3 for every sub-step, so the rotation is fixed per lane.
+    int kn_off[FN];
+    if (B_KN) {
+        const int blk = lane >> 4, li = lane & 15;
+        const int krow = 8 * (blk >> 1) + (li >> 2);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = bfrag[j] + 16 * (blk & 1) + 4 * (li & 3);
+            const int pos = krow * BCH + ((col >> 3) + 4 * (krow & 3)) % BCH;
+            kn_off[j] = pos * 16 + (col & 4) * 2;
+        }
+    }
+
+    auto read_frags = [&](const unsigned char* sa, const unsigned char* sb, int s, bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+            fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 32 * 128 + row_off[s]));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            if (!B_KN) {
+                fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + bfrag[j] * 128 + row_off[s]));
+            } else {
+                // transposing read: the block's lane n receives rows k..k+3 of column n
+                const unsigned char* p = sb + kn_off[j] + s * 16 * BCH * 16;
+                const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * BCH * 16));
+                const s16x8 both = {h0[0], h0[1], h0[2], h0[3], h1[0], h1[1], h1[2], h1[3]};
+                fb[j] = __builtin_bit_cast(bf16x8, both);
+            }
+        }
+    };
+    auto mfma_step = [&](const bf16x8 (&fa)[FM], const bf16x8 (&fb)[FN]) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+
+    issue(0, 0);
 
     for (int kt = 0; kt < nk; ++kt) {
         const int stage = kt & 1;
-        if (kt + 1 < nk) load_tile(kt + 1);
-        const unsigned char* sa = smem + stage * STAGE_BYTES;
-        const unsigned char* sb = sa + A_TILE_BYTES;
+        SDP_WAIT_VMCNT(0);  // this wave's chunks of step kt have landed
+        __syncthreads();    // everybody's have; and everybody is done reading the other stage
+        if (kt + 1 < nk) issue(kt + 1, stage ^ 1);
+        const unsigned char* sa = smem + stage * STAGE;
+        const unsigned char* sb = sa + A_BYTES;
+        // fragments of sub-step s+1 are read while the MFMAs of sub-step s run
+        bf16x8 fa[2][FM], fb[2][FN];
+        read_frags(sa, sb, 0, fa[0], fb[0]);
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
-            bf16x8 fa[2], fb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int r = 64 * wm + 32 * i + l32;
-                fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + row_chunk(r, 2 * s + lhi) * 16));
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if (!B_KN) {
-                    const int r = bfrag[j] + l32;
-                    fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + row_chunk(r, 2 * s + lhi) * 16));
-                } else {
-                    // transposing read: inside each 16-lane block, lane i addresses 4 columns of row
-                    // k + i/4; the block's lane n receives rows k..k+3 of column n.
-                    const int blk = lane >> 4, li = lane & 15;
-                    const int col = bfrag[j] + 16 * (blk & 1) + 4 * (li & 3);
-                    const int kbase = 16 * s + 8 * (blk >> 1) + (li >> 2);
-                    s16x4 h[2];
-#pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {
-                        const int k = kbase + 4 * hh;
-                        const unsigned char* p = sb + k_chunk(k, col >> 3) * 16 + (col & 4) * 2;
-                        h[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
-                    }
-                    typedef short s16x8 __attribute__((ext_vector_type(8)));
-                    s16x8 both = {h[0][0], h[0][1], h[0][2], h[0][3], h[1][0], h[1][1], h[1][2], h[1][3]};
-                    fb[j] = __builtin_bit_cast(bf16x8, both);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            if (s + 1 < BK / 16) read_frags(sa, sb, s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+            mfma_step(fa[s & 1], fb[s & 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < nk) store_tile(stage ^ 1);
-        __syncthreads();
     }
 
     // ---- epilogue.  acc[i][j][4q + r] is C(m, n) with
-    //      m = m0 + 64 wm + 32 i + 8 q + 4 (lane / 32) + r,  n = (fragment j column base) + lane % 32
+    //      m = m0 + WM wm + 32 i + 8 q + 4 (lane / 32) + r,  n = n0 + (fragment j column base) + lane % 32
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int mb = m0 + 64 * wm + 32 * i + 8 * q + 4 * lhi;
+            const int mb = m0 + WM * wm + 32 * i + 8 * q + 4 * lhi;
             if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < FN; ++j) {
                     const int n = n0 + bfrag[j] + l32;
                     if (n >= g.N) continue;
 #pragma unroll
@@ -232,25 +329,28 @@ __global__ __launch_bounds__(NTHREADS, 2) void gemm_mfma_kernel(Dev g) {
                         const int m = mb + r;
                         if (m >= g.M) continue;
                         const int64_t row = g.cs ? g.cs[m] : m;
-                        g.C[row * g.ldc + n] = f32_to_bf16(acc[i][j][4 * q + r]);
+                        gC[row * g.ldc + n] = f32_to_bf16(acc[i][j][4 * q + r]);
                     }
                 }
             } else if (EPI == EPI_SWIGLU_FWD) {
-                const int n = n0 + 32 * wn + l32;
-                if (n >= g.N) continue;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int m = mb + r;
-                    if (m >= g.M) continue;
-                    const float gv = acc[i][0][4 * q + r], uv = acc[i][1][4 * q + r];
-                    const int64_t o = (int64_t)m * g.ldc + n;
-                    g.C[o] = f32_to_bf16(gv);
-                    g.C2[o] = f32_to_bf16(uv);
-                    g.C3[o] = f32_to_bf16(swiglu_fwd<false>(gv, uv));
+                for (int jj = 0; jj < FN / 2; ++jj) {
+                    const int n = n0 + (WN / 2) * wn + 32 * jj + l32;
+                    if (n >= g.N) continue;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int m = mb + r;
+                        if (m >= g.M) continue;
+                        const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
+                        const int64_t o = (int64_t)m * g.ldc + n;
+                        g.C[o] = f32_to_bf16(gv);
+                        g.C2[o] = f32_to_bf16(uv);
+                        g.C3[o] = f32_to_bf16(swiglu_fwd<false>(gv, uv));
+                    }
                 }
             } else { // EPI_SWIGLU_BWD
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < FN; ++j) {
                     const int n = n0 + bfrag[j] + l32;
                     if (n >= g.N) continue;
                     float dg[4], du[4], act[4];
@@ -287,8 +387,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void gemm_mfma_kernel(Dev g) {
     }
 }
 
-template <int B_KN, int EPI>
-int launch(const GemmDesc& d, hipStream_t s) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, int B_KN, int EPI, int OP>
+int launch_cfg(const GemmDesc& d, hipStream_t s) {
+    constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
+    constexpr int LDS = 2 * (BM + BN) * BK * 2;
     Dev g;
     g.M = d.M, g.N = d.N, g.K = d.K;
     g.A = (const uint16_t*)d.A, g.A2 = (const uint16_t*)d.A2, g.B = (const uint16_t*)d.B, g.B2 = (const uint16_t*)d.B2;
@@ -299,28 +401,68 @@ int launch(const GemmDesc& d, hipStream_t s) {
     g.tiles_m = (d.M + BM - 1) / BM;
     const int ncols = EPI == EPI_SWIGLU_FWD ? BN / 2 : BN;
     g.tiles_n = (d.N + ncols - 1) / ncols;
-    const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n;
-    if (blocks > 0x7FFFFFFF) return SDP_ERR_SHAPE;
-    auto kern = gemm_mfma_kernel<B_KN, EPI>;
-    static bool attr_set = false; // one flag per template instantiation
+    const int64_t ntiles = (int64_t)g.tiles_m * g.tiles_n;
+    const int nbatch = OP == OP_DW ? d.nbatch : 1;
+    if (ntiles * nbatch > 0x7FFFFFFF) return SDP_ERR_SHAPE;
+    g.ntiles = (int)ntiles;
+    for (int z = 0; z < 3; ++z) {
+        g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
+    }
+    auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, B_KN, EPI, OP>;
+    static bool attr_set = false; // one flag per instantiation
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return SDP_ERR_HIP;
         attr_set = true;
     }
     ProfileScope ps(d.name, s);
-    kern<<<dim3((unsigned)blocks), NTHREADS, LDS_BYTES, s>>>(g);
+    kern<<<dim3((unsigned)(ntiles * nbatch)), NTHREADS, LDS, s>>>(g);
     return launch_status();
+}
+
+constexpr int kNumCU = 256;
+
+// estimated time of a tile shape, in units of 256 x 256 tile-depths: rounds over the CUs times tile
+// area, times a penalty for the smaller shapes' lower MFMA duty (more LDS traffic per flop).
+double shape_cost(int M, int ncols_total, int nbatch, int bm, int bn, double penalty) {
+    const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((ncols_total + bn - 1) / bn) * nbatch;
+    const int64_t rounds = (tiles + kNumCU - 1) / kNumCU;
+    return (double)rounds * bm * bn * penalty;
+}
+
+template <int B_KN, int EPI, int OP>
+int launch(const GemmDesc& d, hipStream_t s) {
+    // columns of tile space (gate and up interleaved double the tile columns)
+    const int ncols = EPI == EPI_SWIGLU_FWD ? 2 * d.N : d.N;
+    const int nbatch = OP == OP_DW ? d.nbatch : 1;
+    const double c256 = shape_cost(d.M, ncols, nbatch, 256, 256, 1.0);
+    const double c192 = shape_cost(d.M, ncols, nbatch, 256, 192, 1.08);
+    const double c128 = shape_cost(d.M, ncols, nbatch, 128, 128, 1.6);
+    // SDP_FORCE_TILE=256|192|128 in the environment overrides the choice (tuning runs and tests)
+    int force = d.force_tile;
+    if (const char* e = getenv("SDP_FORCE_TILE")) force = atoi(e);
+    if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) return launch_cfg<256, 256, 2, 4, B_KN, EPI, OP>(d, s);
+    if constexpr (EPI != EPI_SWIGLU_FWD) {
+        if (force == 192 || (!force && c192 <= c128)) return launch_cfg<256, 192, 4, 2, B_KN, EPI, OP>(d, s);
+    }
+    return launch_cfg<128, 128, 2, 2, B_KN, EPI, OP>(d, s);
 }
 
 } // namespace
 
 bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return false;
-    // 16-byte global chunks: every row start and every chunk must be 8-element aligned
-    if (d.K % 8 || d.lda % 8 || d.ldb % 8) return false;
+    // 16-byte global chunks, 16-deep MFMA steps
+    if (d.K % 16 || d.lda % 8 || d.ldb % 8) return false;
     if (d.b_kn && d.N % 8) return false;
-    for (const void* p : {d.A, d.B}) if (!p || !aligned16(p)) return false;
+    if (d.nbatch > 0) {
+        if (d.nbatch > 3 || d.epilogue != EPI_STORE || !d.b_kn) return false;
+        for (int z = 0; z < d.nbatch; ++z)
+            if (!d.Ab[z] || !d.Bb[z] || !d.Cb[z] || !aligned16(d.Ab[z]) || !aligned16(d.Bb[z])) return false;
+    } else {
+        for (const void* p : {d.A, d.B})
+            if (!p || !aligned16(p)) return false;
+    }
     if (d.epilogue == EPI_DUAL_ACC || d.epilogue == EPI_SWIGLU_FWD)
         if (!d.B2 || !aligned16(d.B2)) return false;
     if (d.epilogue == EPI_DUAL_ACC && (!d.A2 || !aligned16(d.A2))) return false;
@@ -331,13 +473,14 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 
 int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
     if (!gemm_mfma_supported(d)) return SDP_ERR_UNSUPPORTED;
+    // OP only gives every call site its own kernel symbol, so that profiles name the step
     if (d.b_kn) {
-        if (d.epilogue == EPI_STORE) return launch<1, EPI_STORE>(d, s);
-        if (d.epilogue == EPI_DUAL_ACC) return launch<1, EPI_DUAL_ACC>(d, s);
+        if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<1, EPI_STORE, OP_DW>(d, s);
+        if (d.epilogue == EPI_STORE) return launch<1, EPI_STORE, OP_DOWN>(d, s);
+        if (d.epilogue == EPI_DUAL_ACC) return launch<1, EPI_DUAL_ACC, OP_DX>(d, s);
     } else {
-        if (d.epilogue == EPI_STORE) return launch<0, EPI_STORE>(d, s);
-        if (d.epilogue == EPI_SWIGLU_FWD) return launch<0, EPI_SWIGLU_FWD>(d, s);
-        if (d.epilogue == EPI_SWIGLU_BWD) return launch<0, EPI_SWIGLU_BWD>(d, s);
+        if (d.epilogue == EPI_SWIGLU_FWD) return launch<0, EPI_SWIGLU_FWD, OP_GATE_UP>(d, s);
+        if (d.epilogue == EPI_SWIGLU_BWD) return launch<0, EPI_SWIGLU_BWD, OP_DACT>(d, s);
     }
     return SDP_ERR_UNSUPPORTED;
 }

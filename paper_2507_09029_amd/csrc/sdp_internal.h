@@ -73,7 +73,17 @@ struct GemmDesc {
     void* T3 = nullptr; // ActT
     int64_t ldt = 0;
     const char* name = "gemm";
+    // batched launch of up to three problems with the same shape, strides, gathers and scatter
+    // (the weight-gradient contractions): nbatch > 0 selects Ab/Bb/Cb instead of A/B/C
+    int nbatch = 0;
+    const void* Ab[3] = {nullptr, nullptr, nullptr};
+    const void* Bb[3] = {nullptr, nullptr, nullptr};
+    void* Cb[3] = {nullptr, nullptr, nullptr};
+    int force_tile = 0; // 0 = choose; 256 / 192 / 128 force a tile shape (tuning and tests)
 };
+
+// tags that give each call site of the MFMA contraction its own kernel symbol
+enum GemmOp { OP_GATE_UP = 0, OP_DOWN = 1, OP_DACT = 2, OP_DX = 3, OP_DW = 4 };
 
 // Plain LDS-tiled FMA contraction, any shape; element type float or bf16 (dtype as sdp_dtype).
 int gemm_simple(int dtype, const GemmDesc& g, hipStream_t s);

@@ -130,18 +130,27 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     const void* lhs[3] = {dGT, dUT, ActT};
     const void* rhs[3] = {X, X, dY};
     void* outp[3] = {dW1, dW3, dW2T};
-    for (int i = 0; i < 3; ++i) {
-        GemmDesc dw;
-        dw.name = "mlp_dw";
-        dw.M = p, dw.N = d, dw.K = T;
-        dw.A = lhs[i], dw.lda = T;
-        dw.a_gather = mode == SDP_MASK_BACKWARD ? idx_k : nullptr; // rows of the neuron-major operand on the mask
-        dw.B = rhs[i], dw.ldb = d, dw.b_kn = 1;
-        dw.epilogue = EPI_STORE;
-        dw.C = outp[i], dw.ldc = d;
-        dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
-        rc = run(dtype, dw, s);
+    GemmDesc dw;
+    dw.name = "mlp_dw";
+    dw.M = p, dw.N = d, dw.K = T;
+    dw.lda = T;
+    dw.a_gather = mode == SDP_MASK_BACKWARD ? idx_k : nullptr; // rows of the neuron-major operand on the mask
+    dw.ldb = d, dw.b_kn = 1;
+    dw.epilogue = EPI_STORE;
+    dw.ldc = d;
+    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
+    dw.nbatch = 3;
+    for (int i = 0; i < 3; ++i) dw.Ab[i] = lhs[i], dw.Bb[i] = rhs[i], dw.Cb[i] = outp[i];
+    if (dtype == SDP_BF16 && gemm_mfma_supported(dw)) {
+        rc = gemm_mfma_bf16(dw, s); // one launch for the three
         if (rc != SDP_OK) return rc;
+    } else {
+        dw.nbatch = 0;
+        for (int i = 0; i < 3; ++i) {
+            dw.A = lhs[i], dw.B = rhs[i], dw.C = outp[i];
+            rc = gemm_simple(dtype, dw, s);
+            if (rc != SDP_OK) return rc;
+        }
     }
     return SDP_OK;
 }
