@@ -44,7 +44,7 @@ def flops_per_launch(name, w):
         "mlp_down": 2 * w.T * w.d * n,
         "mlp_dact": 2 * w.T * w.d * n,
         "mlp_dx": 4 * w.T * w.d * n,
-        "mlp_dw": 2 * w.T * w.d * w.p,
+        "mlp_dw": 6 * w.T * w.d * w.p,  # one batched launch for dW1, dW3, dW2T
     }.get(name)
 
 

@@ -1,29 +1,33 @@
-// bf16 MFMA contraction for gfx950 (CDNA4) with the masked-MLP gathers and SwiGLU epilogues fused.
+// bf16 MFMA contraction for gfx950 (CDNA4) with the masked-MLP row gather and SwiGLU epilogues fused.
 //
 //   C[M][N] = sum_k A(m,k) B(k,n),  bf16 operands, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
+//   B is stored [N][K] (rows optionally gathered through an index table); A is stored [M][K], or
+//   [K][M] ("depth-major": the activations that the weight-gradient contractions read transposed).
 //
 // Tile: BM x BN outputs per workgroup, depth step 64, WAVES_M x WAVES_N waves of 64 lanes, each wave
 // owning (BM/WAVES_M) x (BN/WAVES_N) outputs as 32 x 32 MFMA tiles.  The flagship shape is
-// 256 x 256 with 8 waves (2 x 4): 128 accumulator registers per lane, two waves per SIMD.
+// 256 x 256 with 8 waves: 128 accumulator registers per lane, two waves per SIMD.
 //
 // HBM/L2 -> LDS: direct loads (global_load_lds_dwordx4).  One wave instruction moves 64 chunks of
 // 16 bytes (8 bf16) into 1 KB of consecutive LDS; which global chunk a lane fetches is free, so the
-// LDS layout below is produced by choosing the global address per lane.  No registers, no
+// LDS layouts below are produced by choosing the global address per lane.  No registers and no
 // ds_write instructions are spent on staging.  Two LDS stages; per depth step: wait for this wave's
 // loads of the step, one barrier, issue the next step's loads, run the MFMAs.
 //
 // LDS layouts (positions in 16-byte chunks):
-//   "row tile"  [R rows][64 k]      : A always; B when stored [N][K].  Chunk (r, c) sits at
-//                r*8 + (c ^ ((r >> 1) & 7)).  A lane's MFMA operand (8 consecutive k of one row)
-//                is one chunk: one ds_read_b128.
-//   "k tile"    [64 k][BN cols]     : B when stored [K][N] (gathered weight rows of the down / dX
-//                contractions, X and dY of the weight-gradient contractions).  Chunk (k, c) sits at
-//                k*(BN/8) + (c + 4 (k & 3)) mod (BN/8).  The MFMA operand needs 8 consecutive k
-//                of one column, i.e. a transpose: two ds_read_b64_tr_b16 per fragment.
+//   "row tile"  [R rows][64 k]   : B always, A when stored [M][K].  Chunk (r, c) sits at
+//                r*8 + (c ^ ((r >> 1) & 7)).  A lane's MFMA operand (8 consecutive k of one row) is
+//                one chunk: one ds_read_b128.
+//   "k tile"    [64 k][BM cols]  : A when stored [K][M].  Chunk (k, c) sits at
+//                k*(BM/8) + (c + 4 (k & 3)) mod (BM/8).  The MFMA operand needs 8 consecutive k of
+//                one column, i.e. a transpose: two ds_read_b64_tr_b16 per fragment.
 // Both patterns spread the lanes served in one LDS cycle over distinct banks.
 //
-// Row gathers (active-neuron indices) are applied when forming global addresses: a gathered row is
-// one contiguous run of K (or N) elements, so every global access stays a 16-byte chunk.
+// The MFMA is issued with the B fragment as its first operand: a lane then holds, for one output
+// row m, 4 consecutive columns n.  Epilogues go through LDS: each wave packs 32 x WN outputs as bf16
+// into a private LDS strip with 8-byte writes and reads the strip back as 16-byte chunks of whole
+// rows, so that every global store (and the loads of the saved pre-activations) is a coalesced
+// 16-byte access.  SwiGLU and its backward are applied on the fp32 accumulators before packing.
 //
 // Workgroup -> tile mapping is XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs
 // (each with its own L2), so ids are first regrouped per XCD and each XCD then walks a compact
@@ -42,7 +46,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -59,13 +62,15 @@ struct Dev {
     int M, N, K;
     const uint16_t *A, *A2, *B, *B2;
     int64_t lda, ldb;
-    const int32_t *ag, *bg, *cs;
+    const int32_t *bg, *cs;
     uint16_t *C, *C2, *C3;
     int64_t ldc;
     const uint16_t *Gin, *Uin;
     int64_t ldg;
-    uint16_t *T1, *T2, *T3;
-    int64_t ldt;
+    uint16_t *Cc, *Cc2, *Cc3;
+    int64_t ldcc;
+    const int32_t* cidx;
+    int pc;
     int tiles_m, tiles_n, ntiles;
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
     const uint16_t *Ab[3], *Bb[3];
@@ -75,26 +80,42 @@ struct Dev {
 __device__ inline uint32_t pack_bf16(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
+__device__ inline u32x2 pack4(float a, float b, float c, float d) { return u32x2{pack_bf16(a, b), pack_bf16(c, d)}; }
+__device__ inline float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 // s_waitcnt vmcnt(n) alone (expcnt / lgkmcnt left at their maxima), gfx9 encoding
 #define SDP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int B_KN, int EPI, int OP>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+struct Geometry {
+    static constexpr int NW = WAVES_M * WAVES_N;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int FM = WM / 32, FN = WN / 32;
+    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+    // epilogue strip: 32 rows x SW columns of bf16, rows padded by 8 bytes
+    static constexpr int SW = EPI == EPI_SWIGLU_FWD ? WN / 2 : WN;
+    static constexpr int RS = SW * 2 + 8;
+    static constexpr int STRIP = 32 * RS;
+    static constexpr int LDS = 2 * STAGE > NW * STRIP ? 2 * STAGE : NW * STRIP;
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int A_KM, int EPI, int OP>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev g) {
-    constexpr int NW = WAVES_M * WAVES_N;
-    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-    constexpr int FM = WM / 32, FN = WN / 32;
+    using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
+    constexpr int NW = Geo::NW, WM = Geo::WM, WN = Geo::WN, FM = Geo::FM, FN = Geo::FN;
+    constexpr int A_BYTES = Geo::A_BYTES, STAGE = Geo::STAGE;
     constexpr bool kFwd = EPI == EPI_SWIGLU_FWD;
-    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-    constexpr int SA = (BM / 8) / NW;          // A slabs (1 KB) per wave per step
-    constexpr int SB = (BN / 8) / NW;          // B slabs per wave per step (both layouts: BN*64*2/1024 = BN/8)
-    constexpr int BCH = BN / 8;                // chunks per k-tile row
+    constexpr int SA = (BM / 8) / NW;  // A slabs (1 KB) per wave per step
+    constexpr int SB = (BN / 8) / NW;  // B slabs per wave per step
+    constexpr int ACH = BM / 8;        // chunks per row of the A k tile
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "slabs must divide among the waves");
     static_assert(!kFwd || FN % 2 == 0, "gate/up fragments come in pairs");
+    static_assert(ACH % 4 == 0, "rotation works in groups of 4 chunks");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: keeps everything derived from it scalar
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: keeps what derives from it scalar
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int l32 = lane & 31, lhi = lane >> 5;
 
@@ -137,37 +158,36 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // ---- per-lane global source of every slab this wave fills: byte offsets from a uniform base.
     // Row and column indices beyond the matrix are clamped to the last valid one: such lanes fetch
     // valid memory whose products only reach outputs that are never stored.
-    // row tile, slab s: rows 8s .. 8s+7; lane -> row 8s + lane/8, stored position lane%8
     uint32_t a_off[SA];
+    int a_k[SA]; // A_KM: k row inside the tile
 #pragma unroll
     for (int i = 0; i < SA; ++i) {
-        const int r = 8 * (wave + NW * i) + (lane >> 3);
-        const int c = (lane & 7) ^ ((r >> 1) & 7);
-        int m = m0 + r;
-        m = m < g.M ? m : g.M - 1;
-        const int64_t row = g.ag ? g.ag[m] : m;
-        a_off[i] = (uint32_t)((row * g.lda + c * 8) * 2);
-    }
-    uint32_t b_off[SB]; // B_KN == 0: row offset + chunk; B_KN == 1: column chunk offset (row added per step)
-    int b_k[SB];        // B_KN == 1: k row inside the tile
-#pragma unroll
-    for (int i = 0; i < SB; ++i) {
-        if (!B_KN) {
+        if (!A_KM) {
+            // row tile, slab s: rows 8s .. 8s+7; lane -> row 8s + lane/8, stored position lane%8
             const int r = 8 * (wave + NW * i) + (lane >> 3);
             const int c = (lane & 7) ^ ((r >> 1) & 7);
-            int n = kFwd ? n0 + (r % (BN / 2)) : n0 + r;
-            n = n < g.N ? n : g.N - 1;
-            const int64_t row = g.bg ? g.bg[n] : n;
-            b_off[i] = (uint32_t)((row * g.ldb + c * 8) * 2);
-            b_k[i] = 0;
+            int m = m0 + r;
+            m = m < g.M ? m : g.M - 1;
+            a_off[i] = (uint32_t)(((int64_t)m * g.lda + c * 8) * 2);
+            a_k[i] = 0;
         } else {
             const int q = 64 * (wave + NW * i) + lane; // chunk slot inside the k tile
-            const int k = q / BCH, pos = q % BCH;
-            b_k[i] = k;
-            int col = n0 + ((pos + BCH - 4 * (k & 3)) % BCH) * 8; // inverse of the stored rotation
-            col = col < g.N ? col : g.N - 8;
-            b_off[i] = (uint32_t)(col * 2);
+            const int k = q / ACH, pos = q % ACH;
+            a_k[i] = k;
+            int col = m0 + ((pos + ACH - 4 * (k & 3)) % ACH) * 8; // inverse of the stored rotation
+            col = col < g.M ? col : g.M - 8;
+            a_off[i] = (uint32_t)(((int64_t)k * g.lda + col) * 2);
         }
+    }
+    uint32_t b_off[SB];
+#pragma unroll
+    for (int i = 0; i < SB; ++i) {
+        const int r = 8 * (wave + NW * i) + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        int n = kFwd ? n0 + (r % (BN / 2)) : n0 + r;
+        n = n < g.N ? n : g.N - 1;
+        const int64_t row = g.bg ? g.bg[n] : n;
+        b_off[i] = (uint32_t)((row * g.ldb + c * 8) * 2);
     }
 
     // CHECK = false: a whole step.  CHECK = true: the partial last step; chunks at k >= K are
@@ -178,44 +198,36 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         const int k0 = (second ? kt - nk1 : kt) * BK;
         unsigned char* sa = smem + stage * STAGE;
         unsigned char* sb = sa + A_BYTES;
-        const unsigned char* abase = (const unsigned char*)(second ? g.A2 : gA) + (int64_t)k0 * 2;
         const u32x4 zero4 = {0u, 0u, 0u, 0u};
+        const unsigned char* abase =
+            (const unsigned char*)(second ? g.A2 : gA) + (A_KM ? (int64_t)k0 * g.lda * 2 : (int64_t)k0 * 2);
 #pragma unroll
         for (int i = 0; i < SA; ++i) {
             unsigned char* dst = sa + (wave + NW * i) * 1024;
-            if (!CHECK || k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K)
+            bool ok = true;
+            if (CHECK) {
+                if (A_KM)
+                    ok = k0 + a_k[i] < g.K;
+                else
+                    ok = k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K;
+            }
+            if (ok)
                 __builtin_amdgcn_global_load_lds((glb_void_ptr)(abase + a_off[i]), (lds_void_ptr)dst, 16, 0, 0);
             else
                 *(u32x4*)(dst + lane * 16) = zero4;
         }
-        if (!B_KN) {
-            const unsigned char* bbase0 = (const unsigned char*)gB + (int64_t)k0 * 2;
-            const unsigned char* bbase1 = (const unsigned char*)g.B2 + (int64_t)k0 * 2;
+        const unsigned char* bbase0 = (const unsigned char*)(second ? g.B2 : gB) + (int64_t)k0 * 2;
+        const unsigned char* bbase1 = (const unsigned char*)g.B2 + (int64_t)k0 * 2;
 #pragma unroll
-            for (int i = 0; i < SB; ++i) {
-                unsigned char* dst = sb + (wave + NW * i) * 1024;
-                // SWIGLU_FWD: tile rows BN/2.. hold the up-projection rows (second matrix)
-                const bool up = kFwd && 8 * (wave + NW * i) >= BN / 2;
-                const unsigned char* base = up ? bbase1 : bbase0;
-                if (!CHECK || k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K)
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(base + b_off[i]), (lds_void_ptr)dst, 16, 0, 0);
-                else
-                    *(u32x4*)(dst + lane * 16) = zero4;
-            }
-        } else {
-            const unsigned char* bbase = (const unsigned char*)(second ? g.B2 : gB);
-#pragma unroll
-            for (int i = 0; i < SB; ++i) {
-                unsigned char* dst = sb + (wave + NW * i) * 1024;
-                const int k = k0 + b_k[i];
-                if (!CHECK || k < g.K) {
-                    const int64_t row = g.bg ? g.bg[k] : k;
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(bbase + row * g.ldb * 2 + b_off[i]), (lds_void_ptr)dst, 16,
-                                                     0, 0);
-                } else {
-                    *(u32x4*)(dst + lane * 16) = zero4;
-                }
-            }
+        for (int i = 0; i < SB; ++i) {
+            unsigned char* dst = sb + (wave + NW * i) * 1024;
+            // SWIGLU_FWD: tile rows BN/2.. hold the up-projection rows (second matrix)
+            const bool up = kFwd && 8 * (wave + NW * i) >= BN / 2;
+            const unsigned char* base = up ? bbase1 : bbase0;
+            if (!CHECK || k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K)
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(base + b_off[i]), (lds_void_ptr)dst, 16, 0, 0);
+            else
+                *(u32x4*)(dst + lane * 16) = zero4;
         }
     };
     auto issue = [&](int kt, int stage) {
@@ -234,7 +246,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // tile row (row tile) or column (k tile) where fragment j of this wave starts (wave-uniform)
+    // B tile row where fragment j of this wave starts (wave-uniform)
     int bfrag[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -248,48 +260,50 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // offsets; fragment index, depth sub-step and stage only add compile-time constants.
     // row tile: chunk (r, c) at r*8 + (c ^ ((r >> 1) & 7)); for r = base + lane%32 with base a
     // multiple of 32 the XOR term is (lane%32 >> 1) & 7 for every fragment.
-    int row_off[BK / 16];  // byte offset of this lane's chunk inside its row, per depth sub-step
+    int row_off[BK / 16];
 #pragma unroll
     for (int s = 0; s < BK / 16; ++s) row_off[s] = (((2 * s + lhi) ^ ((l32 >> 1) & 7)) * 16) + l32 * 128;
     const int a_base = WM * wm * 128;
     // k tile: lane i of a 16-lane block addresses row k + i/4, 4 columns starting at 4 (i%4) of the
     // block's 16 columns; k & 3 == (i/4) & 3 for every sub-step, so the rotation is fixed per lane.
-    int kn_off[FN];
-    if (B_KN) {
+    int km_off[FM];
+    if (A_KM) {
         const int blk = lane >> 4, li = lane & 15;
         const int krow = 8 * (blk >> 1) + (li >> 2);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = bfrag[j] + 16 * (blk & 1) + 4 * (li & 3);
-            const int pos = krow * BCH + ((col >> 3) + 4 * (krow & 3)) % BCH;
-            kn_off[j] = pos * 16 + (col & 4) * 2;
+        for (int i = 0; i < FM; ++i) {
+            const int col = WM * wm + 32 * i + 16 * (blk & 1) + 4 * (li & 3);
+            const int pos = krow * ACH + ((col >> 3) + 4 * (krow & 3)) % ACH;
+            km_off[i] = pos * 16 + (col & 4) * 2;
         }
     }
 
     auto read_frags = [&](const unsigned char* sa, const unsigned char* sb, int s, bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
-            fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 32 * 128 + row_off[s]));
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            if (!B_KN) {
-                fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + bfrag[j] * 128 + row_off[s]));
+        for (int i = 0; i < FM; ++i) {
+            if (!A_KM) {
+                fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 32 * 128 + row_off[s]));
             } else {
                 // transposing read: the block's lane n receives rows k..k+3 of column n
-                const unsigned char* p = sb + kn_off[j] + s * 16 * BCH * 16;
+                const unsigned char* p = sa + km_off[i] + s * 16 * ACH * 16;
                 const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
-                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * BCH * 16));
+                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * ACH * 16));
                 const s16x8 both = {h0[0], h0[1], h0[2], h0[3], h1[0], h1[1], h1[2], h1[3]};
-                fb[j] = __builtin_bit_cast(bf16x8, both);
+                fa[i] = __builtin_bit_cast(bf16x8, both);
             }
         }
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + bfrag[j] * 128 + row_off[s]));
     };
+    // B fragment first: the accumulator tile is then indexed [n][m] in the MFMA's own layout, i.e.
+    // lane (l32, lhi) holds, for output row m = l32, columns n = 8 q + 4 lhi + r in element 4 q + r.
     auto mfma_step = [&](const bf16x8 (&fa)[FM], const bf16x8 (&fb)[FN]) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     };
 
     issue(0, 0);
@@ -312,73 +326,132 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     }
 
-    // ---- epilogue.  acc[i][j][4q + r] is C(m, n) with
-    //      m = m0 + WM wm + 32 i + 8 q + 4 (lane / 32) + r,  n = n0 + (fragment j column base) + lane % 32
+    // ================================ epilogue ================================
+    // acc[i][j][4q + r] = C(m, n),  m = m0 + WM wm + 32 i + l32,
+    //                               n = n0 + (column base of fragment j) + 8 q + 4 lhi + r.
+    __syncthreads(); // all waves are done with the operand tiles: LDS becomes per-wave strips
+    constexpr int SW = Geo::SW, RS = Geo::RS;
+    constexpr int CPR = SW / 8;               // 16-byte chunks per strip row
+    constexpr int NCH = 32 * CPR;             // chunks per strip
+    unsigned char* strip = smem + wave * Geo::STRIP;
+    const int wcol0 = kFwd ? n0 + (WN / 2) * wn : n0 + WN * wn; // first output column of this wave's strip
+
+    // write one packed 8-byte group of the strip: row l32, columns cbase + 8 q + 4 lhi ..
+    auto strip_put = [&](int cbase, int q, u32x2 v) { *(u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2) = v; };
+    auto strip_get = [&](int cbase, int q) { return *(const u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2); };
+    // strip -> global: rows of `out` (leading dimension ld), optional row scatter
+    auto strip_store = [&](uint16_t* out, int64_t ld, const int32_t* scatter, int i) {
+#pragma unroll
+        for (int it = 0; it < (NCH + 63) / 64; ++it) {
+            const int c = it * 64 + lane;
+            if (NCH % 64 != 0 && c >= NCH) break;
+            const int row = c / CPR, cc = c % CPR;
+            const u32x2 lo = *(const u32x2*)(strip + row * RS + cc * 16);
+            const u32x2 hi = *(const u32x2*)(strip + row * RS + cc * 16 + 8);
+            const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
+            if (m < g.M && n < g.N) {
+                const int64_t orow = scatter ? scatter[m] : m;
+                *(u32x4*)(out + orow * ld + n) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+        }
+    };
+    // global -> strip: the same chunk mapping, zero outside the matrix
+    auto strip_load = [&](const uint16_t* in, int64_t ld, int i) {
+#pragma unroll
+        for (int it = 0; it < (NCH + 63) / 64; ++it) {
+            const int c = it * 64 + lane;
+            if (NCH % 64 != 0 && c >= NCH) break;
+            const int row = c / CPR, cc = c % CPR;
+            const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (m < g.M && n < g.N) v = *(const u32x4*)(in + (int64_t)m * ld + n);
+            *(u32x2*)(strip + row * RS + cc * 16) = u32x2{v[0], v[1]};
+            *(u32x2*)(strip + row * RS + cc * 16 + 8) = u32x2{v[2], v[3]};
+        }
+    };
+
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+        if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int mb = m0 + WM * wm + 32 * i + 8 * q + 4 * lhi;
-            if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int n = n0 + bfrag[j] + l32;
-                    if (n >= g.N) continue;
+                for (int q = 0; q < 4; ++q)
+                    strip_put(32 * j, q, pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+            strip_store(gC, g.ldc, g.cs, i);
+        } else if (EPI == EPI_SWIGLU_FWD) {
+            // fragments 2 jj (gate) and 2 jj + 1 (up) cover the same 32 neurons
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = mb + r;
-                        if (m >= g.M) continue;
-                        const int64_t row = g.cs ? g.cs[m] : m;
-                        gC[row * g.ldc + n] = f32_to_bf16(acc[i][j][4 * q + r]);
-                    }
-                }
-            } else if (EPI == EPI_SWIGLU_FWD) {
+            for (int which = 0; which < 3; ++which) {
 #pragma unroll
-                for (int jj = 0; jj < FN / 2; ++jj) {
-                    const int n = n0 + (WN / 2) * wn + 32 * jj + l32;
-                    if (n >= g.N) continue;
+                for (int jj = 0; jj < FN / 2; ++jj)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = mb + r;
-                        if (m >= g.M) continue;
-                        const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
-                        const int64_t o = (int64_t)m * g.ldc + n;
-                        g.C[o] = f32_to_bf16(gv);
-                        g.C2[o] = f32_to_bf16(uv);
-                        g.C3[o] = f32_to_bf16(swiglu_fwd<false>(gv, uv));
-                    }
-                }
-            } else { // EPI_SWIGLU_BWD
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int n = n0 + bfrag[j] + l32;
-                    if (n >= g.N) continue;
-                    float dg[4], du[4], act[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = mb + r < g.M ? mb + r : g.M - 1;
-                        const float gv = bf16_to_f32(g.Gin[(int64_t)m * g.ldg + n]);
-                        const float uv = bf16_to_f32(g.Uin[(int64_t)m * g.ldg + n]);
-                        swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg[r], du[r], act[r]);
-                        if (mb + r < g.M) {
-                            const int64_t o = (int64_t)(mb + r) * g.ldc + n;
-                            g.C[o] = f32_to_bf16(dg[r]);
-                            g.C2[o] = f32_to_bf16(du[r]);
-                        }
-                    }
-                    // neuron-major copies: 4 consecutive tokens of one neuron per lane
-                    const int64_t t = (int64_t)n * g.ldt + mb;
-                    if (mb + 3 < g.M && (g.ldt & 3) == 0) {
-                        *(u32x2*)(g.T1 + t) = u32x2{pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3])};
-                        *(u32x2*)(g.T2 + t) = u32x2{pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
-                        *(u32x2*)(g.T3 + t) = u32x2{pack_bf16(act[0], act[1]), pack_bf16(act[2], act[3])};
-                    } else {
+                    for (int q = 0; q < 4; ++q) {
+                        float v[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            if (mb + r >= g.M) continue;
-                            g.T1[t + r] = f32_to_bf16(dg[r]);
-                            g.T2[t + r] = f32_to_bf16(du[r]);
-                            g.T3[t + r] = f32_to_bf16(act[r]);
+                            const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
+                            v[r] = which == 0 ? gv : (which == 1 ? uv : swiglu_fwd<false>(gv, uv));
+                        }
+                        strip_put(32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
+                    }
+                strip_store(which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, nullptr, i);
+            }
+        } else { // EPI_SWIGLU_BWD
+            u32x2 gq[FN][4], uq[FN][4];
+            strip_load(g.Gin, g.ldg, i);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) gq[j][q] = strip_get(32 * j, q);
+            strip_load(g.Uin, g.ldg, i);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) uq[j][q] = strip_get(32 * j, q);
+            // column range of the compacted copies that falls into this wave's strip
+            int c_lo = 0, c_hi = 0;
+            if (g.cidx) {
+                int lo = 0, hi = g.pc;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
+                }
+                c_lo = lo;
+                hi = g.pc;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (g.cidx[mid] < wcol0 + SW) lo = mid + 1; else hi = mid;
+                }
+                c_hi = lo;
+            }
+#pragma unroll
+            for (int which = 0; which < 3; ++which) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const uint32_t gw = gq[j][q][r >> 1], uw = uq[j][q][r >> 1];
+                            const float gv = (r & 1) ? hi_bf16(gw) : lo_bf16(gw);
+                            const float uv = (r & 1) ? hi_bf16(uw) : lo_bf16(uw);
+                            float dg, du, act;
+                            swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg, du, act);
+                            v[r] = which == 0 ? dg : (which == 1 ? du : act);
+                        }
+                        strip_put(32 * j, q, pack4(v[0], v[1], v[2], v[3]));
+                    }
+                strip_store(which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, nullptr, i);
+                if (g.cidx) {
+                    // compacted copy: lane t takes compact column c_lo + t, i.e. strip column cidx[c_lo + t] - wcol0
+                    uint16_t* outc = which == 0 ? g.Cc : (which == 1 ? g.Cc2 : g.Cc3);
+                    for (int t = c_lo + lane; t < c_hi; t += 64) {
+                        const int src = g.cidx[t] - wcol0;
+                        for (int row = 0; row < 32; ++row) {
+                            const int m = m0 + WM * wm + 32 * i + row;
+                            if (m < g.M) outc[(int64_t)m * g.ldcc + t] = *(const uint16_t*)(strip + row * RS + src * 2);
                         }
                     }
                 }
@@ -387,17 +460,19 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int B_KN, int EPI, int OP>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int A_KM, int EPI, int OP>
 int launch_cfg(const GemmDesc& d, hipStream_t s) {
+    using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
-    constexpr int LDS = 2 * (BM + BN) * BK * 2;
+    constexpr int LDS = Geo::LDS;
     Dev g;
     g.M = d.M, g.N = d.N, g.K = d.K;
     g.A = (const uint16_t*)d.A, g.A2 = (const uint16_t*)d.A2, g.B = (const uint16_t*)d.B, g.B2 = (const uint16_t*)d.B2;
-    g.lda = d.lda, g.ldb = d.ldb, g.ag = d.a_gather, g.bg = d.b_gather, g.cs = d.c_scatter;
+    g.lda = d.lda, g.ldb = d.ldb, g.bg = d.b_gather, g.cs = d.c_scatter;
     g.C = (uint16_t*)d.C, g.C2 = (uint16_t*)d.C2, g.C3 = (uint16_t*)d.C3, g.ldc = d.ldc;
     g.Gin = (const uint16_t*)d.Gin, g.Uin = (const uint16_t*)d.Uin, g.ldg = d.ldg;
-    g.T1 = (uint16_t*)d.T1, g.T2 = (uint16_t*)d.T2, g.T3 = (uint16_t*)d.T3, g.ldt = d.ldt;
+    g.Cc = (uint16_t*)d.Cc, g.Cc2 = (uint16_t*)d.Cc2, g.Cc3 = (uint16_t*)d.Cc3, g.ldcc = d.ldcc;
+    g.cidx = d.cidx, g.pc = d.pc;
     g.tiles_m = (d.M + BM - 1) / BM;
     const int ncols = EPI == EPI_SWIGLU_FWD ? BN / 2 : BN;
     g.tiles_n = (d.N + ncols - 1) / ncols;
@@ -408,7 +483,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     for (int z = 0; z < 3; ++z) {
         g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
     }
-    auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, B_KN, EPI, OP>;
+    auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, A_KM, EPI, OP>;
     static bool attr_set = false; // one flag per instantiation
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
@@ -430,7 +505,7 @@ double shape_cost(int M, int ncols_total, int nbatch, int bm, int bn, double pen
     return (double)rounds * bm * bn * penalty;
 }
 
-template <int B_KN, int EPI, int OP>
+template <int A_KM, int EPI, int OP>
 int launch(const GemmDesc& d, hipStream_t s) {
     // columns of tile space (gate and up interleaved double the tile columns)
     const int ncols = EPI == EPI_SWIGLU_FWD ? 2 * d.N : d.N;
@@ -441,44 +516,56 @@ int launch(const GemmDesc& d, hipStream_t s) {
     // SDP_FORCE_TILE=256|192|128 in the environment overrides the choice (tuning runs and tests)
     int force = d.force_tile;
     if (const char* e = getenv("SDP_FORCE_TILE")) force = atoi(e);
-    if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) return launch_cfg<256, 256, 2, 4, B_KN, EPI, OP>(d, s);
-    if constexpr (EPI != EPI_SWIGLU_FWD) {
-        if (force == 192 || (!force && c192 <= c128)) return launch_cfg<256, 192, 4, 2, B_KN, EPI, OP>(d, s);
+    if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) {
+        // depth-major A is read with the slower transposing LDS reads: give each wave fewer A fragments
+        if constexpr (A_KM != 0) return launch_cfg<256, 256, 4, 2, A_KM, EPI, OP>(d, s);
+        else return launch_cfg<256, 256, 2, 4, A_KM, EPI, OP>(d, s);
     }
-    return launch_cfg<128, 128, 2, 2, B_KN, EPI, OP>(d, s);
+    if constexpr (EPI != EPI_SWIGLU_FWD) {
+        if (force == 192 || (!force && c192 <= c128)) return launch_cfg<256, 192, 4, 2, A_KM, EPI, OP>(d, s);
+    }
+    return launch_cfg<128, 128, 2, 2, A_KM, EPI, OP>(d, s);
 }
 
 } // namespace
 
 bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return false;
-    // 16-byte global chunks, 16-deep MFMA steps
-    if (d.K % 16 || d.lda % 8 || d.ldb % 8) return false;
-    if (d.b_kn && d.N % 8) return false;
+    // 16-byte global chunks, 16-deep MFMA steps, 32-bit byte offsets inside each operand
+    if (d.K % 16 || d.lda % 8 || d.ldb % 8 || d.N % 8 || d.ldc % 8) return false;
+    if (d.a_km && d.M % 8) return false;
+    const int64_t a_rows = d.a_km ? d.K : d.M;
+    if (a_rows * d.lda * 2 >= ((int64_t)1 << 32)) return false;
+    if ((d.b_rows > 0 ? d.b_rows : (int64_t)d.N) * d.ldb * 2 >= ((int64_t)1 << 32)) return false;
+    if (d.b_gather && d.b_rows <= 0) return false;
     if (d.nbatch > 0) {
-        if (d.nbatch > 3 || d.epilogue != EPI_STORE || !d.b_kn) return false;
+        if (d.nbatch > 3 || d.epilogue != EPI_STORE) return false;
         for (int z = 0; z < d.nbatch; ++z)
-            if (!d.Ab[z] || !d.Bb[z] || !d.Cb[z] || !aligned16(d.Ab[z]) || !aligned16(d.Bb[z])) return false;
+            if (!d.Ab[z] || !d.Bb[z] || !d.Cb[z] || !aligned16(d.Ab[z]) || !aligned16(d.Bb[z]) || !aligned16(d.Cb[z]))
+                return false;
     } else {
-        for (const void* p : {d.A, d.B})
+        for (const void* p : {d.A, d.B, (const void*)d.C})
             if (!p || !aligned16(p)) return false;
     }
     if (d.epilogue == EPI_DUAL_ACC || d.epilogue == EPI_SWIGLU_FWD)
         if (!d.B2 || !aligned16(d.B2)) return false;
     if (d.epilogue == EPI_DUAL_ACC && (!d.A2 || !aligned16(d.A2))) return false;
-    if (d.epilogue == EPI_SWIGLU_FWD && d.b_kn) return false;
-    if (d.epilogue == EPI_SWIGLU_BWD && d.b_kn) return false;
+    if (d.epilogue == EPI_SWIGLU_FWD || d.epilogue == EPI_SWIGLU_BWD) {
+        if (d.a_km || !d.C2 || !d.C3 || !aligned16(d.C2) || !aligned16(d.C3)) return false;
+    }
+    if (d.epilogue == EPI_SWIGLU_BWD && (!d.Gin || !d.Uin || !aligned16(d.Gin) || !aligned16(d.Uin) || d.ldg % 8))
+        return false;
     return true;
 }
 
 int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
     if (!gemm_mfma_supported(d)) return SDP_ERR_UNSUPPORTED;
     // OP only gives every call site its own kernel symbol, so that profiles name the step
-    if (d.b_kn) {
+    if (d.a_km) {
         if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<1, EPI_STORE, OP_DW>(d, s);
-        if (d.epilogue == EPI_STORE) return launch<1, EPI_STORE, OP_DOWN>(d, s);
-        if (d.epilogue == EPI_DUAL_ACC) return launch<1, EPI_DUAL_ACC, OP_DX>(d, s);
     } else {
+        if (d.epilogue == EPI_STORE && d.nbatch == 0) return launch<0, EPI_STORE, OP_DOWN>(d, s);
+        if (d.epilogue == EPI_DUAL_ACC) return launch<0, EPI_DUAL_ACC, OP_DX>(d, s);
         if (d.epilogue == EPI_SWIGLU_FWD) return launch<0, EPI_SWIGLU_FWD, OP_GATE_UP>(d, s);
         if (d.epilogue == EPI_SWIGLU_BWD) return launch<0, EPI_SWIGLU_BWD, OP_DACT>(d, s);
     }

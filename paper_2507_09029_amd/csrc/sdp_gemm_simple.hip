@@ -36,15 +36,27 @@ struct Dev {
     int M, N, K;
     const void *A, *A2, *B, *B2;
     int64_t lda, ldb;
-    const int32_t *ag, *bg, *cs;
-    int b_kn;
+    const int32_t *bg, *cs;
+    int a_km;
     void *C, *C2, *C3;
     int64_t ldc;
     const void *Gin, *Uin;
     int64_t ldg;
-    void *T1, *T2, *T3;
-    int64_t ldt;
+    void *Cc, *Cc2, *Cc3;
+    int64_t ldcc;
+    const int32_t* cidx;
+    int pc;
 };
+
+// rank of column n in the ascending index list, or -1 if it is not listed
+__device__ inline int compact_rank(const int32_t* idx, int p, int n) {
+    int lo = 0, hi = p;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (idx[mid] < n) lo = mid + 1; else hi = mid;
+    }
+    return (lo < p && idx[lo] == n) ? lo : -1;
+}
 
 template <typename T, int EPI>
 __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
@@ -63,40 +75,33 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
         const T* B = (const T*)(pass ? g.B2 : g.B);
         const T* B2 = (const T*)g.B2;
         for (int k0 = 0; k0 < g.K; k0 += BK) {
-            // A tile: element e -> (m = e / BK, k = e % BK); rows contiguous along k
-            for (int e = tid; e < BM * BK; e += NT) {
-                const int m = e / BK, k = e % BK;
-                float v = 0.f;
-                if (m0 + m < g.M && k0 + k < g.K) {
-                    const int64_t row = g.ag ? g.ag[m0 + m] : (m0 + m);
-                    v = ld<T>(A + row * g.lda + k0 + k);
-                }
-                As[k][m] = v;
-            }
-            if (g.b_kn) {
-                for (int e = tid; e < BN * BK; e += NT) {
-                    const int k = e / BN, n = e % BN;
-                    float v = 0.f, v2 = 0.f;
-                    if (n0 + n < g.N && k0 + k < g.K) {
-                        const int64_t row = g.bg ? g.bg[k0 + k] : (k0 + k);
-                        v = ld<T>(B + row * g.ldb + n0 + n);
-                        if (kTwoB) v2 = ld<T>(B2 + row * g.ldb + n0 + n);
-                    }
-                    Bs[k][n] = v;
-                    if (kTwoB) B2s[k][n] = v2;
+            if (!g.a_km) {
+                // A tile: element e -> (m = e / BK, k = e % BK); rows contiguous along k
+                for (int e = tid; e < BM * BK; e += NT) {
+                    const int m = e / BK, k = e % BK;
+                    float v = 0.f;
+                    if (m0 + m < g.M && k0 + k < g.K) v = ld<T>(A + (int64_t)(m0 + m) * g.lda + k0 + k);
+                    As[k][m] = v;
                 }
             } else {
-                for (int e = tid; e < BN * BK; e += NT) {
-                    const int n = e / BK, k = e % BK;
-                    float v = 0.f, v2 = 0.f;
-                    if (n0 + n < g.N && k0 + k < g.K) {
-                        const int64_t row = g.bg ? g.bg[n0 + n] : (n0 + n);
-                        v = ld<T>(B + row * g.ldb + k0 + k);
-                        if (kTwoB) v2 = ld<T>(B2 + row * g.ldb + k0 + k);
-                    }
-                    Bs[k][n] = v;
-                    if (kTwoB) B2s[k][n] = v2;
+                // A stored [K][M]: element e -> (k = e / BM, m = e % BM)
+                for (int e = tid; e < BM * BK; e += NT) {
+                    const int k = e / BM, m = e % BM;
+                    float v = 0.f;
+                    if (m0 + m < g.M && k0 + k < g.K) v = ld<T>(A + (int64_t)(k0 + k) * g.lda + m0 + m);
+                    As[k][m] = v;
                 }
+            }
+            for (int e = tid; e < BN * BK; e += NT) {
+                const int n = e / BK, k = e % BK;
+                float v = 0.f, v2 = 0.f;
+                if (n0 + n < g.N && k0 + k < g.K) {
+                    const int64_t row = g.bg ? g.bg[n0 + n] : (n0 + n);
+                    v = ld<T>(B + row * g.ldb + k0 + k);
+                    if (kTwoB) v2 = ld<T>(B2 + row * g.ldb + k0 + k);
+                }
+                Bs[k][n] = v;
+                if (kTwoB) B2s[k][n] = v2;
             }
             __syncthreads();
 #pragma unroll
@@ -143,9 +148,15 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
                 swiglu_bwd<sizeof(T) == 4>(acc[i][j], gv, uv, dg, du, act);
                 st<T>((T*)g.C + (int64_t)m * g.ldc + n, dg);
                 st<T>((T*)g.C2 + (int64_t)m * g.ldc + n, du);
-                st<T>((T*)g.T1 + (int64_t)n * g.ldt + m, dg);
-                st<T>((T*)g.T2 + (int64_t)n * g.ldt + m, du);
-                st<T>((T*)g.T3 + (int64_t)n * g.ldt + m, act);
+                st<T>((T*)g.C3 + (int64_t)m * g.ldc + n, act);
+                if (g.cidx) {
+                    const int c = compact_rank(g.cidx, g.pc, n);
+                    if (c >= 0) {
+                        st<T>((T*)g.Cc + (int64_t)m * g.ldcc + c, dg);
+                        st<T>((T*)g.Cc2 + (int64_t)m * g.ldcc + c, du);
+                        st<T>((T*)g.Cc3 + (int64_t)m * g.ldcc + c, act);
+                    }
+                }
             }
         }
     }
@@ -153,8 +164,8 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
 
 template <typename T, int EPI>
 int launch(const GemmDesc& d, hipStream_t s) {
-    Dev g{d.M, d.N, d.K, d.A, d.A2, d.B, d.B2, d.lda, d.ldb, d.a_gather, d.b_gather, d.c_scatter, d.b_kn,
-          d.C, d.C2, d.C3, d.ldc, d.Gin, d.Uin, d.ldg, d.T1, d.T2, d.T3, d.ldt};
+    Dev g{d.M, d.N, d.K, d.A, d.A2, d.B, d.B2, d.lda, d.ldb, d.b_gather, d.c_scatter, d.a_km,
+          d.C, d.C2, d.C3, d.ldc, d.Gin, d.Uin, d.ldg, d.Cc, d.Cc2, d.Cc3, d.ldcc, d.cidx, d.pc};
     dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM);
     ProfileScope ps(d.name, s);
     gemm_simple_kernel<T, EPI><<<grid, NT, 0, s>>>(g);

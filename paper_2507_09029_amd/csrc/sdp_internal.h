@@ -30,20 +30,19 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- contraction descriptor --------------------------------------------------------------------
-// C[M][N] = sum_k A(m,k) * B(k,n), fp32 accumulation.
-//   A(m,k) = A[ra(m) * lda + k]                          (rows contiguous along k)
-//   B(k,n) = b_kn ? B[rb(k) * ldb + n] : B[rb(n) * ldb + k]
-// ra / rb are the identity when the gather pointer is null, else a lookup in an int32 table.
-// A second operand pair (A2, B2) with the same shapes, strides and gathers is used by two of the
-// epilogues below.
+// C[M][N] = sum_k A(m,k) * B(k,n), fp32 accumulation, all matrices row-major.
+//   A(m,k) = a_km ? A[k * lda + m] : A[m * lda + k]      (a_km: A is stored depth-major, [K][M])
+//   B(k,n) = B[rb(n) * ldb + k]                           (B is stored [N][K], rows contiguous along k)
+// rb is the identity when b_gather is null, else a lookup in an int32 table (active-neuron rows).
+// A second operand pair (A2, B2) with the same shapes and strides is used by two of the epilogues.
 enum Epilogue {
     EPI_STORE = 0,       // C[rc(m) * ldc + n] = acc                      (rc: optional row scatter)
     EPI_DUAL_ACC = 1,    // as STORE with acc = A.B + A2.B2
     EPI_SWIGLU_FWD = 2,  // g = A.B, u = A.B2: G = g, U = u, Act = silu(g) * u, all [M][N] (ld = ldc)
-    EPI_SWIGLU_BWD = 3   // da = A.B; with g = Gin[m][n], u = Uin[m][n]:
-                         //   dU = da silu(g), dG = da u silu'(g), act = silu(g) u
-                         //   written row-major [M][N] (dG, dU; ld = ldc) and transposed [N][M]
-                         //   (dGT, dUT, ActT; ld = ldt)
+    EPI_SWIGLU_BWD = 3   // da = A.B; with g = Gin[m][n], u = Uin[m][n]  (ld = ldg):
+                         //   dU = da silu(g), dG = da u silu'(g), act = silu(g) u, all [M][N] (ld = ldc);
+                         //   with cidx != null also the column-compacted copies [M][pc] (ld = ldcc):
+                         //   column c of Cc / Cc2 / Cc3 is column cidx[c] of dG / dU / act (cidx ascending)
 };
 
 struct GemmDesc {
@@ -51,30 +50,32 @@ struct GemmDesc {
     const void* A = nullptr;
     const void* A2 = nullptr;
     int64_t lda = 0;
-    const int32_t* a_gather = nullptr;
+    int a_km = 0;
     const void* B = nullptr;
     const void* B2 = nullptr;
     int64_t ldb = 0;
     const int32_t* b_gather = nullptr;
-    int b_kn = 0;
+    int64_t b_rows = 0; // number of rows of the stored B (bounds the gathered row index); 0 = N
     int epilogue = EPI_STORE;
     // outputs
     void* C = nullptr;  // STORE / DUAL_ACC: C.  SWIGLU_FWD: G.  SWIGLU_BWD: dG
     void* C2 = nullptr; // SWIGLU_FWD: U.  SWIGLU_BWD: dU
-    void* C3 = nullptr; // SWIGLU_FWD: Act
+    void* C3 = nullptr; // SWIGLU_FWD / SWIGLU_BWD: Act
     int64_t ldc = 0;
     const int32_t* c_scatter = nullptr;
-    // SWIGLU_BWD extra
+    // SWIGLU_BWD inputs and optional compact copies
     const void* Gin = nullptr;
     const void* Uin = nullptr;
     int64_t ldg = 0;
-    void* T1 = nullptr; // dGT
-    void* T2 = nullptr; // dUT
-    void* T3 = nullptr; // ActT
-    int64_t ldt = 0;
+    void* Cc = nullptr;
+    void* Cc2 = nullptr;
+    void* Cc3 = nullptr;
+    int64_t ldcc = 0;
+    const int32_t* cidx = nullptr;
+    int pc = 0;
     const char* name = "gemm";
-    // batched launch of up to three problems with the same shape, strides, gathers and scatter
-    // (the weight-gradient contractions): nbatch > 0 selects Ab/Bb/Cb instead of A/B/C
+    // batched launch of up to three problems with the same shape, strides and scatter (the
+    // weight-gradient contractions): nbatch > 0 selects Ab/Bb/Cb instead of A/B/C
     int nbatch = 0;
     const void* Ab[3] = {nullptr, nullptr, nullptr};
     const void* Bb[3] = {nullptr, nullptr, nullptr};
@@ -90,5 +91,9 @@ int gemm_simple(int dtype, const GemmDesc& g, hipStream_t s);
 // bf16 MFMA contraction; returns SDP_ERR_UNSUPPORTED when the shape / alignment does not fit.
 int gemm_mfma_bf16(const GemmDesc& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmDesc& g);
+
+// out[c][r] = in[rows ? rows[r] : r][c] for r < R, c < C: (gathered) transpose, element size 2 or 4.
+int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t* rows, int R, int C, void* out,
+                   int64_t ld_out, const char* name, hipStream_t s);
 
 } // namespace sdp

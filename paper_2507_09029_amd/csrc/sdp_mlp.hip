@@ -1,15 +1,21 @@
 // One worker's masked SwiGLU MLP forward and backward (the paper's Sec. 3.1 regimes applied to the
-// neuron-level masks of Sec. 3.2), expressed as a fixed sequence of contractions.
+// neuron-level masks of Sec. 3.2), expressed as a fixed sequence of contractions C = A . B^T whose
+// operands are all read depth-contiguous.
 //
-// With n = p and gather = idx_k under forward masking, n = F and no gather under backward masking:
-//   forward   gate_up : [G | U] = X . [W1 | W3][S]^T        (T x n, depth d)  + SwiGLU epilogue -> Act
-//             down    : Y  = Act . W2T[S]                    (T x d, depth n)
-//   backward  dact    : dA = dY . W2T[S]^T                   (T x n, depth d)  + SwiGLU-backward epilogue
-//                        -> dG, dU (row-major) and dG^T, dU^T, Act^T (neuron-major)
-//             dx      : dX = dG . W1[S] + dU . W3[S]         (T x d, depth 2n)
-//             dw1/3/2 : dW1[S] = dG^T . X, dW3[S] = dU^T . X, dW2T[S] = Act^T . dY   (p x d, depth T)
-// Under backward masking the three weight-gradient contractions read only rows idx_k of the
-// neuron-major dG^T, dU^T, Act^T: the gradient is computed on the worker's mask and nowhere else.
+// With n = p and S = idx_k under forward masking, n = F and S = all neurons under backward masking:
+//   forward   wt      : W2c = W2T[S]^T                       ([d][n], gather + transpose, HBM-bound)
+//             gate_up : [G | U] = X . [W1 | W3][S]^T         (T x n, depth d; rows of W1, W3 gathered in
+//                        the operand load)  + SwiGLU epilogue -> Act
+//             down    : Y  = Act . W2c^T                     (T x d, depth n)
+//   backward  wt      : W1c = W1[S]^T, W3c = W3[S]^T ([d][n]);  XT = X^T, dYT = dY^T ([d][T])
+//             dact    : dA = dY . W2T[S]^T                   (T x n, depth d; rows of W2T gathered)
+//                        + SwiGLU-backward epilogue -> dG, dU, Act [T][n]
+//                        (+ under backward masking their column-compacted copies [T][p] on the mask)
+//             dx      : dX = dG . W1c^T + dU . W3c^T         (T x d, depth 2n)
+//             dw      : dW1[S] = dG^T . X, dW3[S] = dU^T . X, dW2T[S] = Act^T . dY   (p x d, depth T),
+//                        one batched launch; the left operands are read depth-major ([T][p]).
+// Under backward masking the weight-gradient contractions read only the compacted copies: the
+// gradient is computed on the worker's mask and nowhere else.
 #include "sdp_internal.h"
 
 namespace {
@@ -38,13 +44,17 @@ int run(int dtype, const GemmDesc& g, hipStream_t s) {
 extern "C" size_t sdp_masked_mlp_fwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p) {
     if (check_common(mode, dtype, T, d, F, mode == SDP_MASK_BACKWARD ? F : p) != SDP_OK) return 0;
     const size_t n = mode == SDP_MASK_FORWARD ? p : F;
-    return round_up((size_t)T * n * esize(dtype), 256);
+    return round_up((size_t)T * n * esize(dtype), 256) + round_up((size_t)d * n * esize(dtype), 256);
 }
 
 extern "C" size_t sdp_masked_mlp_bwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p) {
     if (check_common(mode, dtype, T, d, F, p) != SDP_OK) return 0;
     const size_t n = mode == SDP_MASK_FORWARD ? p : F;
-    return 5 * round_up((size_t)T * n * esize(dtype), 256);
+    const size_t e = esize(dtype);
+    size_t bytes = 3 * round_up((size_t)T * n * e, 256) + 2 * round_up((size_t)d * n * e, 256) +
+                   2 * round_up((size_t)d * T * e, 256);
+    if (mode == SDP_MASK_BACKWARD) bytes += 3 * round_up((size_t)T * p * e, 256);
+    return bytes;
 }
 
 extern "C" int sdp_masked_mlp_fwd(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* W1,
@@ -63,21 +73,29 @@ extern "C" int sdp_masked_mlp_fwd(int mode, int dtype, int T, int d, int F, int 
     const int n = mode == SDP_MASK_FORWARD ? p : F;
     const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
 
+    const size_t e = esize(dtype);
+    char* w = (char*)ws;
+    void* Act = w;
+    void* W2c = w + round_up((size_t)T * n * e, 256);
+
+    rc = transpose_rows((int)e, W2T, d, gather, n, d, W2c, n, "mlp_wt_fwd", s);
+    if (rc != SDP_OK) return rc;
+
     GemmDesc gu;
     gu.name = "mlp_gate_up";
     gu.M = T, gu.N = n, gu.K = d;
     gu.A = X, gu.lda = d;
-    gu.B = W1, gu.B2 = W3, gu.ldb = d, gu.b_gather = gather, gu.b_kn = 0;
+    gu.B = W1, gu.B2 = W3, gu.ldb = d, gu.b_gather = gather, gu.b_rows = F;
     gu.epilogue = EPI_SWIGLU_FWD;
-    gu.C = G_save, gu.C2 = U_save, gu.C3 = ws, gu.ldc = n;
+    gu.C = G_save, gu.C2 = U_save, gu.C3 = Act, gu.ldc = n;
     rc = run(dtype, gu, s);
     if (rc != SDP_OK) return rc;
 
     GemmDesc dn;
     dn.name = "mlp_down";
     dn.M = T, dn.N = d, dn.K = n;
-    dn.A = ws, dn.lda = n;
-    dn.B = W2T, dn.ldb = d, dn.b_gather = gather, dn.b_kn = 1;
+    dn.A = Act, dn.lda = n;
+    dn.B = W2c, dn.ldb = n;
     dn.epilogue = EPI_STORE;
     dn.C = Y, dn.ldc = d;
     return run(dtype, dn, s);
@@ -101,19 +119,40 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     hipStream_t s = (hipStream_t)stream;
     const int n = mode == SDP_MASK_FORWARD ? p : F;
     const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
-    const size_t part = round_up((size_t)T * n * esize(dtype), 256);
+    const size_t e = esize(dtype);
+    const size_t act_b = round_up((size_t)T * n * e, 256), wt_b = round_up((size_t)d * n * e, 256);
+    const size_t xt_b = round_up((size_t)d * T * e, 256), cmp_b = round_up((size_t)T * p * e, 256);
     char* w = (char*)ws;
-    void *dG = w, *dU = w + part, *dGT = w + 2 * part, *dUT = w + 3 * part, *ActT = w + 4 * part;
+    void *dG = w, *dU = w + act_b, *Act = w + 2 * act_b;
+    w += 3 * act_b;
+    void *W1c = w, *W3c = w + wt_b;
+    w += 2 * wt_b;
+    void *XT = w, *dYT = w + xt_b;
+    w += 2 * xt_b;
+    void *dGc = dG, *dUc = dU, *Actc = Act; // forward masking: the tensors are compact already
+    if (mode == SDP_MASK_BACKWARD) dGc = w, dUc = w + cmp_b, Actc = w + 2 * cmp_b;
+
+    rc = transpose_rows((int)e, W1, d, gather, n, d, W1c, n, "mlp_wt_bwd", s);
+    if (rc != SDP_OK) return rc;
+    rc = transpose_rows((int)e, W3, d, gather, n, d, W3c, n, "mlp_wt_bwd", s);
+    if (rc != SDP_OK) return rc;
+    rc = transpose_rows((int)e, X, d, nullptr, T, d, XT, T, "mlp_xt", s);
+    if (rc != SDP_OK) return rc;
+    rc = transpose_rows((int)e, dY, d, nullptr, T, d, dYT, T, "mlp_xt", s);
+    if (rc != SDP_OK) return rc;
 
     GemmDesc da;
     da.name = "mlp_dact";
     da.M = T, da.N = n, da.K = d;
     da.A = dY, da.lda = d;
-    da.B = W2T, da.ldb = d, da.b_gather = gather, da.b_kn = 0;
+    da.B = W2T, da.ldb = d, da.b_gather = gather, da.b_rows = F;
     da.epilogue = EPI_SWIGLU_BWD;
     da.Gin = G_save, da.Uin = U_save, da.ldg = n;
-    da.C = dG, da.C2 = dU, da.ldc = n;
-    da.T1 = dGT, da.T2 = dUT, da.T3 = ActT, da.ldt = T;
+    da.C = dG, da.C2 = dU, da.C3 = Act, da.ldc = n;
+    if (mode == SDP_MASK_BACKWARD) {
+        da.Cc = dGc, da.Cc2 = dUc, da.Cc3 = Actc, da.ldcc = p;
+        da.cidx = idx_k, da.pc = p;
+    }
     rc = run(dtype, da, s);
     if (rc != SDP_OK) return rc;
 
@@ -121,21 +160,20 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     dx.name = "mlp_dx";
     dx.M = T, dx.N = d, dx.K = n;
     dx.A = dG, dx.A2 = dU, dx.lda = n;
-    dx.B = W1, dx.B2 = W3, dx.ldb = d, dx.b_gather = gather, dx.b_kn = 1;
+    dx.B = W1c, dx.B2 = W3c, dx.ldb = n;
     dx.epilogue = EPI_DUAL_ACC;
     dx.C = dX, dx.ldc = d;
     rc = run(dtype, dx, s);
     if (rc != SDP_OK) return rc;
 
-    const void* lhs[3] = {dGT, dUT, ActT};
-    const void* rhs[3] = {X, X, dY};
+    const void* lhs[3] = {dGc, dUc, Actc};
+    const void* rhs[3] = {XT, XT, dYT};
     void* outp[3] = {dW1, dW3, dW2T};
     GemmDesc dw;
     dw.name = "mlp_dw";
     dw.M = p, dw.N = d, dw.K = T;
-    dw.lda = T;
-    dw.a_gather = mode == SDP_MASK_BACKWARD ? idx_k : nullptr; // rows of the neuron-major operand on the mask
-    dw.ldb = d, dw.b_kn = 1;
+    dw.lda = p, dw.a_km = 1; // [T][p]: depth-major
+    dw.ldb = T;
     dw.epilogue = EPI_STORE;
     dw.ldc = d;
     dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
