@@ -75,10 +75,14 @@ struct Dev {
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
     const uint16_t *Ab[3], *Bb[3];
     uint16_t* Cb[3];
+    int debug; // timing experiments only (results are garbage): bit 0 = no operand loads, bit 3 = no epilogue
 };
 
+// two fp32 -> packed bf16, round to nearest even (the hardware's v_cvt_pk_bf16_f32)
 __device__ inline uint32_t pack_bf16(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
 }
 __device__ inline u32x2 pack4(float a, float b, float c, float d) { return u32x2{pack_bf16(a, b), pack_bf16(c, d)}; }
 __device__ inline float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
@@ -97,7 +101,8 @@ struct Geometry {
     static constexpr int SW = EPI == EPI_SWIGLU_FWD ? WN / 2 : WN;
     static constexpr int RS = SW * 2 + 8;
     static constexpr int STRIP = 32 * RS;
-    static constexpr int LDS = 2 * STAGE > NW * STRIP ? 2 * STAGE : NW * STRIP;
+    static constexpr int NSTRIP = EPI == EPI_SWIGLU_BWD ? 3 : 1; // strips per wave
+    static constexpr int LDS = 2 * STAGE > NW * NSTRIP * STRIP ? 2 * STAGE : NW * NSTRIP * STRIP;
 };
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int A_KM, int EPI, int OP>
@@ -312,7 +317,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         const int stage = kt & 1;
         SDP_WAIT_VMCNT(0);  // this wave's chunks of step kt have landed
         __syncthreads();    // everybody's have; and everybody is done reading the other stage
-        if (kt + 1 < nk) issue(kt + 1, stage ^ 1);
+        if (kt + 1 < nk && !(g.debug & 1)) issue(kt + 1, stage ^ 1);
         const unsigned char* sa = smem + stage * STAGE;
         const unsigned char* sb = sa + A_BYTES;
         // fragments of sub-step s+1 are read while the MFMAs of sub-step s run
@@ -330,17 +335,22 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // acc[i][j][4q + r] = C(m, n),  m = m0 + WM wm + 32 i + l32,
     //                               n = n0 + (column base of fragment j) + 8 q + 4 lhi + r.
     __syncthreads(); // all waves are done with the operand tiles: LDS becomes per-wave strips
+    if (g.debug & 8) return;
     constexpr int SW = Geo::SW, RS = Geo::RS;
     constexpr int CPR = SW / 8;               // 16-byte chunks per strip row
     constexpr int NCH = 32 * CPR;             // chunks per strip
-    unsigned char* strip = smem + wave * Geo::STRIP;
-    const int wcol0 = kFwd ? n0 + (WN / 2) * wn : n0 + WN * wn; // first output column of this wave's strip
+    unsigned char* strip0 = smem + wave * (Geo::NSTRIP * Geo::STRIP);
+    const int wcol0 = kFwd ? n0 + (WN / 2) * wn : n0 + WN * wn; // first output column of this wave's strips
 
-    // write one packed 8-byte group of the strip: row l32, columns cbase + 8 q + 4 lhi ..
-    auto strip_put = [&](int cbase, int q, u32x2 v) { *(u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2) = v; };
-    auto strip_get = [&](int cbase, int q) { return *(const u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2); };
+    // one packed 8-byte group of a strip: row l32, columns cbase + 8 q + 4 lhi ..
+    auto strip_put = [&](unsigned char* strip, int cbase, int q, u32x2 v) {
+        *(u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2) = v;
+    };
+    auto strip_get = [&](const unsigned char* strip, int cbase, int q) {
+        return *(const u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2);
+    };
     // strip -> global: rows of `out` (leading dimension ld), optional row scatter
-    auto strip_store = [&](uint16_t* out, int64_t ld, const int32_t* scatter, int i) {
+    auto strip_store = [&](const unsigned char* strip, uint16_t* out, int64_t ld, const int32_t* scatter, int i) {
 #pragma unroll
         for (int it = 0; it < (NCH + 63) / 64; ++it) {
             const int c = it * 64 + lane;
@@ -356,7 +366,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     };
     // global -> strip: the same chunk mapping, zero outside the matrix
-    auto strip_load = [&](const uint16_t* in, int64_t ld, int i) {
+    auto strip_load = [&](unsigned char* strip, const uint16_t* in, int64_t ld, int i) {
 #pragma unroll
         for (int it = 0; it < (NCH + 63) / 64; ++it) {
             const int c = it * 64 + lane;
@@ -370,15 +380,35 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     };
 
+    // backward masking: column range of the compacted copies that falls into this wave's strips
+    int c_lo = 0, c_hi = 0;
+    if (EPI == EPI_SWIGLU_BWD && g.cidx) {
+        int lo = 0, hi = g.pc;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
+        }
+        c_lo = lo;
+        hi = g.pc;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (g.cidx[mid] < wcol0 + SW) lo = mid + 1; else hi = mid;
+        }
+        c_hi = lo;
+    }
+
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+        // keep the scheduler from pulling the next fragment row's loads (and their registers) up here
+        __builtin_amdgcn_sched_barrier(0);
         if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    strip_put(32 * j, q, pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
-            strip_store(gC, g.ldc, g.cs, i);
+                    strip_put(strip0, 32 * j, q,
+                              pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+            strip_store(strip0, gC, g.ldc, g.cs, i);
         } else if (EPI == EPI_SWIGLU_FWD) {
             // fragments 2 jj (gate) and 2 jj + 1 (up) cover the same 32 neurons
 #pragma unroll
@@ -393,66 +423,53 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                             const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
                             v[r] = which == 0 ? gv : (which == 1 ? uv : swiglu_fwd<false>(gv, uv));
                         }
-                        strip_put(32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
+                        strip_put(strip0, 32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
                     }
-                strip_store(which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, nullptr, i);
+                strip_store(strip0, which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, nullptr, i);
             }
-        } else { // EPI_SWIGLU_BWD
+        } else { // EPI_SWIGLU_BWD: three strips per wave (dG, dU, Act)
+            unsigned char* strip1 = strip0 + Geo::STRIP;
+            unsigned char* strip2 = strip1 + Geo::STRIP;
+            strip_load(strip0, g.Gin, g.ldg, i);
+            strip_load(strip1, g.Uin, g.ldg, i);
             u32x2 gq[FN][4], uq[FN][4];
-            strip_load(g.Gin, g.ldg, i);
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) gq[j][q] = strip_get(32 * j, q);
-            strip_load(g.Uin, g.ldg, i);
+                for (int q = 0; q < 4; ++q) {
+                    gq[j][q] = strip_get(strip0, 32 * j, q);
+                    uq[j][q] = strip_get(strip1, 32 * j, q);
+                }
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) uq[j][q] = strip_get(32 * j, q);
-            // column range of the compacted copies that falls into this wave's strip
-            int c_lo = 0, c_hi = 0;
-            if (g.cidx) {
-                int lo = 0, hi = g.pc;
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
-                }
-                c_lo = lo;
-                hi = g.pc;
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if (g.cidx[mid] < wcol0 + SW) lo = mid + 1; else hi = mid;
-                }
-                c_hi = lo;
-            }
+                for (int q = 0; q < 4; ++q) {
+                    float dg[4], du[4], act[4];
 #pragma unroll
-            for (int which = 0; which < 3; ++which) {
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float v[4];
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const uint32_t gw = gq[j][q][r >> 1], uw = uq[j][q][r >> 1];
-                            const float gv = (r & 1) ? hi_bf16(gw) : lo_bf16(gw);
-                            const float uv = (r & 1) ? hi_bf16(uw) : lo_bf16(uw);
-                            float dg, du, act;
-                            swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg, du, act);
-                            v[r] = which == 0 ? dg : (which == 1 ? du : act);
-                        }
-                        strip_put(32 * j, q, pack4(v[0], v[1], v[2], v[3]));
+                    for (int r = 0; r < 4; ++r) {
+                        const uint32_t gw = gq[j][q][r >> 1], uw = uq[j][q][r >> 1];
+                        const float gv = (r & 1) ? hi_bf16(gw) : lo_bf16(gw);
+                        const float uv = (r & 1) ? hi_bf16(uw) : lo_bf16(uw);
+                        swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg[r], du[r], act[r]);
                     }
-                strip_store(which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, nullptr, i);
-                if (g.cidx) {
-                    // compacted copy: lane t takes compact column c_lo + t, i.e. strip column cidx[c_lo + t] - wcol0
-                    uint16_t* outc = which == 0 ? g.Cc : (which == 1 ? g.Cc2 : g.Cc3);
-                    for (int t = c_lo + lane; t < c_hi; t += 64) {
-                        const int src = g.cidx[t] - wcol0;
-                        for (int row = 0; row < 32; ++row) {
-                            const int m = m0 + WM * wm + 32 * i + row;
-                            if (m < g.M) outc[(int64_t)m * g.ldcc + t] = *(const uint16_t*)(strip + row * RS + src * 2);
-                        }
+                    strip_put(strip0, 32 * j, q, pack4(dg[0], dg[1], dg[2], dg[3]));
+                    strip_put(strip1, 32 * j, q, pack4(du[0], du[1], du[2], du[3]));
+                    strip_put(strip2, 32 * j, q, pack4(act[0], act[1], act[2], act[3]));
+                }
+            strip_store(strip0, g.C, g.ldc, nullptr, i);
+            strip_store(strip1, g.C2, g.ldc, nullptr, i);
+            strip_store(strip2, g.C3, g.ldc, nullptr, i);
+            if (g.cidx) {
+                // compacted copies: lane t takes compact column c_lo + t = strip column cidx[c_lo + t] - wcol0
+                for (int t = c_lo + lane; t < c_hi; t += 64) {
+                    const int src = (g.cidx[t] - wcol0) * 2;
+                    for (int row = 0; row < 32; ++row) {
+                        const int m = m0 + WM * wm + 32 * i + row;
+                        if (m >= g.M) break;
+                        const int64_t o = (int64_t)m * g.ldcc + t;
+                        g.Cc[o] = *(const uint16_t*)(strip0 + row * RS + src);
+                        g.Cc2[o] = *(const uint16_t*)(strip1 + row * RS + src);
+                        g.Cc3[o] = *(const uint16_t*)(strip2 + row * RS + src);
                     }
                 }
             }
@@ -483,6 +500,8 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     for (int z = 0; z < 3; ++z) {
         g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
     }
+    g.debug = 0;
+    if (const char* e = getenv("SDP_DEBUG_TIMING")) g.debug = atoi(e);
     auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, A_KM, EPI, OP>;
     static bool attr_set = false; // one flag per instantiation
     if (!attr_set) {
