@@ -11,6 +11,46 @@
 namespace sdp {
 namespace {
 
+// 16-bit elements, 16-byte accesses on both sides.  Tile: 64 input rows x 64 columns.
+// Requires C % 8 == 0, R % 8 == 0, ld_in % 8 == 0, ld_out % 8 == 0 and 16-byte aligned bases.
+__global__ __launch_bounds__(256) void transpose_rows_vec_kernel(const uint16_t* __restrict__ in, int64_t ld_in,
+                                                                 const int32_t* __restrict__ rows, int R, int C,
+                                                                 uint16_t* __restrict__ out, int64_t ld_out) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    // tile[r][c], rows padded to 66 elements (33 words): a column walk hits 64 distinct banks
+    __shared__ uint32_t tile[64 * 33];
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int t = threadIdx.x;
+    // load: 64 rows x 8 chunks of 8 elements; thread -> rows t/8 and t/8 + 32, chunk t%8
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = (t >> 3) + 32 * h, cc = t & 7;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r0 + r < R && c0 + cc * 8 < C) {
+            const int64_t src = rows ? rows[r0 + r] : (r0 + r);
+            v = *(const u32x4*)(in + src * ld_in + c0 + cc * 8);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[r * 33 + cc * 4 + e] = v[e];
+    }
+    __syncthreads();
+    // store: 64 output rows (columns c) x 8 chunks of 8 input rows; thread -> columns t/8 and t/8 + 32
+    const uint16_t* th = (const uint16_t*)tile;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int c = (t >> 3) + 32 * h, rc = t & 7;
+        if (c0 + c < C && r0 + rc * 8 < R) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = th[(rc * 8 + 2 * e) * 66 + c], hi = th[(rc * 8 + 2 * e + 1) * 66 + c];
+                w[e] = lo | (hi << 16);
+            }
+            *(u32x4*)(out + (int64_t)(c0 + c) * ld_out + r0 + rc * 8) = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_rows_kernel(const T* __restrict__ in, int64_t ld_in,
                                                              const int32_t* __restrict__ rows, int R, int C,
@@ -42,7 +82,11 @@ int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t*
     dim3 grid((R + 63) / 64, (C + 63) / 64);
     if (grid.y > 65535) return SDP_ERR_SHAPE;
     ProfileScope ps(name, s);
-    if (elem_bytes == 2)
+    const bool vec = elem_bytes == 2 && C % 8 == 0 && R % 8 == 0 && ld_in % 8 == 0 && ld_out % 8 == 0 && aligned16(in) &&
+                     aligned16(out);
+    if (vec)
+        transpose_rows_vec_kernel<<<grid, 256, 0, s>>>((const uint16_t*)in, ld_in, rows, R, C, (uint16_t*)out, ld_out);
+    else if (elem_bytes == 2)
         transpose_rows_kernel<uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)in, ld_in, rows, R, C, (uint16_t*)out, ld_out);
     else
         transpose_rows_kernel<uint32_t><<<grid, 256, 0, s>>>((const uint32_t*)in, ld_in, rows, R, C, (uint32_t*)out, ld_out);
