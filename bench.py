@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-grad-avg-1b", action="store_true", help="skip the 1B-parameter average measurement")
     ap.add_argument("--avg-steps", type=int, default=20)
     ap.add_argument("--events", type=int, default=1, help="1: per-kernel HIP events recorded during the timed steps")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the K simulated workers are spread over (worker k on stream k %% S)")
     return ap.parse_args()
 
 
@@ -131,32 +133,45 @@ def main():
     mask, idx, pos, cov = sdp.make_masks(w.K, w.F, w.p, w.mask_seed, True)
     row_mask = mask.repeat(1, 3).contiguous()
     n = w.p if w.mode == "fm" else w.F
-    Y = torch.empty((w.T, w.d), dtype=tdt, device=dev)
-    G = torch.empty((w.T, n), dtype=tdt, device=dev)
-    U = torch.empty((w.T, n), dtype=tdt, device=dev)
-    dX = torch.empty((w.T, w.d), dtype=tdt, device=dev)
+    S = max(1, min(a.streams, w.K))
+    main = torch.cuda.current_stream()
+    streams = [main] + [torch.cuda.Stream() for _ in range(S - 1)]  # default priority
+    per = []
+    for _ in range(S):
+        per.append(dict(
+            Y=torch.empty((w.T, w.d), dtype=tdt, device=dev), G=torch.empty((w.T, n), dtype=tdt, device=dev),
+            U=torch.empty((w.T, n), dtype=tdt, device=dev), dX=torch.empty((w.T, w.d), dtype=tdt, device=dev),
+            ws_f=torch.empty(sdp.masked_mlp_fwd_workspace_bytes(w.mode, tdt, w.T, w.d, w.F, w.p), dtype=torch.uint8, device=dev),
+            ws_b=torch.empty(sdp.masked_mlp_bwd_workspace_bytes(w.mode, tdt, w.T, w.d, w.F, w.p), dtype=torch.uint8, device=dev)))
     bufs = [torch.zeros((3 * w.F, w.d), dtype=tdt, device=dev) for _ in range(w.K)]
     avg = torch.empty((3 * w.F, w.d), dtype=torch.float32, device=dev)
     avg_cov = torch.empty((3 * w.F,), dtype=torch.uint8, device=dev)
-    ws_f = torch.empty(sdp.masked_mlp_fwd_workspace_bytes(w.mode, tdt, w.T, w.d, w.F, w.p), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(sdp.masked_mlp_bwd_workspace_bytes(w.mode, tdt, w.T, w.d, w.F, w.p), dtype=torch.uint8, device=dev)
     ws_i = torch.empty(max(sdp.index_masks_workspace_bytes(w.K, w.F), 256), dtype=torch.uint8, device=dev)
     idx2 = torch.empty_like(idx)
     pos2 = torch.empty_like(pos)
     cnt2 = torch.empty((w.K,), dtype=torch.int32, device=dev)
     cov2 = torch.empty_like(cov)
     L = sdp.lib()
-    stream = torch.cuda.current_stream().cuda_stream
+    ev_idx = torch.cuda.Event()
+    ev_done = [torch.cuda.Event() for _ in range(S)]
 
     def step():
         st = L.sdp_index_masks(w.K, w.F, mask.data_ptr(), idx2.data_ptr(), w.p, pos2.data_ptr(), cnt2.data_ptr(),
-                               cov2.data_ptr(), ws_i.data_ptr(), ws_i.numel(), stream)
+                               cov2.data_ptr(), ws_i.data_ptr(), ws_i.numel(), main.cuda_stream)
         assert st == 0, st
+        if S > 1:
+            ev_idx.record(main)
         for k in range(w.K):
-            b = bufs[k]
-            sdp.masked_mlp_fwd(w.mode, Xs[k], *Wd, idx2[k], out=(Y, G, U), ws=ws_f)
-            sdp.masked_mlp_bwd(w.mode, Xs[k], dYs[k], *Wd, idx2[k], G, U, dw_layout="scatter",
-                               out=(dX, b[: w.F], b[w.F: 2 * w.F], b[2 * w.F:]), ws=ws_b)
+            b, q = bufs[k], per[k % S]
+            with torch.cuda.stream(streams[k % S]):
+                if S > 1 and k < S and k % S != 0:
+                    streams[k % S].wait_event(ev_idx)
+                sdp.masked_mlp_fwd(w.mode, Xs[k], *Wd, idx2[k], out=(q["Y"], q["G"], q["U"]), ws=q["ws_f"])
+                sdp.masked_mlp_bwd(w.mode, Xs[k], dYs[k], *Wd, idx2[k], q["G"], q["U"], dw_layout="scatter",
+                                   out=(q["dX"], b[: w.F], b[w.F: 2 * w.F], b[2 * w.F:]), ws=q["ws_b"])
+        for i in range(1, S):
+            ev_done[i].record(streams[i])
+            main.wait_event(ev_done[i])
         sdp.coverage_grad_avg(bufs, row_mask, out=avg, cov=avg_cov)
 
     for _ in range(a.warmup):
@@ -198,12 +213,12 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "mode": w.mode, "tokens": w.T, "d_model": w.d, "d_ff": w.F, "active_neurons": w.p,
-                   "workers_simulated": w.K, "active_flop_per_step": flop_step},
+                   "workers_simulated": w.K, "active_flop_per_step": flop_step, "streams": S},
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
         "roofline": roofline, "kernels": kernels,
     }
     if not a.no_grad_avg_1b:
-        del Xs, dYs, bufs, avg, ws_b, ws_f
+        del Xs, dYs, bufs, avg, per
         torch.cuda.empty_cache()
         rec["grad_avg"] = bench_grad_avg_1b(sdp, torch, a.avg_steps)
     if not a.no_cpu_baseline:

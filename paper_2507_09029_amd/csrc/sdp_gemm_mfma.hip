@@ -583,6 +583,7 @@ int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
     if (d.a_km) {
         if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<1, EPI_STORE, OP_DW>(d, s);
     } else {
+        if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<0, EPI_STORE, OP_DW>(d, s);
         if (d.epilogue == EPI_STORE && d.nbatch == 0) return launch<0, EPI_STORE, OP_DOWN>(d, s);
         if (d.epilogue == EPI_DUAL_ACC) return launch<0, EPI_DUAL_ACC, OP_DX>(d, s);
         if (d.epilogue == EPI_SWIGLU_FWD) return launch<0, EPI_SWIGLU_FWD, OP_GATE_UP>(d, s);

@@ -24,6 +24,11 @@ using namespace sdp;
 
 size_t esize(int dtype) { return dtype == SDP_F32 ? 4 : 2; }
 
+// Leading dimension of the token-contiguous copies X^T, dY^T [d][T]: T plus 64 elements, so that
+// consecutive rows do not sit a power of two apart (rows 2^k bytes apart fall onto the same memory
+// channels, and a depth step touches one 128-byte piece of each of 192-256 rows).
+int64_t ld_tokens(int T) { return (int64_t)T + 64; }
+
 int check_common(int mode, int dtype, int T, int d, int F, int p) {
     if (mode != SDP_MASK_FORWARD && mode != SDP_MASK_BACKWARD) return SDP_ERR_INVALID_ARG;
     if (dtype != SDP_F32 && dtype != SDP_BF16) return SDP_ERR_INVALID_ARG;
@@ -52,8 +57,9 @@ extern "C" size_t sdp_masked_mlp_bwd_workspace_bytes(int mode, int dtype, int T,
     const size_t n = mode == SDP_MASK_FORWARD ? p : F;
     const size_t e = esize(dtype);
     size_t bytes = 3 * round_up((size_t)T * n * e, 256) + 2 * round_up((size_t)d * n * e, 256) +
-                   2 * round_up((size_t)d * T * e, 256);
+                   2 * round_up((size_t)d * ld_tokens(T) * e, 256);
     if (mode == SDP_MASK_BACKWARD) bytes += 3 * round_up((size_t)T * p * e, 256);
+    bytes += 3 * round_up((size_t)p * ld_tokens(T) * e, 256); // neuron-major copies of dG, dU, Act on the mask
     return bytes;
 }
 
@@ -121,7 +127,7 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
     const size_t e = esize(dtype);
     const size_t act_b = round_up((size_t)T * n * e, 256), wt_b = round_up((size_t)d * n * e, 256);
-    const size_t xt_b = round_up((size_t)d * T * e, 256), cmp_b = round_up((size_t)T * p * e, 256);
+    const size_t xt_b = round_up((size_t)d * ld_tokens(T) * e, 256), cmp_b = round_up((size_t)T * p * e, 256);
     char* w = (char*)ws;
     void *dG = w, *dU = w + act_b, *Act = w + 2 * act_b;
     w += 3 * act_b;
@@ -130,15 +136,20 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     void *XT = w, *dYT = w + xt_b;
     w += 2 * xt_b;
     void *dGc = dG, *dUc = dU, *Actc = Act; // forward masking: the tensors are compact already
-    if (mode == SDP_MASK_BACKWARD) dGc = w, dUc = w + cmp_b, Actc = w + 2 * cmp_b;
+    if (mode == SDP_MASK_BACKWARD) {
+        dGc = w, dUc = w + cmp_b, Actc = w + 2 * cmp_b;
+        w += 3 * cmp_b;
+    }
+    const size_t nm_b = round_up((size_t)p * ld_tokens(T) * e, 256);
+    void *dGn = w, *dUn = w + nm_b, *Actn = w + 2 * nm_b; // [p][T(+pad)]: neuron-major
 
     rc = transpose_rows((int)e, W1, d, gather, n, d, W1c, n, "mlp_wt_bwd", s);
     if (rc != SDP_OK) return rc;
     rc = transpose_rows((int)e, W3, d, gather, n, d, W3c, n, "mlp_wt_bwd", s);
     if (rc != SDP_OK) return rc;
-    rc = transpose_rows((int)e, X, d, nullptr, T, d, XT, T, "mlp_xt", s);
+    rc = transpose_rows((int)e, X, d, nullptr, T, d, XT, ld_tokens(T), "mlp_xt", s);
     if (rc != SDP_OK) return rc;
-    rc = transpose_rows((int)e, dY, d, nullptr, T, d, dYT, T, "mlp_xt", s);
+    rc = transpose_rows((int)e, dY, d, nullptr, T, d, dYT, ld_tokens(T), "mlp_xt", s);
     if (rc != SDP_OK) return rc;
 
     GemmDesc da;
@@ -172,18 +183,26 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     GemmDesc dw;
     dw.name = "mlp_dw";
     dw.M = p, dw.N = d, dw.K = T;
-    dw.lda = p, dw.a_km = 1; // [T][p]: depth-major
-    dw.ldb = T;
+    dw.ldb = ld_tokens(T);
     dw.epilogue = EPI_STORE;
     dw.ldc = d;
     dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
+    // bf16, aligned shapes: the three left operands are first transposed to neuron-major [p][T] (one
+    // HBM-bound launch), so that the contraction reads both operands depth-contiguous with plain 16-byte
+    // LDS reads; one batched MFMA launch then computes the three gradients.
     dw.nbatch = 3;
-    for (int i = 0; i < 3; ++i) dw.Ab[i] = lhs[i], dw.Bb[i] = rhs[i], dw.Cb[i] = outp[i];
-    if (dtype == SDP_BF16 && gemm_mfma_supported(dw)) {
-        rc = gemm_mfma_bf16(dw, s); // one launch for the three
+    dw.lda = ld_tokens(T), dw.a_km = 0;
+    void* nmaj[3] = {dGn, dUn, Actn};
+    for (int i = 0; i < 3; ++i) dw.Ab[i] = nmaj[i], dw.Bb[i] = rhs[i], dw.Cb[i] = outp[i];
+    if (dtype == SDP_BF16 && gemm_mfma_supported(dw) && p % 8 == 0 && T % 8 == 0) {
+        rc = transpose3_bf16(lhs, p, T, p, nmaj, ld_tokens(T), "mlp_nt", s);
+        if (rc != SDP_OK) return rc;
+        rc = gemm_mfma_bf16(dw, s);
         if (rc != SDP_OK) return rc;
     } else {
+        // plain path: read the left operands depth-major ([T][p]) as they are
         dw.nbatch = 0;
+        dw.lda = p, dw.a_km = 1;
         for (int i = 0; i < 3; ++i) {
             dw.A = lhs[i], dw.B = rhs[i], dw.C = outp[i];
             rc = gemm_simple(dtype, dw, s);

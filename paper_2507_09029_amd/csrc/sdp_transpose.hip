@@ -13,10 +13,17 @@ namespace {
 
 // 16-bit elements, 16-byte accesses on both sides.  Tile: 64 input rows x 64 columns.
 // Requires C % 8 == 0, R % 8 == 0, ld_in % 8 == 0, ld_out % 8 == 0 and 16-byte aligned bases.
-__global__ __launch_bounds__(256) void transpose_rows_vec_kernel(const uint16_t* __restrict__ in, int64_t ld_in,
+struct Batch3 {
+    const uint16_t* in[3];
+    uint16_t* out[3];
+};
+
+__global__ __launch_bounds__(256) void transpose_rows_vec_kernel(Batch3 b, int64_t ld_in,
                                                                  const int32_t* __restrict__ rows, int R, int C,
-                                                                 uint16_t* __restrict__ out, int64_t ld_out) {
+                                                                 int64_t ld_out) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const uint16_t* __restrict__ in = blockIdx.z == 0 ? b.in[0] : (blockIdx.z == 1 ? b.in[1] : b.in[2]);
+    uint16_t* __restrict__ out = blockIdx.z == 0 ? b.out[0] : (blockIdx.z == 1 ? b.out[1] : b.out[2]);
     // tile[r][c], rows padded to 66 elements (33 words): a column walk hits 64 distinct banks
     __shared__ uint32_t tile[64 * 33];
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
@@ -84,12 +91,28 @@ int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t*
     ProfileScope ps(name, s);
     const bool vec = elem_bytes == 2 && C % 8 == 0 && R % 8 == 0 && ld_in % 8 == 0 && ld_out % 8 == 0 && aligned16(in) &&
                      aligned16(out);
-    if (vec)
-        transpose_rows_vec_kernel<<<grid, 256, 0, s>>>((const uint16_t*)in, ld_in, rows, R, C, (uint16_t*)out, ld_out);
-    else if (elem_bytes == 2)
+    if (vec) {
+        Batch3 b{{(const uint16_t*)in, nullptr, nullptr}, {(uint16_t*)out, nullptr, nullptr}};
+        transpose_rows_vec_kernel<<<grid, 256, 0, s>>>(b, ld_in, rows, R, C, ld_out);
+    } else if (elem_bytes == 2)
         transpose_rows_kernel<uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)in, ld_in, rows, R, C, (uint16_t*)out, ld_out);
     else
         transpose_rows_kernel<uint32_t><<<grid, 256, 0, s>>>((const uint32_t*)in, ld_in, rows, R, C, (uint32_t*)out, ld_out);
+    return launch_status();
+}
+
+// Three transposes of the same shape in one launch (bf16, vector path only: the caller checks).
+int transpose3_bf16(const void* const in[3], int64_t ld_in, int R, int C, void* const out[3], int64_t ld_out,
+                    const char* name, hipStream_t s) {
+    if (R < 1 || C < 1 || C % 8 || R % 8 || ld_in % 8 || ld_out % 8) return SDP_ERR_SHAPE;
+    for (int i = 0; i < 3; ++i)
+        if (!in[i] || !out[i] || !aligned16(in[i]) || !aligned16(out[i])) return SDP_ERR_INVALID_ARG;
+    dim3 grid((R + 63) / 64, (C + 63) / 64, 3);
+    if (grid.y > 65535) return SDP_ERR_SHAPE;
+    Batch3 b{{(const uint16_t*)in[0], (const uint16_t*)in[1], (const uint16_t*)in[2]},
+             {(uint16_t*)out[0], (uint16_t*)out[1], (uint16_t*)out[2]}};
+    ProfileScope ps(name, s);
+    transpose_rows_vec_kernel<<<grid, 256, 0, s>>>(b, ld_in, nullptr, R, C, ld_out);
     return launch_status();
 }
 
