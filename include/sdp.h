@@ -156,8 +156,12 @@ int sdp_coverage_grad_avg(int K, int64_t R, int D, int gdtype, const void* const
  * kernel names, the launch count and total milliseconds since the last reset.
  *   names  host array of cap pointers, set to static strings owned by the library
  *   calls, ms host arrays of cap entries.   Returns the number of entries filled, or < 0.
+ * sdp_profile_filter(name) restricts the bracketing to launches of that one kernel name (NULL or ""
+ * = all): events between back-to-back kernels keep them from overlapping their launch and drain
+ * phases, so timing every kernel slows a step by about a tenth; timing one kernel does not.
  * ------------------------------------------------------------------------------------------- */
 int sdp_profile_enable(int on);
+int sdp_profile_filter(const char* name);
 int sdp_profile_reset(void);
 int sdp_profile_read(int cap, const char** names, int64_t* calls, double* ms);
 

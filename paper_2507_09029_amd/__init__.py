@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     masked_mlp_fwd,
     masked_mlp_fwd_workspace_bytes,
     profile_enable,
+    profile_filter,
     profile_read,
     profile_reset,
     sample_masks_host,

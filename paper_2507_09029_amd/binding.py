@@ -68,6 +68,8 @@ def lib():
     L.sdp_coverage_grad_avg.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp]
     L.sdp_profile_enable.restype = i32
     L.sdp_profile_enable.argtypes = [i32]
+    L.sdp_profile_filter.restype = i32
+    L.sdp_profile_filter.argtypes = [ctypes.c_char_p]
     L.sdp_profile_reset.restype = i32
     L.sdp_profile_reset.argtypes = []
     L.sdp_profile_read.restype = i32
@@ -219,6 +221,11 @@ def coverage_grad_avg(grads, mask, out=None, cov=None):
 
 def profile_enable(on=True):
     _check(lib().sdp_profile_enable(int(bool(on))), "sdp_profile_enable")
+
+
+def profile_filter(name=None):
+    """Time only launches of kernel `name` (None: every kernel)."""
+    _check(lib().sdp_profile_filter(name.encode() if name else None), "sdp_profile_filter")
 
 
 def profile_reset():

@@ -20,6 +20,7 @@ std::vector<Pending> g_pending;
 std::vector<hipEvent_t> g_free;
 std::map<std::string, std::pair<int64_t, double>> g_totals; // name -> (calls, ms)
 std::vector<const char*> g_names;                            // insertion order, static strings
+std::string g_filter;                                        // empty = every kernel
 
 hipEvent_t take_event() {
     if (!g_free.empty()) {
@@ -56,6 +57,12 @@ void drain_locked() {
 
 bool profiling_on() { return g_on; }
 
+bool profiling_wants(const char* name) {
+    if (!g_on) return false;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return g_filter.empty() || g_filter == name;
+}
+
 void profile_begin(const char* name, hipStream_t s) {
     std::lock_guard<std::mutex> lk(g_mu);
     Pending p{name, take_event(), take_event()};
@@ -88,6 +95,12 @@ extern "C" const char* sdp_status_string(int status) {
 extern "C" int sdp_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(sdp::g_mu);
     sdp::g_on = on != 0;
+    return SDP_OK;
+}
+
+extern "C" int sdp_profile_filter(const char* name) {
+    std::lock_guard<std::mutex> lk(sdp::g_mu);
+    sdp::g_filter = name ? name : "";
     return SDP_OK;
 }
 

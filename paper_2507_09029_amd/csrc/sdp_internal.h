@@ -9,13 +9,14 @@ namespace sdp {
 
 // ---- per-kernel event timing (sdp_profile_*) -------------------------------------------------
 bool profiling_on();
+bool profiling_wants(const char* name); // on, and `name` passes the filter
 void profile_begin(const char* name, hipStream_t s);
 void profile_end(hipStream_t s);
 
 struct ProfileScope {
     hipStream_t s;
     bool on;
-    ProfileScope(const char* name, hipStream_t stream) : s(stream), on(profiling_on()) {
+    ProfileScope(const char* name, hipStream_t stream) : s(stream), on(profiling_on() && profiling_wants(name)) {
         if (on) profile_begin(name, s);
     }
     ~ProfileScope() {
