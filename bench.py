@@ -23,6 +23,20 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s)
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak (published: 8 TB/s)
 
+# HBM-side bytes per launch, from rocprofv3 counter runs (FETCH_SIZE, then WRITE_SIZE, each scaled by
+# what the same counter reads for a 1 GiB copy); the summaries with their commands are
+# profiles/mlp_config2_hbm_traffic.md and profiles/coverage_grad_avg_config5_hbm_traffic.md.
+# Counters cannot be read from inside this process, so these are recorded values for the named
+# workload and launch configuration; any other workload reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("config2_bf16_fm_500M", "mlp_gate_up"): 151.2e6 + 100.9e6,
+    ("config2_bf16_fm_500M", "mlp_down"): 84.0e6 + 25.2e6,
+    ("config2_bf16_fm_500M", "mlp_dact"): 143.2e6 + 100.7e6,
+    ("config2_bf16_fm_500M", "mlp_dx"): 167.9e6 + 25.2e6,
+    ("config2_bf16_fm_500M", "mlp_dw"): 403.2e6 + 18.9e6,
+    ("config5_avg_1B", "coverage_grad_avg"): 11.071e9 + 4.293e9,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -101,7 +115,7 @@ def bench_grad_avg_1b(sdp, torch, steps):
         "algorithmic_bytes": c.algorithmic_bytes, "ms_per_call": kern * 1e3, "ms_per_call_wall": wall * 1e3,
         "value": gbs, "unit": "GB/s",
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((c.name, "coverage_grad_avg"))},
     }
 
 
@@ -251,7 +265,10 @@ def main():
         avg_ms = ms / calls
         ach = flops_per_launch(dominant, w) / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dominant, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_launch_ms": avg_ms,
+                    "frac": ach / PEAK_BF16_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)) if S == 1 else None,
+                    "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, recorded)",
+                    "avg_launch_ms": avg_ms,
                     "launches_timed": calls, "flop_per_launch": flops_per_launch(dominant, w),
                     "share_of_step": ms / a.steps / ms_per_step}
 

@@ -31,7 +31,8 @@
 //
 // Workgroup -> tile mapping is XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs
 // (each with its own L2), so ids are first regrouped per XCD and each XCD then walks a compact
-// block of tiles (GROUP_M tile-rows at a time) whose operand tiles are shared through that L2.
+// block of tiles (the problems of a batch, then group_m tile-rows at a time, group_m chosen on the
+// host per shape) whose operand tiles are shared through that L2.
 //
 // Batching: the three weight-gradient contractions of one worker (same M x N x K, different operands)
 // run as one launch of 3 x tiles workgroups, so that their few, deep tiles fill the CUs together.
@@ -56,7 +57,6 @@ typedef __attribute__((address_space(1))) const void* glb_void_ptr;
 
 constexpr int BK = 64;
 constexpr int NUM_XCD = 8;
-constexpr int GROUP_M = 8;
 
 struct Dev {
     int M, N, K;
@@ -71,7 +71,8 @@ struct Dev {
     int64_t ldcc;
     const int32_t* cidx;
     int pc;
-    int tiles_m, tiles_n, ntiles;
+    int tiles_m, tiles_n, ntot; // ntot = tiles of all problems of the launch
+    int group_m, nbatch;
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
     const uint16_t *Ab[3], *Bb[3];
     uint16_t* Cb[3];
@@ -125,9 +126,29 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     const int l32 = lane & 31, lhi = lane >> 5;
 
     // ---- workgroup -> (problem of the batch, tile), XCD-aware ----
+    // Ids congruent mod 8 share an XCD: XCD x is given the contiguous range [start_x, start_x + count_x)
+    // of a linear order in which the problems of a batch vary fastest, then group_m tile-rows, then the
+    // tile-columns: the tiles that run together on one XCD then form a compact block of (problems x
+    // tile-rows x tile-columns) whose operand rows are fetched into that XCD's L2 once.
     int bid = blockIdx.x;
-    const int batch = bid / g.ntiles;
-    bid -= batch * g.ntiles;
+    {
+        const int x = bid % NUM_XCD, j = bid / NUM_XCD;
+        const int base = g.ntot / NUM_XCD, rem = g.ntot % NUM_XCD;
+        bid = x * base + (x < rem ? x : rem) + j;
+    }
+    const int nb = OP == OP_DW ? g.nbatch : 1;
+    int tile_m, tile_n, batch;
+    {
+        const int per_group = g.group_m * g.tiles_n * nb;
+        const int grp = bid / per_group;
+        const int first_m = grp * g.group_m;
+        const int gm = g.tiles_m - first_m < g.group_m ? g.tiles_m - first_m : g.group_m;
+        int in = bid - grp * per_group;
+        batch = in % nb;
+        in /= nb;
+        tile_m = first_m + in % gm;
+        tile_n = in / gm;
+    }
     const uint16_t* gA = g.A;
     const uint16_t* gB = g.B;
     uint16_t* gC = g.C;
@@ -135,22 +156,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         gA = batch == 0 ? g.Ab[0] : (batch == 1 ? g.Ab[1] : g.Ab[2]);
         gB = batch == 0 ? g.Bb[0] : (batch == 1 ? g.Bb[1] : g.Bb[2]);
         gC = batch == 0 ? g.Cb[0] : (batch == 1 ? g.Cb[1] : g.Cb[2]);
-    }
-    {
-        // ids congruent mod 8 share an XCD: give XCD x the contiguous range [start_x, start_x + count_x)
-        const int x = bid % NUM_XCD, j = bid / NUM_XCD;
-        const int base = g.ntiles / NUM_XCD, rem = g.ntiles % NUM_XCD;
-        bid = x * base + (x < rem ? x : rem) + j;
-    }
-    int tile_m, tile_n;
-    {
-        const int per_group = GROUP_M * g.tiles_n;
-        const int grp = bid / per_group;
-        const int first_m = grp * GROUP_M;
-        const int gm = g.tiles_m - first_m < GROUP_M ? g.tiles_m - first_m : GROUP_M;
-        const int in = bid - grp * per_group;
-        tile_m = first_m + in % gm;
-        tile_n = in / gm;
     }
     const int m0 = tile_m * BM;
     const int n0 = kFwd ? tile_n * (BN / 2) : tile_n * BN; // SWIGLU_FWD: BN columns = BN/2 neurons x {gate, up}
@@ -477,6 +482,29 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     }
 }
 
+constexpr int kNumCU = 256;
+
+// Tile-rows per group of the workgroup -> tile order: the tiles resident on one XCD at a time (its
+// share of the launch, at most one per CU) form a block of nbatch x group_m x columns; pick the
+// group_m for which that block touches the fewest distinct operand rows (A rows weigh na operands,
+// B rows nb), i.e. the least traffic into that XCD's L2.
+int choose_group_m(int tiles_m, int tiles_n, int nbatch, int na, int nb, int bm, int bn) {
+    const int64_t ntot = (int64_t)tiles_m * tiles_n * nbatch;
+    const int per_xcd = kNumCU / NUM_XCD;
+    int64_t c = (ntot + NUM_XCD - 1) / NUM_XCD;
+    if (c > per_xcd) c = per_xcd;
+    int best = 1;
+    int64_t best_cost = -1;
+    for (int gm = 1; gm <= tiles_m && gm <= per_xcd; ++gm) {
+        const int64_t cols = (c + (int64_t)nbatch * gm - 1) / ((int64_t)nbatch * gm); // tile-columns the block needs
+        const int64_t groups = (cols + tiles_n - 1) / tiles_n;
+        const int64_t ncols = cols < tiles_n ? cols : tiles_n;
+        const int64_t cost = (int64_t)na * gm * groups * bm + (int64_t)nb * ncols * bn;
+        if (best_cost < 0 || cost < best_cost) best_cost = cost, best = gm;
+    }
+    return best;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int A_KM, int EPI, int OP>
 int launch_cfg(const GemmDesc& d, hipStream_t s) {
     using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
@@ -496,10 +524,22 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     const int64_t ntiles = (int64_t)g.tiles_m * g.tiles_n;
     const int nbatch = OP == OP_DW ? d.nbatch : 1;
     if (ntiles * nbatch > 0x7FFFFFFF) return SDP_ERR_SHAPE;
-    g.ntiles = (int)ntiles;
+    g.ntot = (int)(ntiles * nbatch);
+    g.nbatch = nbatch;
+    int na = 1, nbo = 1; // distinct A / B operands among the problems of a batch
     for (int z = 0; z < 3; ++z) {
         g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
     }
+    if (OP == OP_DW) {
+        na = nbo = 0;
+        for (int z = 0; z < nbatch; ++z) {
+            bool newa = true, newb = true;
+            for (int y = 0; y < z; ++y) newa &= d.Ab[y] != d.Ab[z], newb &= d.Bb[y] != d.Bb[z];
+            na += newa, nbo += newb;
+        }
+    }
+    g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na, nbo, BM, BN);
+    if (const char* e = getenv("SDP_GROUP_M")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
     g.debug = 0;
     if (const char* e = getenv("SDP_DEBUG_TIMING")) g.debug = atoi(e);
     auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, A_KM, EPI, OP>;
@@ -513,8 +553,6 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     kern<<<dim3((unsigned)(ntiles * nbatch)), NTHREADS, LDS, s>>>(g);
     return launch_status();
 }
-
-constexpr int kNumCU = 256;
 
 // estimated time of a tile shape, in units of 256 x 256 tile-depths: rounds over the CUs times tile
 // area, times a penalty for the smaller shapes' lower MFMA duty (more LDS traffic per flop).

@@ -68,6 +68,9 @@ SMALL = [
     MlpWorkload("full_cover_f32_fm", "f32", 64, 32, 64, 64, 2, "fm", 13),       # C = 1: the dense MLP
     MlpWorkload("tiles_bf16_fm", "bf16", 264, 136, 520, 264, 4, "fm", 14),      # several tiles + ragged tails
     MlpWorkload("tiles_bf16_bm", "bf16", 264, 136, 520, 264, 4, "bm", 14),
+    MlpWorkload("tails16_bf16_fm", "bf16", 272, 144, 528, 272, 4, "fm", 18),    # MFMA path, every depth ends in a partial step
+    MlpWorkload("tails16_bf16_bm", "bf16", 272, 144, 528, 304, 4, "bm", 18),
+    MlpWorkload("tails48_bf16_fm", "bf16", 304, 176, 560, 240, 4, "fm", 19),    # depth tails of 48, ragged rows / columns
     MlpWorkload("aligned_bf16_fm", "bf16", 512, 256, 1024, 512, 4, "fm", 15),
     MlpWorkload("aligned_bf16_bm", "bf16", 512, 256, 1024, 768, 4, "bm", 16),
     MlpWorkload("full_cover_bf16_bm", "bf16", 256, 128, 256, 256, 2, "bm", 17),
