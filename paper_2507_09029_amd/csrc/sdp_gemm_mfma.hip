@@ -76,7 +76,6 @@ struct Dev {
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
     const uint16_t *Ab[3], *Bb[3];
     uint16_t* Cb[3];
-    int debug; // timing experiments only (results are garbage): bit 0 = no operand loads, bit 3 = no epilogue
 };
 
 // two fp32 -> packed bf16, round to nearest even (the hardware's v_cvt_pk_bf16_f32)
@@ -89,7 +88,12 @@ __device__ inline u32x2 pack4(float a, float b, float c, float d) { return u32x2
 __device__ inline float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// source of the chunks that lie beyond the depth of the matrices in a partial last step
+__device__ __attribute__((aligned(256))) const uint32_t kZeroChunk[64] = {0};
+
 // s_waitcnt vmcnt(n) alone (expcnt / lgkmcnt left at their maxima), gfx9 encoding
+// s_waitcnt lgkmcnt(0) alone: this wave's LDS reads have returned
+#define SDP_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14))
 #define SDP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
@@ -97,27 +101,27 @@ struct Geometry {
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int FM = WM / 32, FN = WN / 32;
-    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static constexpr int RING = 2 * A_BYTES + 3 * B_BYTES; // two A stages, three B stages
     // epilogue strip: 32 rows x SW columns of bf16, rows padded by 8 bytes
     static constexpr int SW = EPI == EPI_SWIGLU_FWD ? WN / 2 : WN;
     static constexpr int RS = SW * 2 + 8;
     static constexpr int STRIP = 32 * RS;
     static constexpr int NSTRIP = EPI == EPI_SWIGLU_BWD ? 3 : 1; // strips per wave
-    static constexpr int LDS = 2 * STAGE > NW * NSTRIP * STRIP ? 2 * STAGE : NW * NSTRIP * STRIP;
+    static constexpr int LDS = RING > NW * NSTRIP * STRIP ? RING : NW * NSTRIP * STRIP;
+    static_assert(LDS <= 160 * 1024, "LDS of one CU");
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int A_KM, int EPI, int OP>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OP>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev g) {
     using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
     constexpr int NW = Geo::NW, WM = Geo::WM, WN = Geo::WN, FM = Geo::FM, FN = Geo::FN;
-    constexpr int A_BYTES = Geo::A_BYTES, STAGE = Geo::STAGE;
+    constexpr int A_BYTES = Geo::A_BYTES, B_BYTES = Geo::B_BYTES;
     constexpr bool kFwd = EPI == EPI_SWIGLU_FWD;
     constexpr int SA = (BM / 8) / NW;  // A slabs (1 KB) per wave per step
     constexpr int SB = (BN / 8) / NW;  // B slabs per wave per step
-    constexpr int ACH = BM / 8;        // chunks per row of the A k tile
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "slabs must divide among the waves");
     static_assert(!kFwd || FN % 2 == 0, "gate/up fragments come in pairs");
-    static_assert(ACH % 4 == 0, "rotation works in groups of 4 chunks");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -160,36 +164,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     const int m0 = tile_m * BM;
     const int n0 = kFwd ? tile_n * (BN / 2) : tile_n * BN; // SWIGLU_FWD: BN columns = BN/2 neurons x {gate, up}
 
-    // ---- depth steps: nfull whole steps, then at most one partial step (K % 64 in {16, 32, 48}) ----
-    const int nfull = g.K / BK;
+    // ---- depth steps; a partial last step (K % 64 in {16, 32, 48}) reads its missing chunks from a
+    // zero buffer, so that every step issues the same loads and runs all four MFMA sub-steps ----
     const int nk1 = (g.K + BK - 1) / BK;
     const int nk = EPI == EPI_DUAL_ACC ? 2 * nk1 : nk1;
 
     // ---- per-lane global source of every slab this wave fills: byte offsets from a uniform base.
-    // Row and column indices beyond the matrix are clamped to the last valid one: such lanes fetch
-    // valid memory whose products only reach outputs that are never stored.
-    uint32_t a_off[SA];
-    int a_k[SA]; // A_KM: k row inside the tile
+    // Row indices beyond the matrix are clamped to the last valid one: such lanes fetch valid
+    // memory whose products only reach outputs that are never stored.
+    // Slab s holds tile rows 8s .. 8s+7; lane -> row 8s + lane/8, stored chunk position lane%8.
+    uint32_t a_off[SA], b_off[SB];
+    int a_k[SA], b_k[SB]; // depth offset of this lane's chunk inside a step
 #pragma unroll
     for (int i = 0; i < SA; ++i) {
-        if (!A_KM) {
-            // row tile, slab s: rows 8s .. 8s+7; lane -> row 8s + lane/8, stored position lane%8
-            const int r = 8 * (wave + NW * i) + (lane >> 3);
-            const int c = (lane & 7) ^ ((r >> 1) & 7);
-            int m = m0 + r;
-            m = m < g.M ? m : g.M - 1;
-            a_off[i] = (uint32_t)(((int64_t)m * g.lda + c * 8) * 2);
-            a_k[i] = 0;
-        } else {
-            const int q = 64 * (wave + NW * i) + lane; // chunk slot inside the k tile
-            const int k = q / ACH, pos = q % ACH;
-            a_k[i] = k;
-            int col = m0 + ((pos + ACH - 4 * (k & 3)) % ACH) * 8; // inverse of the stored rotation
-            col = col < g.M ? col : g.M - 8;
-            a_off[i] = (uint32_t)(((int64_t)k * g.lda + col) * 2);
-        }
+        const int r = 8 * (wave + NW * i) + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        int m = m0 + r;
+        m = m < g.M ? m : g.M - 1;
+        a_off[i] = (uint32_t)(((int64_t)m * g.lda + c * 8) * 2);
+        a_k[i] = c * 8;
     }
-    uint32_t b_off[SB];
 #pragma unroll
     for (int i = 0; i < SB; ++i) {
         const int r = 8 * (wave + NW * i) + (lane >> 3);
@@ -198,54 +192,46 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         n = n < g.N ? n : g.N - 1;
         const int64_t row = g.bg ? g.bg[n] : n;
         b_off[i] = (uint32_t)((row * g.ldb + c * 8) * 2);
+        b_k[i] = c * 8;
     }
 
-    // CHECK = false: a whole step.  CHECK = true: the partial last step; chunks at k >= K are
-    // zero-filled with an ordinary LDS store so that the MFMAs can always run all four sub-steps.
-    auto issue_loads = [&](int kt, int stage, auto check) {
-        constexpr bool CHECK = decltype(check)::value;
+    // LDS: two A stages, then a ring of three B stages
+    unsigned char* const lds_a = smem;
+    unsigned char* const lds_b = smem + 2 * A_BYTES;
+
+    // loads [first, last) of the SA (resp. SB) slabs of depth step kt; TAIL: K % 64 != 0
+    auto issue_a = [&](int kt, auto tail_c, int first, int last) {
+        constexpr bool TAIL = decltype(tail_c)::value;
         const bool second = EPI == EPI_DUAL_ACC && kt >= nk1;
         const int k0 = (second ? kt - nk1 : kt) * BK;
-        unsigned char* sa = smem + stage * STAGE;
-        unsigned char* sb = sa + A_BYTES;
-        const u32x4 zero4 = {0u, 0u, 0u, 0u};
-        const unsigned char* abase =
-            (const unsigned char*)(second ? g.A2 : gA) + (A_KM ? (int64_t)k0 * g.lda * 2 : (int64_t)k0 * 2);
+        const int krem = g.K - k0;
+        unsigned char* sa = lds_a + (kt & 1) * A_BYTES;
+        const unsigned char* abase = (const unsigned char*)(second ? g.A2 : gA) + (int64_t)k0 * 2;
 #pragma unroll
         for (int i = 0; i < SA; ++i) {
-            unsigned char* dst = sa + (wave + NW * i) * 1024;
-            bool ok = true;
-            if (CHECK) {
-                if (A_KM)
-                    ok = k0 + a_k[i] < g.K;
-                else
-                    ok = k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K;
-            }
-            if (ok)
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(abase + a_off[i]), (lds_void_ptr)dst, 16, 0, 0);
-            else
-                *(u32x4*)(dst + lane * 16) = zero4;
+            if (i < first || i >= last) continue;
+            const unsigned char* src = abase + a_off[i];
+            if (TAIL && a_k[i] >= krem) src = (const unsigned char*)kZeroChunk;
+            __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(sa + (wave + NW * i) * 1024), 16, 0, 0);
         }
+    };
+    auto issue_b = [&](int kt, int slot, auto tail_c, int first, int last) {
+        constexpr bool TAIL = decltype(tail_c)::value;
+        const bool second = EPI == EPI_DUAL_ACC && kt >= nk1;
+        const int k0 = (second ? kt - nk1 : kt) * BK;
+        const int krem = g.K - k0;
+        unsigned char* sb = lds_b + slot * B_BYTES;
         const unsigned char* bbase0 = (const unsigned char*)(second ? g.B2 : gB) + (int64_t)k0 * 2;
         const unsigned char* bbase1 = (const unsigned char*)g.B2 + (int64_t)k0 * 2;
 #pragma unroll
         for (int i = 0; i < SB; ++i) {
-            unsigned char* dst = sb + (wave + NW * i) * 1024;
+            if (i < first || i >= last) continue;
             // SWIGLU_FWD: tile rows BN/2.. hold the up-projection rows (second matrix)
             const bool up = kFwd && 8 * (wave + NW * i) >= BN / 2;
-            const unsigned char* base = up ? bbase1 : bbase0;
-            if (!CHECK || k0 + (int)((lane & 7) ^ (((8 * (wave + NW * i) + (lane >> 3)) >> 1) & 7)) * 8 < g.K)
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(base + b_off[i]), (lds_void_ptr)dst, 16, 0, 0);
-            else
-                *(u32x4*)(dst + lane * 16) = zero4;
+            const unsigned char* src = (up ? bbase1 : bbase0) + b_off[i];
+            if (TAIL && b_k[i] >= krem) src = (const unsigned char*)kZeroChunk;
+            __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(sb + (wave + NW * i) * 1024), 16, 0, 0);
         }
-    };
-    auto issue = [&](int kt, int stage) {
-        const int k_in_pair = (EPI == EPI_DUAL_ACC && kt >= nk1) ? kt - nk1 : kt;
-        if (k_in_pair < nfull)
-            issue_loads(kt, stage, std::false_type{});
-        else
-            issue_loads(kt, stage, std::true_type{});
     };
 
     f32x16 acc[FM][FN];
@@ -274,34 +260,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
 #pragma unroll
     for (int s = 0; s < BK / 16; ++s) row_off[s] = (((2 * s + lhi) ^ ((l32 >> 1) & 7)) * 16) + l32 * 128;
     const int a_base = WM * wm * 128;
-    // k tile: lane i of a 16-lane block addresses row k + i/4, 4 columns starting at 4 (i%4) of the
-    // block's 16 columns; k & 3 == (i/4) & 3 for every sub-step, so the rotation is fixed per lane.
-    int km_off[FM];
-    if (A_KM) {
-        const int blk = lane >> 4, li = lane & 15;
-        const int krow = 8 * (blk >> 1) + (li >> 2);
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int col = WM * wm + 32 * i + 16 * (blk & 1) + 4 * (li & 3);
-            const int pos = krow * ACH + ((col >> 3) + 4 * (krow & 3)) % ACH;
-            km_off[i] = pos * 16 + (col & 4) * 2;
-        }
-    }
 
     auto read_frags = [&](const unsigned char* sa, const unsigned char* sb, int s, bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            if (!A_KM) {
-                fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 32 * 128 + row_off[s]));
-            } else {
-                // transposing read: the block's lane n receives rows k..k+3 of column n
-                const unsigned char* p = sa + km_off[i] + s * 16 * ACH * 16;
-                const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
-                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * ACH * 16));
-                const s16x8 both = {h0[0], h0[1], h0[2], h0[3], h1[0], h1[1], h1[2], h1[3]};
-                fa[i] = __builtin_bit_cast(bf16x8, both);
-            }
-        }
+        for (int i = 0; i < FM; ++i)
+            fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 32 * 128 + row_off[s]));
 #pragma unroll
         for (int j = 0; j < FN; ++j)
             fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + bfrag[j] * 128 + row_off[s]));
@@ -316,31 +279,102 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     };
 
-    issue(0, 0);
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int stage = kt & 1;
-        SDP_WAIT_VMCNT(0);  // this wave's chunks of step kt have landed
-        __syncthreads();    // everybody's have; and everybody is done reading the other stage
-        if (kt + 1 < nk && !(g.debug & 1)) issue(kt + 1, stage ^ 1);
-        const unsigned char* sa = smem + stage * STAGE;
-        const unsigned char* sb = sa + A_BYTES;
-        // fragments of sub-step s+1 are read while the MFMAs of sub-step s run
-        bf16x8 fa[2][FM], fb[2][FN];
-        read_frags(sa, sb, 0, fa[0], fb[0]);
-#pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            if (s + 1 < BK / 16) read_frags(sa, sb, s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
-            mfma_step(fa[s & 1], fb[s & 1]);
-            __builtin_amdgcn_sched_barrier(0);
+    // ---- main loop: two wave groups in alternating phases.
+    // Group 0 = the first half of the waves, group 1 = the second half; the hardware places wave w of
+    // a workgroup on SIMD w % 4, so every SIMD holds one wave of each group.  A depth step is cut into
+    // two halves of two 16-deep sub-steps.  Each wave alternates a READ phase (the 2 (FM + FN) fragment
+    // reads of one half from LDS, plus its share of the direct loads of later steps) with a COMPUTE
+    // phase (the 2 FM FN MFMAs of that half, at raised priority), and the two groups are one phase
+    // apart: while one wave of a SIMD computes, the other one reads.  One wave alone keeps the matrix
+    // core busy, so the MFMA stream never waits for LDS or for the load unit.  Every phase ends with a
+    // workgroup barrier (plain s_barrier: the waits it needs are stated explicitly, and loads of later
+    // steps stay in flight across it).
+    //   phase 4 k     : group 0 reads (k, half 0), issues the loads of A for step k + 1
+    //   phase 4 k + 1 : group 0 computes (k, 0);  group 1 reads (k, 0), issues A(k + 1)
+    //   phase 4 k + 2 : group 0 reads (k, 1), issues the loads of B for step k + 2;  group 1 computes (k, 0)
+    //   phase 4 k + 3 : group 0 computes (k, 1);  group 1 reads (k, 1), issues B(k + 2)
+    // A has two LDS stages and B three.  Stage contents of step k are read in phases 4 k .. 4 k + 3;
+    // loads into the stages of step k - 1 are issued from phase 4 k on, after the barrier that ends
+    // phase 4 k - 1, before which every wave has waited for its own LDS reads.  Before that same
+    // barrier every wave waits until its loads for step k have landed (loads complete in issue
+    // order; only the newest SB, B of step k + 1, may still be in flight).
+    const int grp = wave / (NW / 2);
+    bf16x8 fa[2][FM], fb[2][FN];
+    auto read_half = [&](const unsigned char* sa, const unsigned char* sb, int h) {
+        read_frags(sa, sb, 2 * h, fa[0], fb[0]);
+        read_frags(sa, sb, 2 * h + 1, fa[1], fb[1]);
+    };
+    auto compute_half = [&]() {
+        __builtin_amdgcn_s_setprio(1);
+        mfma_step(fa[0], fb[0]);
+        mfma_step(fa[1], fb[1]);
+        __builtin_amdgcn_s_setprio(0);
+    };
+    auto phase_end = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto step = [&](int kt, int slot, auto ia_c, auto ib_c, auto tail_c) {
+        constexpr bool IA = decltype(ia_c)::value; // step kt + 1 exists
+        constexpr bool IB = decltype(ib_c)::value; // step kt + 2 exists
+        const unsigned char* sa = lds_a + (kt & 1) * A_BYTES;
+        const unsigned char* sb = lds_b + slot * B_BYTES;
+        const int slot2 = slot == 0 ? 2 : slot - 1; // (kt + 2) % 3
+        // READ (kt, 0)
+        read_half(sa, sb, 0);
+        if (IA) issue_a(kt + 1, tail_c, 0, SA);
+        SDP_WAIT_LGKMCNT0();
+        phase_end();
+        // COMPUTE (kt, 0)
+        compute_half();
+        phase_end();
+        // READ (kt, 1)
+        read_half(sa, sb, 1);
+        if (IB) issue_b(kt + 2, slot2, tail_c, 0, SB);
+        SDP_WAIT_LGKMCNT0();
+        if (grp == 1) {
+            if (IB) SDP_WAIT_VMCNT(SB); else SDP_WAIT_VMCNT(0);
         }
-    }
+        phase_end();
+        // COMPUTE (kt, 1)
+        compute_half();
+        if (grp == 0) {
+            if (IB) SDP_WAIT_VMCNT(SB); else SDP_WAIT_VMCNT(0);
+        }
+        phase_end();
+    };
+    auto run = [&](auto tail_c) {
+        issue_a(0, tail_c, 0, SA);
+        issue_b(0, 0, tail_c, 0, SB);
+        if (nk > 1) {
+            issue_b(1, 1, tail_c, 0, SB);
+            SDP_WAIT_VMCNT(SB);
+        } else {
+            SDP_WAIT_VMCNT(0);
+        }
+        phase_end();
+        if (grp == 1) phase_end(); // group 1 runs one phase behind
+        int slot = 0;
+        int kt = 0;
+        for (; kt + 2 < nk; ++kt) {
+            step(kt, slot, std::true_type{}, std::true_type{}, tail_c);
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+        if (kt + 1 < nk) {
+            step(kt, slot, std::true_type{}, std::false_type{}, tail_c);
+            slot = slot == 2 ? 0 : slot + 1;
+            ++kt;
+        }
+        step(kt, slot, std::false_type{}, std::false_type{}, tail_c);
+        if (grp == 0) phase_end();
+    };
+    if (g.K % BK == 0) run(std::false_type{}); else run(std::true_type{});
 
     // ================================ epilogue ================================
     // acc[i][j][4q + r] = C(m, n),  m = m0 + WM wm + 32 i + l32,
     //                               n = n0 + (column base of fragment j) + 8 q + 4 lhi + r.
     __syncthreads(); // all waves are done with the operand tiles: LDS becomes per-wave strips
-    if (g.debug & 8) return;
     constexpr int SW = Geo::SW, RS = Geo::RS;
     constexpr int CPR = SW / 8;               // 16-byte chunks per strip row
     constexpr int NCH = 32 * CPR;             // chunks per strip
@@ -505,7 +539,7 @@ int choose_group_m(int tiles_m, int tiles_n, int nbatch, int na, int nb, int bm,
     return best;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int A_KM, int EPI, int OP>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OP>
 int launch_cfg(const GemmDesc& d, hipStream_t s) {
     using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
     constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
@@ -540,9 +574,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     }
     g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na, nbo, BM, BN);
     if (const char* e = getenv("SDP_GROUP_M")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
-    g.debug = 0;
-    if (const char* e = getenv("SDP_DEBUG_TIMING")) g.debug = atoi(e);
-    auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, A_KM, EPI, OP>;
+    auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, OP>;
     static bool attr_set = false; // one flag per instantiation
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
@@ -562,7 +594,7 @@ double shape_cost(int M, int ncols_total, int nbatch, int bm, int bn, double pen
     return (double)rounds * bm * bn * penalty;
 }
 
-template <int A_KM, int EPI, int OP>
+template <int EPI, int OP>
 int launch(const GemmDesc& d, hipStream_t s) {
     // columns of tile space (gate and up interleaved double the tile columns)
     const int ncols = EPI == EPI_SWIGLU_FWD ? 2 * d.N : d.N;
@@ -574,14 +606,12 @@ int launch(const GemmDesc& d, hipStream_t s) {
     int force = d.force_tile;
     if (const char* e = getenv("SDP_FORCE_TILE")) force = atoi(e);
     if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) {
-        // depth-major A is read with the slower transposing LDS reads: give each wave fewer A fragments
-        if constexpr (A_KM != 0) return launch_cfg<256, 256, 4, 2, A_KM, EPI, OP>(d, s);
-        else return launch_cfg<256, 256, 2, 4, A_KM, EPI, OP>(d, s);
+        return launch_cfg<256, 256, 2, 4, EPI, OP>(d, s);
     }
     if constexpr (EPI != EPI_SWIGLU_FWD) {
-        if (force == 192 || (!force && c192 <= c128)) return launch_cfg<256, 192, 4, 2, A_KM, EPI, OP>(d, s);
+        if (force == 192 || (!force && c192 <= c128)) return launch_cfg<256, 192, 4, 2, EPI, OP>(d, s);
     }
-    return launch_cfg<128, 128, 2, 2, A_KM, EPI, OP>(d, s);
+    return launch_cfg<128, 128, 2, 2, EPI, OP>(d, s);
 }
 
 } // namespace
@@ -590,9 +620,8 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return false;
     // 16-byte global chunks, 16-deep MFMA steps, 32-bit byte offsets inside each operand
     if (d.K % 16 || d.lda % 8 || d.ldb % 8 || d.N % 8 || d.ldc % 8) return false;
-    if (d.a_km && d.M % 8) return false;
-    const int64_t a_rows = d.a_km ? d.K : d.M;
-    if (a_rows * d.lda * 2 >= ((int64_t)1 << 32)) return false;
+    if (d.a_km) return false; // depth-major A goes through the transposing pre-pass or the plain kernel
+    if ((int64_t)d.M * d.lda * 2 >= ((int64_t)1 << 32)) return false;
     if ((d.b_rows > 0 ? d.b_rows : (int64_t)d.N) * d.ldb * 2 >= ((int64_t)1 << 32)) return false;
     if (d.b_gather && d.b_rows <= 0) return false;
     if (d.nbatch > 0) {
@@ -608,7 +637,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
         if (!d.B2 || !aligned16(d.B2)) return false;
     if (d.epilogue == EPI_DUAL_ACC && (!d.A2 || !aligned16(d.A2))) return false;
     if (d.epilogue == EPI_SWIGLU_FWD || d.epilogue == EPI_SWIGLU_BWD) {
-        if (d.a_km || !d.C2 || !d.C3 || !aligned16(d.C2) || !aligned16(d.C3)) return false;
+        if (!d.C2 || !d.C3 || !aligned16(d.C2) || !aligned16(d.C3)) return false;
     }
     if (d.epilogue == EPI_SWIGLU_BWD && (!d.Gin || !d.Uin || !aligned16(d.Gin) || !aligned16(d.Uin) || d.ldg % 8))
         return false;
@@ -618,15 +647,11 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
     if (!gemm_mfma_supported(d)) return SDP_ERR_UNSUPPORTED;
     // OP only gives every call site its own kernel symbol, so that profiles name the step
-    if (d.a_km) {
-        if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<1, EPI_STORE, OP_DW>(d, s);
-    } else {
-        if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<0, EPI_STORE, OP_DW>(d, s);
-        if (d.epilogue == EPI_STORE && d.nbatch == 0) return launch<0, EPI_STORE, OP_DOWN>(d, s);
-        if (d.epilogue == EPI_DUAL_ACC) return launch<0, EPI_DUAL_ACC, OP_DX>(d, s);
-        if (d.epilogue == EPI_SWIGLU_FWD) return launch<0, EPI_SWIGLU_FWD, OP_GATE_UP>(d, s);
-        if (d.epilogue == EPI_SWIGLU_BWD) return launch<0, EPI_SWIGLU_BWD, OP_DACT>(d, s);
-    }
+    if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<EPI_STORE, OP_DW>(d, s);
+    if (d.epilogue == EPI_STORE && d.nbatch == 0) return launch<EPI_STORE, OP_DOWN>(d, s);
+    if (d.epilogue == EPI_DUAL_ACC) return launch<EPI_DUAL_ACC, OP_DX>(d, s);
+    if (d.epilogue == EPI_SWIGLU_FWD) return launch<EPI_SWIGLU_FWD, OP_GATE_UP>(d, s);
+    if (d.epilogue == EPI_SWIGLU_BWD) return launch<EPI_SWIGLU_BWD, OP_DACT>(d, s);
     return SDP_ERR_UNSUPPORTED;
 }
 
