@@ -67,8 +67,8 @@ struct Dev {
     int64_t ldc;
     const uint16_t *Gin, *Uin;
     int64_t ldg;
-    uint16_t *Cc, *Cc2, *Cc3;
-    int64_t ldcc;
+    uint16_t *Ct, *Ct2, *Ct3; // SWIGLU_BWD: neuron-major (transposed) copies [column or rank][ldct], optional
+    int64_t ldct;
     const int32_t* cidx;
     int pc;
     int tiles_m, tiles_n, ntot; // ntot = tiles of all problems of the launch
@@ -108,7 +108,9 @@ struct Geometry {
     static constexpr int RS = SW * 2 + 8;
     static constexpr int STRIP = 32 * RS;
     static constexpr int NSTRIP = EPI == EPI_SWIGLU_BWD ? 3 : 1; // strips per wave
-    static constexpr int LDS = RING > NW * NSTRIP * STRIP ? RING : NW * NSTRIP * STRIP;
+    static constexpr int RANKTAB = EPI == EPI_SWIGLU_BWD ? SW * 4 : 0; // per wave: output row of each strip column
+    static constexpr int WAVE_LDS = NSTRIP * STRIP + RANKTAB;
+    static constexpr int LDS = RING > NW * WAVE_LDS ? RING : NW * WAVE_LDS;
     static_assert(LDS <= 160 * 1024, "LDS of one CU");
 };
 
@@ -378,7 +380,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     constexpr int SW = Geo::SW, RS = Geo::RS;
     constexpr int CPR = SW / 8;               // 16-byte chunks per strip row
     constexpr int NCH = 32 * CPR;             // chunks per strip
-    unsigned char* strip0 = smem + wave * (Geo::NSTRIP * Geo::STRIP);
+    unsigned char* strip0 = smem + wave * Geo::WAVE_LDS;
     const int wcol0 = kFwd ? n0 + (WN / 2) * wn : n0 + WN * wn; // first output column of this wave's strips
 
     // one packed 8-byte group of a strip: row l32, columns cbase + 8 q + 4 lhi ..
@@ -419,22 +421,45 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     };
 
-    // backward masking: column range of the compacted copies that falls into this wave's strips
-    int c_lo = 0, c_hi = 0;
-    if (EPI == EPI_SWIGLU_BWD && g.cidx) {
-        int lo = 0, hi = g.pc;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
+    // neuron-major copies: output row of each of this wave's SW strip columns.  Without an index list it
+    // is the column itself; with one (backward masking) it is the column's rank in the ascending list,
+    // or -1 for columns that are not listed.
+    int32_t* ranktab = (int32_t*)(strip0 + Geo::NSTRIP * Geo::STRIP);
+    if (EPI == EPI_SWIGLU_BWD && g.Ct) {
+        for (int c = lane; c < SW; c += 64) ranktab[c] = g.cidx ? -1 : (wcol0 + c < g.N ? wcol0 + c : -1);
+        if (g.cidx) {
+            int lo = 0, hi = g.pc; // first listed column >= wcol0
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
+            }
+            for (int t = lo + lane; t < g.pc; t += 64) {
+                const int c = g.cidx[t] - wcol0;
+                if (c >= SW) break;
+                ranktab[c] = t;
+            }
         }
-        c_lo = lo;
-        hi = g.pc;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (g.cidx[mid] < wcol0 + SW) lo = mid + 1; else hi = mid;
-        }
-        c_hi = lo;
     }
+    // strip -> neuron-major global: out[ranktab[column]][token].  A transposing LDS read hands the lanes of
+    // a 16-lane block, for 4 adjacent strip columns, 4 consecutive rows each; two of them give every lane
+    // 8 consecutive tokens of one column, i.e. one 16-byte store, and 4 lanes cover the 32 tokens (64 bytes).
+    auto strip_store_t = [&](const unsigned char* strip, uint16_t* out, int i) {
+        const int gi = lane >> 4, li = lane & 15, q = li >> 2, cn = li & 3;
+        const int src_row = 8 * (li & 3) + (li >> 2); // as source lane: rows 8 q' + e for the lanes that receive from it
+        const int m = m0 + WM * wm + 32 * i + 8 * q;
+#pragma unroll
+        for (int it = 0; it < SW / 16; ++it) {
+            const int c4 = 16 * it + 4 * gi;
+            const unsigned char* p = strip + src_row * RS + c4 * 2;
+            const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+            const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * RS));
+            const int row = ranktab[c4 + cn];
+            if (row >= 0 && m < g.M) {
+                const u32x2 a = __builtin_bit_cast(u32x2, h0), b = __builtin_bit_cast(u32x2, h1);
+                *(u32x4*)(out + (int64_t)row * g.ldct + m) = u32x4{a[0], a[1], b[0], b[1]};
+            }
+        }
+    };
 
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -497,20 +522,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                 }
             strip_store(strip0, g.C, g.ldc, nullptr, i);
             strip_store(strip1, g.C2, g.ldc, nullptr, i);
-            strip_store(strip2, g.C3, g.ldc, nullptr, i);
-            if (g.cidx) {
-                // compacted copies: lane t takes compact column c_lo + t = strip column cidx[c_lo + t] - wcol0
-                for (int t = c_lo + lane; t < c_hi; t += 64) {
-                    const int src = (g.cidx[t] - wcol0) * 2;
-                    for (int row = 0; row < 32; ++row) {
-                        const int m = m0 + WM * wm + 32 * i + row;
-                        if (m >= g.M) break;
-                        const int64_t o = (int64_t)m * g.ldcc + t;
-                        g.Cc[o] = *(const uint16_t*)(strip0 + row * RS + src);
-                        g.Cc2[o] = *(const uint16_t*)(strip1 + row * RS + src);
-                        g.Cc3[o] = *(const uint16_t*)(strip2 + row * RS + src);
-                    }
-                }
+            if (g.C3) strip_store(strip2, g.C3, g.ldc, nullptr, i);
+            if (g.Ct) {
+                strip_store_t(strip0, g.Ct, i);
+                strip_store_t(strip1, g.Ct2, i);
+                strip_store_t(strip2, g.Ct3, i);
             }
         }
     }
@@ -550,7 +566,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     g.lda = d.lda, g.ldb = d.ldb, g.bg = d.b_gather, g.cs = d.c_scatter;
     g.C = (uint16_t*)d.C, g.C2 = (uint16_t*)d.C2, g.C3 = (uint16_t*)d.C3, g.ldc = d.ldc;
     g.Gin = (const uint16_t*)d.Gin, g.Uin = (const uint16_t*)d.Uin, g.ldg = d.ldg;
-    g.Cc = (uint16_t*)d.Cc, g.Cc2 = (uint16_t*)d.Cc2, g.Cc3 = (uint16_t*)d.Cc3, g.ldcc = d.ldcc;
+    g.Ct = (uint16_t*)d.Ct, g.Ct2 = (uint16_t*)d.Ct2, g.Ct3 = (uint16_t*)d.Ct3, g.ldct = d.ldct;
     g.cidx = d.cidx, g.pc = d.pc;
     g.tiles_m = (d.M + BM - 1) / BM;
     const int ncols = EPI == EPI_SWIGLU_FWD ? BN / 2 : BN;
@@ -636,11 +652,21 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.epilogue == EPI_DUAL_ACC || d.epilogue == EPI_SWIGLU_FWD)
         if (!d.B2 || !aligned16(d.B2)) return false;
     if (d.epilogue == EPI_DUAL_ACC && (!d.A2 || !aligned16(d.A2))) return false;
-    if (d.epilogue == EPI_SWIGLU_FWD || d.epilogue == EPI_SWIGLU_BWD) {
+    if (d.epilogue == EPI_SWIGLU_FWD) {
         if (!d.C2 || !d.C3 || !aligned16(d.C2) || !aligned16(d.C3)) return false;
     }
-    if (d.epilogue == EPI_SWIGLU_BWD && (!d.Gin || !d.Uin || !aligned16(d.Gin) || !aligned16(d.Uin) || d.ldg % 8))
-        return false;
+    if (d.epilogue == EPI_SWIGLU_BWD) {
+        if (!d.C2 || !aligned16(d.C2) || (d.C3 && !aligned16(d.C3))) return false; // Act row-major is optional
+        if (!d.Gin || !d.Uin || !aligned16(d.Gin) || !aligned16(d.Uin) || d.ldg % 8) return false;
+        if (d.Cc || d.Cc2 || d.Cc3) return false; // row-major compact copies: plain kernel only
+        if (d.Ct) {
+            if (!d.Ct2 || !d.Ct3 || !aligned16(d.Ct) || !aligned16(d.Ct2) || !aligned16(d.Ct3)) return false;
+            if (d.ldct % 8 || d.M % 8 || d.ldct < d.M) return false;
+            if (d.cidx && d.pc < 1) return false;
+        } else if (!d.C3) {
+            return false;
+        }
+    }
     return true;
 }
 

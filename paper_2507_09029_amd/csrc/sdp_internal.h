@@ -42,8 +42,8 @@ enum Epilogue {
     EPI_SWIGLU_FWD = 2,  // g = A.B, u = A.B2: G = g, U = u, Act = silu(g) * u, all [M][N] (ld = ldc)
     EPI_SWIGLU_BWD = 3   // da = A.B; with g = Gin[m][n], u = Uin[m][n]  (ld = ldg):
                          //   dU = da silu(g), dG = da u silu'(g), act = silu(g) u, all [M][N] (ld = ldc);
-                         //   with cidx != null also the column-compacted copies [M][pc] (ld = ldcc):
-                         //   column c of Cc / Cc2 / Cc3 is column cidx[c] of dG / dU / act (cidx ascending)
+                         //   plain kernel: with cidx != null also the column-compacted copies [M][pc]
+                         //   (ld = ldcc): column c of Cc / Cc2 / Cc3 is column cidx[c] of dG / dU / act
 };
 
 struct GemmDesc {
@@ -74,6 +74,13 @@ struct GemmDesc {
     int64_t ldcc = 0;
     const int32_t* cidx = nullptr;
     int pc = 0;
+    // SWIGLU_BWD, MFMA kernel only: neuron-major copies Ct / Ct2 / Ct3 of dG / dU / act, [rows][ldct] with
+    // Ct[r(n)][m] = dG[m][n]; r(n) = n, or with cidx the rank of n in cidx (columns not listed are dropped).
+    // With Ct set, C3 may be null (act is then not stored row-major).
+    void* Ct = nullptr;
+    void* Ct2 = nullptr;
+    void* Ct3 = nullptr;
+    int64_t ldct = 0;
     const char* name = "gemm";
     // batched launch of up to three problems with the same shape, strides and scatter (the
     // weight-gradient contractions): nbatch > 0 selects Ab/Bb/Cb instead of A/B/C

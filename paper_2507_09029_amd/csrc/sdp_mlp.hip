@@ -152,6 +152,22 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     rc = transpose_rows((int)e, dY, d, nullptr, T, d, dYT, ld_tokens(T), "mlp_xt", s);
     if (rc != SDP_OK) return rc;
 
+    // weight-gradient contraction (set up first: whether it can take the MFMA path decides what the
+    // activation-gradient kernel writes)
+    const void* rhs[3] = {XT, XT, dYT};
+    void* outp[3] = {dW1, dW3, dW2T};
+    void* nmaj[3] = {dGn, dUn, Actn};
+    GemmDesc dw;
+    dw.name = "mlp_dw";
+    dw.M = p, dw.N = d, dw.K = T;
+    dw.ldb = ld_tokens(T);
+    dw.epilogue = EPI_STORE;
+    dw.ldc = d;
+    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
+    dw.nbatch = 3;
+    dw.lda = ld_tokens(T), dw.a_km = 0;
+    for (int i = 0; i < 3; ++i) dw.Ab[i] = nmaj[i], dw.Bb[i] = rhs[i], dw.Cb[i] = outp[i];
+
     GemmDesc da;
     da.name = "mlp_dact";
     da.M = T, da.N = n, da.K = d;
@@ -159,14 +175,28 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     da.B = W2T, da.ldb = d, da.b_gather = gather, da.b_rows = F;
     da.epilogue = EPI_SWIGLU_BWD;
     da.Gin = G_save, da.Uin = U_save, da.ldg = n;
-    da.C = dG, da.C2 = dU, da.C3 = Act, da.ldc = n;
-    if (mode == SDP_MASK_BACKWARD) {
-        da.Cc = dGc, da.Cc2 = dUc, da.Cc3 = Actc, da.ldcc = p;
-        da.cidx = idx_k, da.pc = p;
+    da.C = dG, da.C2 = dU, da.ldc = n;
+    // bf16, aligned shapes: the epilogue also writes dG, dU and act transposed (neuron-major [p][T],
+    // under backward masking only the worker's p columns), which is the layout in which the batched
+    // weight-gradient contraction reads both operands depth-contiguous; act is not stored row-major.
+    da.Ct = dGn, da.Ct2 = dUn, da.Ct3 = Actn, da.ldct = ld_tokens(T);
+    if (mode == SDP_MASK_BACKWARD) da.cidx = idx_k, da.pc = p;
+    const bool fused = dtype == SDP_BF16 && p % 8 == 0 && T % 8 == 0 && gemm_mfma_supported(dw) && gemm_mfma_supported(da);
+    if (!fused) {
+        da.Ct = da.Ct2 = da.Ct3 = nullptr, da.cidx = nullptr, da.pc = 0;
+        da.C3 = Act;
+        if (mode == SDP_MASK_BACKWARD) {
+            da.Cc = dGc, da.Cc2 = dUc, da.Cc3 = Actc, da.ldcc = p;
+            da.cidx = idx_k, da.pc = p;
+        }
     }
     rc = run(dtype, da, s);
     if (rc != SDP_OK) return rc;
 
+    if (fused) {
+        rc = gemm_mfma_bf16(dw, s);
+        if (rc != SDP_OK) return rc;
+    }
     GemmDesc dx;
     dx.name = "mlp_dx";
     dx.M = T, dx.N = d, dx.K = n;
@@ -177,37 +207,15 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     rc = run(dtype, dx, s);
     if (rc != SDP_OK) return rc;
 
+    if (fused) return SDP_OK;
+    // plain path: read the left operands depth-major ([T][p]) as they are
     const void* lhs[3] = {dGc, dUc, Actc};
-    const void* rhs[3] = {XT, XT, dYT};
-    void* outp[3] = {dW1, dW3, dW2T};
-    GemmDesc dw;
-    dw.name = "mlp_dw";
-    dw.M = p, dw.N = d, dw.K = T;
-    dw.ldb = ld_tokens(T);
-    dw.epilogue = EPI_STORE;
-    dw.ldc = d;
-    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
-    // bf16, aligned shapes: the three left operands are first transposed to neuron-major [p][T] (one
-    // HBM-bound launch), so that the contraction reads both operands depth-contiguous with plain 16-byte
-    // LDS reads; one batched MFMA launch then computes the three gradients.
-    dw.nbatch = 3;
-    dw.lda = ld_tokens(T), dw.a_km = 0;
-    void* nmaj[3] = {dGn, dUn, Actn};
-    for (int i = 0; i < 3; ++i) dw.Ab[i] = nmaj[i], dw.Bb[i] = rhs[i], dw.Cb[i] = outp[i];
-    if (dtype == SDP_BF16 && gemm_mfma_supported(dw) && p % 8 == 0 && T % 8 == 0) {
-        rc = transpose3_bf16(lhs, p, T, p, nmaj, ld_tokens(T), "mlp_nt", s);
+    dw.nbatch = 0;
+    dw.lda = p, dw.a_km = 1;
+    for (int i = 0; i < 3; ++i) {
+        dw.A = lhs[i], dw.B = rhs[i], dw.C = outp[i];
+        rc = gemm_simple(dtype, dw, s);
         if (rc != SDP_OK) return rc;
-        rc = gemm_mfma_bf16(dw, s);
-        if (rc != SDP_OK) return rc;
-    } else {
-        // plain path: read the left operands depth-major ([T][p]) as they are
-        dw.nbatch = 0;
-        dw.lda = p, dw.a_km = 1;
-        for (int i = 0; i < 3; ++i) {
-            dw.A = lhs[i], dw.B = rhs[i], dw.C = outp[i];
-            rc = gemm_simple(dtype, dw, s);
-            if (rc != SDP_OK) return rc;
-        }
     }
     return SDP_OK;
 }
