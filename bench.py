@@ -285,6 +285,18 @@ def main():
         "kernels_note": "per-kernel table from an untimed survey of up to 3 steps with HIP events around every kernel "
                         "(that instrumentation slows a step by about a tenth); roofline is timed live in the K timed steps",
     }
+    # practical ceiling of the matrix cores: the same MFMA instruction with no memory traffic, on operands with
+    # this workload's statistics (N(0,1) rounded to bf16) and on all-zero operands (the clock the chip holds
+    # under MFMA load depends on the operand bits)
+    if w.dtype == "bf16":
+        nop = L.sdp_probe_mfma_operand_bytes() // 2
+        rnd = Xs[0].reshape(-1)[:nop].contiguous()
+        rec["mfma_ceiling"] = {
+            "random_operands_tflops": sdp.probe_mfma_tflops(rnd),
+            "zero_operands_tflops": sdp.probe_mfma_tflops(torch.zeros_like(rnd)),
+            "published_peak_tflops": PEAK_BF16_TFLOPS,
+            "note": "v_mfma_f32_32x32x16_bf16 loop, 8 waves per CU, no memory traffic; measured live",
+        }
     if not a.no_grad_avg_1b:
         del Xs, dYs, bufs, avg, per
         torch.cuda.empty_cache()

@@ -165,6 +165,21 @@ int sdp_profile_filter(const char* name);
 int sdp_profile_reset(void);
 int sdp_profile_read(int cap, const char** names, int64_t* calls, double* ms);
 
+/* ---------------------------------------------------------------------------------------------
+ * Measurement aid (not a step of the method): the rate at which this GPU's matrix cores sustain the
+ * bf16 MFMA instruction the contractions use, on operand values supplied by the caller and with no
+ * memory traffic inside the loop.  The clock the chip holds under MFMA load depends on the operand
+ * values (power), so this is the practical ceiling that the contractions' rates can be read against.
+ *   operands  device, sdp_probe_mfma_operand_bytes() bytes of bf16 values, 16-byte aligned
+ *   blocks    workgroups of 512 lanes to launch (a few per CU), iters: 32 MFMAs per wave each
+ *   sink      device scratch, sdp_probe_mfma_sink_bytes(blocks) bytes (written, never read)
+ *   tflops    host out.  The call launches the loop twice, times the second launch with HIP events
+ *             and synchronises `stream`.
+ * ------------------------------------------------------------------------------------------- */
+size_t sdp_probe_mfma_operand_bytes(void);
+size_t sdp_probe_mfma_sink_bytes(int blocks);
+int sdp_probe_mfma_tflops(const void* operands, int blocks, int iters, void* sink, double* tflops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -74,6 +74,12 @@ def lib():
     L.sdp_profile_reset.argtypes = []
     L.sdp_profile_read.restype = i32
     L.sdp_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    L.sdp_probe_mfma_operand_bytes.restype = sz
+    L.sdp_probe_mfma_operand_bytes.argtypes = []
+    L.sdp_probe_mfma_sink_bytes.restype = sz
+    L.sdp_probe_mfma_sink_bytes.argtypes = [i32]
+    L.sdp_probe_mfma_tflops.restype = i32
+    L.sdp_probe_mfma_tflops.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = L
     return L
 
@@ -240,3 +246,17 @@ def profile_read(cap=64):
     n = lib().sdp_profile_read(cap, names, calls, ms)
     _check(n, "sdp_profile_read")
     return {names[i].decode(): (int(calls[i]), float(ms[i])) for i in range(n)}
+
+
+def probe_mfma_tflops(operands, blocks=1024, iters=4000):
+    """Sustained bf16 MFMA rate (TFLOP/s) on the values of `operands` (bf16 tensor on the GPU)."""
+    L = lib()
+    need = L.sdp_probe_mfma_operand_bytes()
+    _dev(operands, torch.bfloat16, "operands")
+    if operands.numel() * 2 < need:
+        raise ValueError(f"operands: need at least {need} bytes")
+    sink = torch.empty(L.sdp_probe_mfma_sink_bytes(blocks), dtype=torch.uint8, device=operands.device)
+    out = ctypes.c_double(0.0)
+    _check(L.sdp_probe_mfma_tflops(operands.data_ptr(), blocks, iters, sink.data_ptr(), ctypes.byref(out), _stream()),
+           "sdp_probe_mfma_tflops")
+    return out.value

@@ -1,33 +1,32 @@
 // bf16 MFMA contraction for gfx950 (CDNA4) with the masked-MLP row gather and SwiGLU epilogues fused.
 //
 //   C[M][N] = sum_k A(m,k) B(k,n),  bf16 operands, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
-//   B is stored [N][K] (rows optionally gathered through an index table); A is stored [M][K], or
-//   [K][M] ("depth-major": the activations that the weight-gradient contractions read transposed).
+//   A is stored [M][K], B is stored [N][K] (rows optionally gathered through an index table): both
+//   operands are read along the depth, 16 bytes (8 bf16) at a time.
 //
 // Tile: BM x BN outputs per workgroup, depth step 64, WAVES_M x WAVES_N waves of 64 lanes, each wave
 // owning (BM/WAVES_M) x (BN/WAVES_N) outputs as 32 x 32 MFMA tiles.  The flagship shape is
-// 256 x 256 with 8 waves: 128 accumulator registers per lane, two waves per SIMD.
+// 256 x 256 with 8 waves: 128 accumulator registers per lane, two waves per SIMD, one workgroup per CU.
 //
 // HBM/L2 -> LDS: direct loads (global_load_lds_dwordx4).  One wave instruction moves 64 chunks of
-// 16 bytes (8 bf16) into 1 KB of consecutive LDS; which global chunk a lane fetches is free, so the
-// LDS layouts below are produced by choosing the global address per lane.  No registers and no
-// ds_write instructions are spent on staging.  Two LDS stages; per depth step: wait for this wave's
-// loads of the step, one barrier, issue the next step's loads, run the MFMAs.
+// 16 bytes into 1 KB of consecutive LDS ("slab"); which global chunk a lane fetches is free, so the
+// LDS layout below is produced by choosing the global address per lane.  No registers and no
+// ds_write instructions are spent on staging.  LDS holds two stages of A and three of B.
 //
-// LDS layouts (positions in 16-byte chunks):
-//   "row tile"  [R rows][64 k]   : B always, A when stored [M][K].  Chunk (r, c) sits at
-//                r*8 + (c ^ ((r >> 1) & 7)).  A lane's MFMA operand (8 consecutive k of one row) is
-//                one chunk: one ds_read_b128.
-//   "k tile"    [64 k][BM cols]  : A when stored [K][M].  Chunk (k, c) sits at
-//                k*(BM/8) + (c + 4 (k & 3)) mod (BM/8).  The MFMA operand needs 8 consecutive k of
-//                one column, i.e. a transpose: two ds_read_b64_tr_b16 per fragment.
-// Both patterns spread the lanes served in one LDS cycle over distinct banks.
+// LDS layout of an operand stage, [R rows][64 k] in 16-byte chunks: chunk (r, c) sits at
+// r*8 + (c ^ ((r >> 1) & 7)).  A lane's MFMA operand (8 consecutive k of one row) is one chunk, one
+// ds_read_b128, and the lanes served together fall on distinct banks.
+//
+// Main loop: the waves form two groups that alternate between a phase of LDS reads + load issue and a
+// phase of MFMAs only, one phase apart, so that on every SIMD one wave computes while the other one
+// fetches (see the comment at the loop).
 //
 // The MFMA is issued with the B fragment as its first operand: a lane then holds, for one output
 // row m, 4 consecutive columns n.  Epilogues go through LDS: each wave packs 32 x WN outputs as bf16
 // into a private LDS strip with 8-byte writes and reads the strip back as 16-byte chunks of whole
 // rows, so that every global store (and the loads of the saved pre-activations) is a coalesced
-// 16-byte access.  SwiGLU and its backward are applied on the fp32 accumulators before packing.
+// 16-byte access.  SwiGLU and its backward are applied on the fp32 accumulators before packing; the
+// backward epilogue can also write its three outputs transposed (transposing LDS reads of the strip).
 //
 // Workgroup -> tile mapping is XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs
 // (each with its own L2), so ids are first regrouped per XCD and each XCD then walks a compact

@@ -104,7 +104,4 @@ bool gemm_mfma_supported(const GemmDesc& g);
 int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t* rows, int R, int C, void* out,
                    int64_t ld_out, const char* name, hipStream_t s);
 
-int transpose3_bf16(const void* const in[3], int64_t ld_in, int R, int C, void* const out[3], int64_t ld_out,
-                    const char* name, hipStream_t s);
-
 } // namespace sdp

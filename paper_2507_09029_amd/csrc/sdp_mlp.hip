@@ -9,13 +9,16 @@
 //             down    : Y  = Act . W2c^T                     (T x d, depth n)
 //   backward  wt      : W1c = W1[S]^T, W3c = W3[S]^T ([d][n]);  XT = X^T, dYT = dY^T ([d][T])
 //             dact    : dA = dY . W2T[S]^T                   (T x n, depth d; rows of W2T gathered)
-//                        + SwiGLU-backward epilogue -> dG, dU, Act [T][n]
-//                        (+ under backward masking their column-compacted copies [T][p] on the mask)
-//             dx      : dX = dG . W1c^T + dU . W3c^T         (T x d, depth 2n)
+//                        + SwiGLU-backward epilogue -> dG, dU [T][n] and, transposed, dG^T, dU^T,
+//                        Act^T [p][T] (neuron-major; under backward masking only the worker's p
+//                        columns are kept, row = rank of the neuron in idx_k)
 //             dw      : dW1[S] = dG^T . X, dW3[S] = dU^T . X, dW2T[S] = Act^T . dY   (p x d, depth T),
-//                        one batched launch; the left operands are read depth-major ([T][p]).
-// Under backward masking the weight-gradient contractions read only the compacted copies: the
-// gradient is computed on the worker's mask and nowhere else.
+//                        one batched launch over the neuron-major copies and XT, dYT
+//             dx      : dX = dG . W1c^T + dU . W3c^T         (T x d, depth 2n)
+// Under backward masking the weight-gradient contraction reads only the p kept rows: the gradient is
+// computed on the worker's mask and nowhere else.  fp32 tensors and bf16 shapes the MFMA kernel does
+// not take go through the plain kernel, which reads dG, dU, Act depth-major as they are (and, under
+// backward masking, their column-compacted copies [T][p]).
 #include "sdp_internal.h"
 
 namespace {

@@ -101,19 +101,4 @@ int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t*
     return launch_status();
 }
 
-// Three transposes of the same shape in one launch (bf16, vector path only: the caller checks).
-int transpose3_bf16(const void* const in[3], int64_t ld_in, int R, int C, void* const out[3], int64_t ld_out,
-                    const char* name, hipStream_t s) {
-    if (R < 1 || C < 1 || C % 8 || R % 8 || ld_in % 8 || ld_out % 8) return SDP_ERR_SHAPE;
-    for (int i = 0; i < 3; ++i)
-        if (!in[i] || !out[i] || !aligned16(in[i]) || !aligned16(out[i])) return SDP_ERR_INVALID_ARG;
-    dim3 grid((R + 63) / 64, (C + 63) / 64, 3);
-    if (grid.y > 65535) return SDP_ERR_SHAPE;
-    Batch3 b{{(const uint16_t*)in[0], (const uint16_t*)in[1], (const uint16_t*)in[2]},
-             {(uint16_t*)out[0], (uint16_t*)out[1], (uint16_t*)out[2]}};
-    ProfileScope ps(name, s);
-    transpose_rows_vec_kernel<<<grid, 256, 0, s>>>(b, ld_in, nullptr, R, C, ld_out);
-    return launch_status();
-}
-
 } // namespace sdp
