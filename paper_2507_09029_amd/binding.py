@@ -248,7 +248,7 @@ def profile_read(cap=64):
     return {names[i].decode(): (int(calls[i]), float(ms[i])) for i in range(n)}
 
 
-def probe_mfma_tflops(operands, blocks=1024, iters=4000):
+def probe_mfma_tflops(operands, blocks=1024, iters=500):
     """Sustained bf16 MFMA rate (TFLOP/s) on the values of `operands` (bf16 tensor on the GPU)."""
     L = lib()
     need = L.sdp_probe_mfma_operand_bytes()
