@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s)
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak (published: 8 TB/s)
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # 256 CUs x 128 fp32 FMA lanes x 2 flop x 2.4 GHz
 
 # HBM-side bytes per launch, from rocprofv3 counter runs (FETCH_SIZE, then WRITE_SIZE, each scaled by
 # what the same counter reads for a 1 GiB copy); the summaries with their commands are
@@ -264,8 +265,10 @@ def main():
         calls, ms = prof[dominant]
         avg_ms = ms / calls
         ach = flops_per_launch(dominant, w) / (avg_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": dominant, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_BF16_TFLOPS,
+        # the fp32 path (config 1, a correctness configuration) runs on the vector ALUs, not on the matrix cores
+        bound, peak = ("mfma", PEAK_BF16_TFLOPS) if w.dtype == "bf16" else ("alu", PEAK_FP32_VECTOR_TFLOPS)
+        roofline = {"bound": bound, "kernel": dominant, "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                    "frac": ach / peak,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)) if S == 1 else None,
                     "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, recorded)",
                     "avg_launch_ms": avg_ms,
@@ -279,7 +282,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "mode": w.mode, "tokens": w.T, "d_model": w.d, "d_ff": w.F, "active_neurons": w.p,
                    "workers_simulated": w.K, "active_flop_per_step": flop_step, "streams": S},
-        "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS,
+        "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS if w.dtype == "bf16" else None,
         "roofline": roofline,
         "kernels": kernels,
         "kernels_note": "per-kernel table from an untimed survey of up to 3 steps with HIP events around every kernel "
