@@ -48,6 +48,8 @@ def lib():
         L.orc_rand_below.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64), ctypes.c_uint64]
         L.orc_make_masks.restype = ctypes.c_int
         L.orc_make_masks.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_int, _u8p]
+        L.orc_make_masks_balanced.restype = ctypes.c_int
+        L.orc_make_masks_balanced.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, _u8p]
         L.orc_index_masks.restype = None
         L.orc_index_masks.argtypes = [ctypes.c_int, ctypes.c_int64, _u8p, _i32p, ctypes.c_int64, _i32p, _i32p, _u8p]
         L.orc_mlp_fwd.restype = None
@@ -96,6 +98,15 @@ def make_masks(K, F, p, seed, require_cover=True):
     rc = lib().orc_make_masks(K, F, p, seed, int(bool(require_cover)), _p(mask, _u8p))
     if rc != 0:
         raise ValueError(f"orc_make_masks failed with {rc}")
+    return mask
+
+
+def make_masks_balanced(K, F, p, seed):
+    """Balanced mask matrix m[K][F] (uint8), row sums p, loads near ceil(K p / F); see orc_make_masks_balanced."""
+    mask = np.zeros((K, F), dtype=np.uint8)
+    rc = lib().orc_make_masks_balanced(K, F, p, seed, _p(mask, _u8p))
+    if rc != 0:
+        raise ValueError(f"orc_make_masks_balanced failed with {rc}")
     return mask
 
 

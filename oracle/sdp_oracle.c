@@ -125,6 +125,74 @@ int orc_make_masks(int K, int F, int p, uint64_t seed, int require_cover, uint8_
 }
 
 /* ------------------------------------------------------------------------- */
+/* Balanced mask construction (App. A, Algorithm "Structured Mask             */
+/* Construction"): exact row budget p, column loads pushed towards the target */
+/* t = ceil(K p / F).                                                         */
+/* Phase 1, worker i = 0..K-1 (stream 2^20 + i): weights from the loads of    */
+/* the workers before it, w_j = max(t - c_j, eps) with eps = 1e-6, held as    */
+/* integers 10^6 (t - c_j) or 1; p distinct columns by successive draws with  */
+/* renormalisation: u uniform below the total weight of the columns not yet   */
+/* taken, the column whose running sum first exceeds u is taken.              */
+/* Phase 2, column j ascending, while c_j < t: the first worker (ascending)   */
+/* that does not hold j but holds a column of load > t takes j and gives up   */
+/* its most loaded such column (lowest index on ties); when no worker         */
+/* qualifies the column is left as it is.  As printed, the phase asks for     */
+/* rows below budget, of which there are none after phase 1, and then removes */
+/* a surplus column from rows above budget: the reading here keeps every row  */
+/* sum at p at all times.                                                     */
+/* Returns 0, or -1 on bad arguments.                                         */
+/* ------------------------------------------------------------------------- */
+int orc_make_masks_balanced(int K, int F, int p, uint64_t seed, uint8_t* mask) {
+    if (K < 1 || F < 1 || p < 0 || p > F || !mask) return -1;
+    memset(mask, 0, (size_t)K * F);
+    if (p == 0) return 0;
+    const int64_t t = ((int64_t)K * p + F - 1) / F;
+    int64_t* load = (int64_t*)calloc((size_t)F, sizeof(int64_t));
+    uint64_t* w = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)F);
+    for (int i = 0; i < K; ++i) {
+        orc_rng r = {seed, (uint64_t)(1 << 20) + (uint64_t)i, 0};
+        uint8_t* row = mask + (size_t)i * F;
+        for (int j = 0; j < F; ++j) w[j] = load[j] < t ? (uint64_t)(t - load[j]) * 1000000ULL : 1ULL;
+        for (int d = 0; d < p; ++d) {
+            uint64_t total = 0;
+            for (int j = 0; j < F; ++j)
+                if (!row[j]) total += w[j];
+            uint64_t u = rng_below(&r, total);
+            uint64_t run = 0;
+            for (int j = 0; j < F; ++j) {
+                if (row[j]) continue;
+                run += w[j];
+                if (run > u) {
+                    row[j] = 1;
+                    break;
+                }
+            }
+        }
+        for (int j = 0; j < F; ++j) load[j] += row[j];
+    }
+    for (int j = 0; j < F; ++j) {
+        while (load[j] < t) {
+            int moved = 0;
+            for (int i = 0; i < K && !moved; ++i) {
+                uint8_t* row = mask + (size_t)i * F;
+                if (row[j]) continue;
+                int donor = -1;
+                for (int k = 0; k < F; ++k)
+                    if (row[k] && load[k] > t && (donor < 0 || load[k] > load[donor])) donor = k;
+                if (donor < 0) continue;
+                row[j] = 1, load[j] += 1;
+                row[donor] = 0, load[donor] -= 1;
+                moved = 1;
+            }
+            if (!moved) break;
+        }
+    }
+    free(load);
+    free(w);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Index form of a mask: idx[k][i] = i-th active neuron of worker k in         */
 /* ascending order (entries past count[k] are -1; row stride idx_ld),          */
 /* pos[k][j] = rank of j inside worker k's active set or -1,                   */
