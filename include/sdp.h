@@ -53,6 +53,8 @@ typedef enum {
 typedef enum { SDP_F32 = 0, SDP_BF16 = 1 } sdp_dtype;
 typedef enum { SDP_MASK_FORWARD = 0, SDP_MASK_BACKWARD = 1 } sdp_mode;
 typedef enum { SDP_DW_COMPACT = 0, SDP_DW_SCATTER = 1 } sdp_dw_layout;
+/* values of the `require_cover` argument of the samplers */
+typedef enum { SDP_MASKS_UNIFORM = 0, SDP_MASKS_UNIFORM_COVER = 1, SDP_MASKS_BALANCED = 2 } sdp_mask_sampler;
 
 #define SDP_MAX_WORKERS 64 /* largest K accepted anywhere */
 
@@ -66,13 +68,18 @@ const char* sdp_status_string(int status);
  * derives its index form there (see sdp_index_masks).  Sampler: worker k takes p distinct neurons
  * uniformly (partial Fisher-Yates on the counter-based stream k); with require_cover != 0 every
  * neuron left with load 0 is then given to a worker that hands back a neuron of load >= 2, so all
- * row sums stay p and every c_j >= 1.  The draw is a pure function of (K, F, p, seed,
- * require_cover).
+ * row sums stay p and every c_j >= 1.  require_cover = SDP_MASKS_BALANCED (2) selects the balanced
+ * construction of App. A (Algorithm "Structured Mask Construction") instead: worker i draws its p
+ * neurons with weights max(t - c_j, 1e-6), t = ceil(K p / F), c_j the loads of the workers before it
+ * (successive weighted draws on stream 2^20 + i), then under-loaded neurons j (ascending) are handed
+ * to the first worker that lacks j and holds a neuron loaded above t, which gives up its most
+ * loaded such neuron; row sums are p throughout, loads end within one of K p / F whenever K p is a
+ * multiple of F.  The draw is a pure function of (K, F, p, seed, require_cover).
  *   mask  [K][F] u8 out     idx [K][p] i32 out     pos [K][F] i32 out     cov [F] u8 out
  *   ws: sdp_index_masks_workspace_bytes(K, F).
  * The call synchronises `stream` before returning (the host staging buffer is freed).
- * Errors: INVALID_ARG (null, K < 1, K > SDP_MAX_WORKERS, F < 1, p < 0), SHAPE (p > F),
- * UNCOVERED (require_cover and K p < F), WORKSPACE, HIP.
+ * Errors: INVALID_ARG (null, K < 1, K > SDP_MAX_WORKERS, F < 1, p < 0, require_cover not 0..2),
+ * SHAPE (p > F), UNCOVERED (require_cover = 1 and K p < F), WORKSPACE, HIP.
  * ------------------------------------------------------------------------------------------- */
 int sdp_make_masks(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask, int32_t* idx,
                    int32_t* pos, uint8_t* cov, void* ws, size_t ws_bytes, void* stream);

@@ -103,10 +103,17 @@ def _ws(nbytes, device):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def _sampler(require_cover):
+    """False / True -> uniform sampler without / with coverage repair; "balanced" (or 2) -> App. A's construction."""
+    if require_cover == "balanced":
+        return 2
+    return int(require_cover) if isinstance(require_cover, int) and not isinstance(require_cover, bool) else int(bool(require_cover))
+
+
 def sample_masks_host(K, F, p, seed, require_cover=True):
     """The library's host sampler alone: uint8 [K][F] CPU tensor."""
     mask = torch.zeros((K, F), dtype=torch.uint8)
-    _check(lib().sdp_sample_masks_host(K, F, p, seed, int(bool(require_cover)), mask.data_ptr()), "sdp_sample_masks_host")
+    _check(lib().sdp_sample_masks_host(K, F, p, seed, _sampler(require_cover), mask.data_ptr()), "sdp_sample_masks_host")
     return mask
 
 
@@ -121,7 +128,7 @@ def make_masks(K, F, p, seed, require_cover=True, device="cuda"):
     pos = torch.empty((K, F), dtype=torch.int32, device=device)
     cov = torch.empty((F,), dtype=torch.uint8, device=device)
     ws = _ws(index_masks_workspace_bytes(K, F), device)
-    st = lib().sdp_make_masks(K, F, p, seed, int(bool(require_cover)), mask.data_ptr(), idx.data_ptr(), pos.data_ptr(),
+    st = lib().sdp_make_masks(K, F, p, seed, _sampler(require_cover), mask.data_ptr(), idx.data_ptr(), pos.data_ptr(),
                               cov.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(st, "sdp_make_masks")
     return mask, idx, pos, cov

@@ -84,6 +84,94 @@ int sample_masks(int K, int F, int p, uint64_t seed, bool cover, uint8_t* m) {
     return SDP_OK;
 }
 
+// Balanced construction (App. A, Algorithm "Structured Mask Construction"): exact row budget p, column loads
+// pushed towards t = ceil(K p / F).
+// Phase 1: worker i (stream 2^20 + i) weighs column j by max(t - c_j, 1e-6) with c the loads of the workers
+// before it (kept as integers: 10^6 (t - c_j), or 1), and takes p distinct columns by successive weighted
+// draws: u uniform below the weight still on offer, then the first column whose running weight exceeds u.
+// A Fenwick tree over the weights finds that column in log F steps and takes its weight off the offer.
+// Phase 2: for each column j in ascending order, while c_j < t, the first worker in ascending order that
+// lacks j and holds some column loaded above t swaps its most loaded such column (lowest index on ties)
+// for j; a column for which no worker qualifies stays as it is.  Row sums are p throughout.
+class WeightTree {
+  public:
+    explicit WeightTree(int n) : n_(n), top_(1), node_(n + 1, 0) {
+        while (top_ * 2 <= n) top_ *= 2;
+    }
+    void assign(const std::vector<uint64_t>& w) {
+        std::fill(node_.begin(), node_.end(), (uint64_t)0);
+        for (int j = 0; j < n_; ++j) node_[j + 1] = w[j];
+        for (int i = 1; i <= n_; ++i) {
+            const int up = i + (i & -i);
+            if (up <= n_) node_[up] += node_[i];
+        }
+        total_ = 0;
+        for (int j = 0; j < n_; ++j) total_ += w[j];
+    }
+    uint64_t total() const { return total_; }
+    void remove(int j, uint64_t w) {
+        for (int i = j + 1; i <= n_; i += i & -i) node_[i] -= w;
+        total_ -= w;
+    }
+    // smallest j whose inclusive prefix weight exceeds u (u < total)
+    int find(uint64_t u) const {
+        int pos = 0;
+        for (int step = top_; step > 0; step >>= 1) {
+            const int nxt = pos + step;
+            if (nxt <= n_ && node_[nxt] <= u) {
+                pos = nxt;
+                u -= node_[nxt];
+            }
+        }
+        return pos;
+    }
+
+  private:
+    int n_, top_;
+    uint64_t total_ = 0;
+    std::vector<uint64_t> node_;
+};
+
+int sample_masks_balanced(int K, int F, int p, uint64_t seed, uint8_t* m) {
+    std::fill(m, m + (size_t)K * F, (uint8_t)0);
+    if (p == 0) return SDP_OK;
+    const int64_t target = ((int64_t)K * p + F - 1) / F;
+    std::vector<int64_t> c(F, 0);
+    std::vector<uint64_t> w(F);
+    WeightTree tree(F);
+    for (int i = 0; i < K; ++i) {
+        Stream rng(seed, ((uint64_t)1 << 20) + (uint64_t)i);
+        uint8_t* row = m + (size_t)i * F;
+        for (int j = 0; j < F; ++j) w[j] = c[j] < target ? (uint64_t)(target - c[j]) * 1000000ull : 1ull;
+        tree.assign(w);
+        for (int d = 0; d < p; ++d) {
+            const int j = tree.find(rng.below(tree.total()));
+            row[j] = 1;
+            tree.remove(j, w[j]);
+        }
+        for (int j = 0; j < F; ++j) c[j] += row[j];
+    }
+    // phase 2: per worker, its columns above the target, found on demand
+    for (int j = 0; j < F; ++j) {
+        while (c[j] < target) {
+            bool swapped = false;
+            for (int i = 0; i < K && !swapped; ++i) {
+                uint8_t* row = m + (size_t)i * F;
+                if (row[j]) continue;
+                int give = -1;
+                for (int k = 0; k < F; ++k)
+                    if (row[k] && c[k] > target && (give < 0 || c[k] > c[give])) give = k;
+                if (give < 0) continue;
+                row[give] = 0, --c[give];
+                row[j] = 1, ++c[j];
+                swapped = true;
+            }
+            if (!swapped) break;
+        }
+    }
+    return SDP_OK;
+}
+
 // ---- device side ---------------------------------------------------------------------------
 constexpr int kScanThreads = 256;
 constexpr int kPerThread = 8;
@@ -230,6 +318,8 @@ extern "C" int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* i
 extern "C" int sdp_sample_masks_host(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask_host) {
     if (!mask_host || K < 1 || K > SDP_MAX_WORKERS || F < 1 || p < 0) return SDP_ERR_INVALID_ARG;
     if (p > F) return SDP_ERR_SHAPE;
+    if (require_cover < 0 || require_cover > SDP_MASKS_BALANCED) return SDP_ERR_INVALID_ARG;
+    if (require_cover == SDP_MASKS_BALANCED) return sample_masks_balanced(K, F, p, seed, mask_host);
     if (require_cover && (int64_t)K * p < F) return SDP_ERR_UNCOVERED;
     return sample_masks(K, F, p, seed, require_cover != 0, mask_host);
 }
@@ -239,11 +329,13 @@ extern "C" int sdp_make_masks(int K, int F, int p, uint64_t seed, int require_co
     if (!mask || !idx || !pos || !cov) return SDP_ERR_INVALID_ARG;
     if (K < 1 || K > SDP_MAX_WORKERS || F < 1 || p < 0) return SDP_ERR_INVALID_ARG;
     if (p > F) return SDP_ERR_SHAPE;
-    if (require_cover && (int64_t)K * p < F) return SDP_ERR_UNCOVERED;
+    if (require_cover < 0 || require_cover > SDP_MASKS_BALANCED) return SDP_ERR_INVALID_ARG;
+    if (require_cover == SDP_MASKS_UNIFORM_COVER && (int64_t)K * p < F) return SDP_ERR_UNCOVERED;
     if (!ws || ws_bytes < sdp_index_masks_workspace_bytes(K, F)) return SDP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     std::vector<uint8_t> host((size_t)K * F);
-    int rc = sample_masks(K, F, p, seed, require_cover != 0, host.data());
+    int rc = require_cover == SDP_MASKS_BALANCED ? sample_masks_balanced(K, F, p, seed, host.data())
+                                                 : sample_masks(K, F, p, seed, require_cover != 0, host.data());
     if (rc != SDP_OK) return rc;
     if (hipMemcpyAsync(mask, host.data(), host.size(), hipMemcpyHostToDevice, s) != hipSuccess) return SDP_ERR_HIP;
     if (p > 0) {

@@ -112,6 +112,26 @@ def test_host_sampler_matches_oracle_bit_for_bit(orc, K, F, p, cover):
         assert (got == want).all()
 
 
+@pytest.mark.parametrize("K,F,p", [
+    (4, 1024, 512), (4, 4096, 2048), (8, 5504, 4128), (3, 100, 41), (6, 97, 13), (5, 64, 64), (2, 50, 1), (3, 10, 0),
+    (8, 688, 516), (1, 33, 7),
+])
+def test_balanced_sampler_matches_oracle_bit_for_bit(orc, K, F, p):
+    # the library finds each weighted pick with a Fenwick tree, the oracle by a linear scan
+    for seed in (20250709, 7, 2**63 + 12345):
+        got = sdp.sample_masks_host(K, F, p, seed, "balanced").numpy()
+        want = orc.make_masks_balanced(K, F, p, seed)
+        assert (got == want).all()
+
+
+def test_sampler_mode_is_validated():
+    L = sdp.lib()
+    buf = (ctypes.c_uint8 * 64)()
+    assert L.sdp_sample_masks_host(2, 16, 8, 1, 3, buf) == -1
+    assert L.sdp_sample_masks_host(2, 16, 8, 1, -1, buf) == -1
+    assert L.sdp_sample_masks_host(2, 16, 4, 1, 2, buf) == 0  # balanced mode does not need K p >= F
+
+
 def test_binding_module_does_not_touch_the_oracle():
     src = open(binding.__file__).read() + open(os.path.join(os.path.dirname(binding.__file__), "__init__.py")).read()
     assert "oracle" not in src

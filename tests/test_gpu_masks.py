@@ -40,6 +40,23 @@ def test_make_masks_matches_oracle(sdp, orc, K, F, p, seed, cover):
     assert (wcount == p).all()
 
 
+@pytest.mark.parametrize("K,F,p,seed", [
+    (workloads.CONFIG2.K, workloads.CONFIG2.F, workloads.CONFIG2.p, 31), (workloads.CONFIG3.K, workloads.CONFIG3.F, workloads.CONFIG3.p, 32),
+    (3, 100, 41, 33), (6, 2049, 300, 34),
+])
+def test_make_masks_balanced_matches_oracle(sdp, orc, K, F, p, seed):
+    print(f"make_masks balanced K={K} F={F} p={p} seed={seed}", flush=True)
+    mask, idx, pos, cov = sdp.make_masks(K, F, p, seed, "balanced")
+    torch.cuda.synchronize()
+    want_mask = orc.make_masks_balanced(K, F, p, seed)
+    widx, wpos, wcount, wcov = orc.index_masks(want_mask, idx_ld=p)
+    assert (mask.cpu().numpy() == want_mask).all()
+    assert (idx.cpu().numpy() == widx).all()
+    assert (pos.cpu().numpy() == wpos).all()
+    assert (cov.cpu().numpy() == wcov).all()
+    assert (wcount == p).all()
+
+
 @pytest.mark.parametrize("K,F,density,idx_ld", [
     (5, 333, 0.4, 333), (8, 2048, 0.5, 2048), (3, 2049, 0.9, 100), (1, 6000, 0.01, 6000), (8, 100000, 0.69, 100000),
 ])
