@@ -1,4 +1,6 @@
 """Shared test utilities: the error metric used for every floating-point comparison."""
+import os
+
 import numpy as np
 
 
@@ -27,5 +29,7 @@ def err_report(got, ref):
 
 def assert_close(got, ref, tol, what=""):
     elem, norm = err_report(got, ref)
+    if os.environ.get("SDP_TEST_VERBOSE"):
+        print(f"[err] {what}: elementwise {elem:.3e} normwise {norm:.3e} (tol {tol:.0e})", flush=True)
     assert elem <= tol and norm <= tol, f"{what}: elementwise {elem:.3e}, normwise {norm:.3e} > tol {tol:.1e}"
     return elem, norm
