@@ -51,6 +51,22 @@ def test_avg_matches_oracle_with_poisoned_off_mask_rows(sdp, orc, K, R, D, p, dt
     assert torch.equal(out2, out)
 
 
+def test_avg_block_level_masks(sdp, orc):
+    """Block-level subnetworks (Sec. 3.2: a worker keeps or skips whole blocks): the same average with one mask
+    byte per block, a row being all the parameters of a block.  32 blocks of 2^20 parameters, 22 kept per worker
+    (the paper's 1B setting keeps 22 of 32 blocks), 8 workers."""
+    K, R, D, p = 8, 32, 1 << 20, 22
+    mask = orc.make_masks(K, R, p, 91, True)
+    tmask = torch.from_numpy(mask)
+    print(f"avg block-level K={K} blocks={R} D={D} p={p}", flush=True)
+    grads = workloads.grad_buffers(K, R, D, 1e-3, "bf16", device="cuda", poison_mask=tmask)
+    out, cov = sdp.coverage_grad_avg(grads, tmask.cuda())
+    torch.cuda.synchronize()
+    want, wcov = orc.gated_average([workloads.bf16_bits(g) for g in grads], mask)
+    assert (cov.cpu().numpy() == wcov).all() and (wcov >= 1).all()
+    assert_close(out.cpu().numpy(), want, TOL_SUM, "block-level avg")
+
+
 def test_avg_full_coverage_is_the_mean_and_single_worker_is_identity(sdp):
     K, R, D = 8, 100, 1024
     grads = [g.cuda() for g in workloads.grad_buffers(K, R, D, 1.0, "f32")]
