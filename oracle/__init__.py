@@ -50,6 +50,8 @@ def lib():
         L.orc_make_masks.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_int, _u8p]
         L.orc_make_masks_balanced.restype = ctypes.c_int
         L.orc_make_masks_balanced.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, _u8p]
+        L.orc_avg_adamw.restype = None
+        L.orc_avg_adamw.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), _u8p, _f64p, _f64p, _f64p, _u8p] + [ctypes.c_double] * 6 + [ctypes.c_int]
         L.orc_index_masks.restype = None
         L.orc_index_masks.argtypes = [ctypes.c_int, ctypes.c_int64, _u8p, _i32p, ctypes.c_int64, _i32p, _i32p, _u8p]
         L.orc_mlp_fwd.restype = None
@@ -189,6 +191,28 @@ def gated_average(g_list, mask):
     cov = np.empty((R,), dtype=np.uint8)
     lib().orc_gated_average(K, R, D, gtype, ptrs, _p(mask, _u8p), _p(out, _f64p), _p(cov, _u8p))
     return out, cov
+
+
+def avg_adamw(g_list, mask, theta, m, v, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0):
+    """Gated average followed by AdamW on covered rows; see orc_avg_adamw.
+
+    theta, m, v: arrays [R][D] of any float dtype (widened exactly); returns new fp64 (theta, m, v, cov).
+    """
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, R = mask.shape
+    g_list = [np.ascontiguousarray(g) for g in g_list]
+    D = g_list[0].shape[1]
+    dt = g_list[0].dtype
+    gtype = {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float64): 2}[dt]
+    for g in g_list:
+        assert g.shape == (R, D) and g.dtype == dt
+    th, mm, vv = (np.array(a, dtype=np.float64, order="C", copy=True) for a in (theta, m, v))
+    assert th.shape == mm.shape == vv.shape == (R, D)
+    ptrs = (ctypes.c_void_p * K)(*[g.ctypes.data for g in g_list])
+    cov = np.empty((R,), dtype=np.uint8)
+    lib().orc_avg_adamw(K, R, D, gtype, ptrs, _p(mask, _u8p), _p(th, _f64p), _p(mm, _f64p), _p(vv, _f64p), _p(cov, _u8p),
+                        float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), float(grad_scale), int(step))
+    return th, mm, vv, cov
 
 
 def rho2(mask):

@@ -384,6 +384,42 @@ void orc_gated_average(int K, int64_t R, int64_t D, int gtype, const void* const
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* The gated average followed by the optimizer the paper trains with (AdamW,   */
+/* App. "Hyperparameters for LLM Architecture"), on covered rows only         */
+/* (Sec. 3.2: parameters, gradients and optimizer state live only on covered  */
+/* coordinates).  For every row r with c_r >= 1 and each of its parameters:   */
+/*   ghat  = grad_scale * (1/c_r) * sum_{k covers r} g_k                      */
+/*   theta = theta - lr * wd * theta                  (decoupled weight decay) */
+/*   m     = beta1 m + (1 - beta1) ghat,   v = beta2 v + (1 - beta2) ghat^2    */
+/*   theta = theta - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)*/
+/* Rows with c_r = 0 keep theta, m, v.  Everything in fp64; theta, m, v are    */
+/* updated in place.                                                          */
+/* ------------------------------------------------------------------------- */
+void orc_avg_adamw(int K, int64_t R, int64_t D, int gtype, const void* const* g, const uint8_t* mask,
+                   double* theta, double* m, double* v, uint8_t* cov, double lr, double beta1, double beta2,
+                   double eps, double wd, double grad_scale, int step) {
+    const double bc1 = 1.0 - pow(beta1, (double)step), bc2 = 1.0 - pow(beta2, (double)step);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r) {
+        int c = 0;
+        for (int k = 0; k < K; ++k) c += mask[(int64_t)k * R + r] ? 1 : 0;
+        cov[r] = (uint8_t)c;
+        if (c == 0) continue;
+        for (int64_t e = 0; e < D; ++e) {
+            const int64_t i = r * D + e;
+            double s = 0.0;
+            for (int k = 0; k < K; ++k)
+                if (mask[(int64_t)k * R + r]) s += widen(g[k], gtype, i);
+            const double ghat = grad_scale * (s / (double)c);
+            theta[i] -= lr * wd * theta[i];
+            m[i] = beta1 * m[i] + (1.0 - beta1) * ghat;
+            v[i] = beta2 * v[i] + (1.0 - beta2) * ghat * ghat;
+            theta[i] -= lr * (m[i] / bc1) / (sqrt(v[i] / bc2) + eps);
+        }
+    }
+}
+
 /* Squared Frobenius distance to uniform masking (Thm. 3.1) with per-column    */
 /* loads:  rho^2 = sum_{k,j} (1/K - m_kj / c_j)^2, columns with c_j = 0 give   */
 /* K (1/K)^2.                                                                  */
