@@ -111,13 +111,42 @@ def bench_grad_avg_1b(sdp, torch, steps):
     calls, ms = prof["coverage_grad_avg"]
     kern = ms / calls * 1e-3
     gbs = c.algorithmic_bytes / kern / 1e9
-    return {
+    res = {
         "workload": c.name, "K": c.K, "rows": c.R, "row_len": c.D, "covered_rows_per_worker": c.p,
         "algorithmic_bytes": c.algorithmic_bytes, "ms_per_call": kern * 1e3, "ms_per_call_wall": wall * 1e3,
         "value": gbs, "unit": "GB/s",
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((c.name, "coverage_grad_avg"))},
     }
+    # the same pass with AdamW fused in: besides the covered gradient rows it reads and writes the fp32
+    # parameters and both moments of every covered row once
+    del out
+    covered = int((mask_host.sum(dim=0) > 0).sum())
+    theta = torch.randn((c.R, c.D), device="cuda") * 0.02
+    m = torch.zeros((c.R, c.D), device="cuda")
+    v = torch.zeros((c.R, c.D), device="cuda")
+    hp = dict(lr=4e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    for t in range(1, 3):
+        sdp.coverage_avg_adamw(grads, mask, theta, m, v, step=t, cov=cov, **hp)
+    torch.cuda.synchronize()
+    sdp.profile_reset()
+    sdp.profile_enable(True)
+    nst = max(3, steps // 2)
+    for t in range(3, 3 + nst):
+        sdp.coverage_avg_adamw(grads, mask, theta, m, v, step=t, cov=cov, **hp)
+    torch.cuda.synchronize()
+    prof = sdp.profile_read()
+    sdp.profile_enable(False)
+    calls, ms = prof["coverage_avg_adamw"]
+    kern = ms / calls * 1e-3
+    abytes = c.K * c.p * c.D * 2 + c.K * c.R + c.R + 6 * covered * c.D * 4
+    res["adamw_fused"] = {
+        "algorithmic_bytes": abytes, "covered_rows": covered, "ms_per_call": kern * 1e3,
+        "roofline": {"bound": "hbm", "achieved": abytes / kern / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": abytes / kern / 1e9 / PEAK_HBM_GBS, "traffic": None},
+        "note": "covered gradient rows (bf16) + masks read; theta, m, v (fp32) of covered rows read and written",
+    }
+    return res
 
 
 def main():

@@ -158,6 +158,32 @@ int sdp_coverage_grad_avg(int K, int64_t R, int D, int gdtype, const void* const
                           float* out, uint8_t* cov, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The same pass with the optimizer fused in (the paper trains with AdamW, App. "Hyperparameters for
+ * LLM Architecture": beta1 = 0.9, beta2 = 0.95, weight decay 0.1; Sec. 3.2: parameters, gradients and
+ * optimizer state exist only for covered coordinates): for every row r with c_r >= 1 and every
+ * parameter e of it, with ghat = grad_scale * (1 / c_r) * sum_{k covers r} g_k[r][e],
+ *     theta <- theta (1 - lr wd);  m <- beta1 m + (1 - beta1) ghat;  v <- beta2 v + (1 - beta2) ghat^2;
+ *     theta <- theta - lr / (1 - beta1^t) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps)
+ * (decoupled weight decay, bias-corrected moments, t = step >= 1), all in fp32.  Rows with c_r = 0 are
+ * left untouched: no gradient reached them, and neither decay nor moment update is applied.
+ * grad_scale carries a clipping coefficient computed elsewhere (1 = none).  The averaged gradient
+ * itself is not stored.
+ *   g, mask, cov   as for sdp_coverage_grad_avg
+ *   theta, m, v    [R][D] fp32, updated in place (each row read and written once)
+ *   theta_bf16     [R][D] bf16 out, may be NULL: the updated parameters rounded to nearest even, i.e.
+ *                  the weights of the next step's bf16 contractions (covered rows only)
+ * Errors: INVALID_ARG (null, misaligned, K or D out of range, lr < 0, beta outside [0, 1), eps <= 0,
+ * weight_decay < 0, step < 1, non-finite grad_scale), SHAPE (R D > 2^40).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay, grad_scale;
+    int step; /* t, counted from 1 */
+} sdp_adamw_params;
+int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
+                           float* theta, float* m, float* v, void* theta_bf16, uint8_t* cov,
+                           const sdp_adamw_params* hp, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Per-kernel timing.  With profiling on, every kernel launch is bracketed by HIP events on its
  * stream.  sdp_profile_read synchronises those events and returns, for up to `cap` distinct
  * kernel names, the launch count and total milliseconds since the last reset.

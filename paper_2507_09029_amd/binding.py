@@ -66,6 +66,8 @@ def lib():
     L.sdp_masked_mlp_bwd.argtypes = [i32] * 6 + [vp] * 12 + [i32, vp, sz, vp]
     L.sdp_coverage_grad_avg.restype = i32
     L.sdp_coverage_grad_avg.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp]
+    L.sdp_coverage_avg_adamw.restype = i32
+    L.sdp_coverage_avg_adamw.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp, vp, vp, vp, vp]
     L.sdp_profile_enable.restype = i32
     L.sdp_profile_enable.argtypes = [i32]
     L.sdp_profile_filter.restype = i32
@@ -230,6 +232,39 @@ def coverage_grad_avg(grads, mask, out=None, cov=None):
                                      _dev(out, torch.float32, "out"), _dev(cov, torch.uint8, "cov"), _stream())
     _check(st, "sdp_coverage_grad_avg")
     return out, cov
+
+
+class AdamWParams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("grad_scale", ctypes.c_float), ("step", ctypes.c_int)]
+
+
+def coverage_avg_adamw(grads, mask, theta, m, v, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0,
+                       theta_bf16=None, cov=None):
+    """Coverage average fused with AdamW on covered rows: theta, m, v (fp32 [R][D]) are updated in place.
+
+    theta_bf16 (optional bf16 [R][D]) receives the updated parameters of covered rows.  Returns cov u8 [R].
+    """
+    K = len(grads)
+    if K < 1 or K > MAX_WORKERS:
+        raise SdpError(-1, "sdp_coverage_avg_adamw")
+    dt = grads[0].dtype
+    R, D = grads[0].shape
+    ptrs = (ctypes.c_void_p * K)(*[_dev(g, dt, f"grads[{i}]") for i, g in enumerate(grads)])
+    for t, name in ((theta, "theta"), (m, "m"), (v, "v")):
+        if tuple(t.shape) != (R, D):
+            raise ValueError(f"{name} must be [R][D]")
+    if tuple(mask.shape) != (K, R):
+        raise ValueError("mask must be [K][R]")
+    if cov is None:
+        cov = torch.empty((R,), dtype=torch.uint8, device=grads[0].device)
+    hp = AdamWParams(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+    lowp = _dev(theta_bf16, torch.bfloat16, "theta_bf16") if theta_bf16 is not None else None
+    st = lib().sdp_coverage_avg_adamw(K, R, D, _DTYPES[dt], ptrs, _dev(mask, torch.uint8, "mask"),
+                                      _dev(theta, torch.float32, "theta"), _dev(m, torch.float32, "m"),
+                                      _dev(v, torch.float32, "v"), lowp, _dev(cov, torch.uint8, "cov"), ctypes.byref(hp), _stream())
+    _check(st, "sdp_coverage_avg_adamw")
+    return cov
 
 
 def profile_enable(on=True):

@@ -5,13 +5,50 @@
 // covers it (16-byte loads, non-temporal), sums them in fp32 in worker order, divides by the
 // coverage count and writes fp32 (non-temporal stores).  No atomics: the result is a pure function
 // of the inputs.
+//
+// The same pass can apply the optimizer instead of storing the average (sdp_coverage_avg_adamw):
+// the averaged gradient of a covered row goes straight into a decoupled-weight-decay Adam update of
+// that row's fp32 parameters and moments, which are read and written once; rows nobody covers are
+// left untouched.
 #include "sdp_internal.h"
+
+#include <cmath>
 
 namespace {
 
 struct GradPtrs {
     const void* p[SDP_MAX_WORKERS];
 };
+
+// optimizer state and hyper-parameters of the fused update (OPT = 1)
+struct AdamArgs {
+    float* theta;
+    float* m;
+    float* v;
+    uint16_t* theta_bf16; // optional bf16 copy of the updated parameters
+    float decay;          // 1 - lr * weight_decay
+    float beta1, beta2;
+    float step_size;      // lr / (1 - beta1^t)
+    float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^t)
+    float eps;
+    float grad_scale;
+};
+
+__device__ inline uint32_t pack2_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 p = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+// one parameter: (theta, m, v) <- AdamW(theta, m, v, g)
+__device__ inline void adamw_one(const AdamArgs& a, float g, float& th, float& m, float& v) {
+    g *= a.grad_scale;
+    th *= a.decay;
+    m = a.beta1 * m + (1.0f - a.beta1) * g;
+    v = a.beta2 * v + (1.0f - a.beta2) * g * g;
+    const float denom = __builtin_sqrtf(v) * a.inv_sqrt_bc2 + a.eps;
+    th -= a.step_size * (m / denom);
+}
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -32,9 +69,10 @@ __device__ inline void add_bf16x8(const u32x4 w, float (&acc)[8]) {
 // Requires D % 8 == 0.  BF16: 1 = bf16 input, 0 = fp32 input.
 constexpr int kBatch = 8;
 
-template <int BF16>
+template <int BF16, int OPT>
 __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t* __restrict__ mask, int K, int64_t R,
-                                                       int D, float* __restrict__ out, uint8_t* __restrict__ cov) {
+                                                       int D, float* __restrict__ out, uint8_t* __restrict__ cov,
+                                                       AdamArgs ad) {
     const int segs = (D + 511) / 512; // wave-segments per row
     const int64_t nitems = R * segs;
     const int lane = threadIdx.x & 63;
@@ -48,6 +86,17 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
         const int64_t off = r * D + e0;
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         int c = 0;
+        // optimizer state of the segment: requested first, so that it travels while the gradients are summed
+        // (rows nobody covers are read too, which is harmless and rare, and never written back)
+        f32x4 th[2], mm[2], vv[2];
+        if (OPT && live) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                th[h] = *((const f32x4*)(ad.theta + off) + h);
+                mm[h] = *((const f32x4*)(ad.m + off) + h);
+                vv[h] = *((const f32x4*)(ad.v + off) + h);
+            }
+        }
         for (int k0 = 0; k0 < K; k0 += kBatch) {
             bool covered[kBatch];
             u32x4 lo[kBatch];
@@ -82,7 +131,7 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
                 }
             }
         }
-        if (live) {
+        if (live && !OPT) {
             // c == 0: nobody covers the row, the average is defined as 0 (acc is still 0)
             const float denom = c > 0 ? (float)c : 1.0f;
             f32x4 a, b;
@@ -95,14 +144,38 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
             __builtin_nontemporal_store(a, dst);
             __builtin_nontemporal_store(b, dst + 1);
         }
+        if (live && OPT && c > 0) {
+            // rows nobody covers keep their parameters and moments
+            const float denom = (float)c;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float t = th[h][i], m1 = mm[h][i], v1 = vv[h][i];
+                    adamw_one(ad, acc[4 * h + i] / denom, t, m1, v1);
+                    th[h][i] = t, mm[h][i] = m1, vv[h][i] = v1;
+                }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                *((f32x4*)(ad.theta + off) + h) = th[h];
+                *((f32x4*)(ad.m + off) + h) = mm[h];
+                *((f32x4*)(ad.v + off) + h) = vv[h];
+            }
+            if (ad.theta_bf16) {
+                const u32x4 packed = {pack2_bf16(th[0][0], th[0][1]), pack2_bf16(th[0][2], th[0][3]),
+                                      pack2_bf16(th[1][0], th[1][1]), pack2_bf16(th[1][2], th[1][3])};
+                __builtin_nontemporal_store(packed, (u32x4*)(ad.theta_bf16 + off));
+            }
+        }
         if (cov && seg == 0 && lane == 0) cov[r] = (uint8_t)c;
     }
 }
 
 // Any D: one thread per parameter.
-template <int BF16>
+template <int BF16, int OPT>
 __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_t* __restrict__ mask, int K, int64_t R,
-                                                        int D, float* __restrict__ out, uint8_t* __restrict__ cov) {
+                                                        int D, float* __restrict__ out, uint8_t* __restrict__ cov,
+                                                        AdamArgs ad) {
     const int64_t n = R * D;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = i / D;
@@ -116,9 +189,54 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
             else
                 acc += ((const float*)g.p[k])[i];
         }
-        out[i] = acc / (c > 0 ? (float)c : 1.0f);
+        if (!OPT) {
+            out[i] = acc / (c > 0 ? (float)c : 1.0f);
+        } else if (c > 0) {
+            float t = ad.theta[i], m1 = ad.m[i], v1 = ad.v[i];
+            adamw_one(ad, acc / (float)c, t, m1, v1);
+            ad.theta[i] = t, ad.m[i] = m1, ad.v[i] = v1;
+            if (ad.theta_bf16) ad.theta_bf16[i] = (uint16_t)(pack2_bf16(t, 0.f) & 0xFFFFu);
+        }
         if (cov && i == r * D) cov[r] = (uint8_t)c;
     }
+}
+
+// argument checks and launch shared by the two entry points; ad == nullptr: store the average into out
+int launch_average(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask, float* out,
+                   uint8_t* cov, const AdamArgs* ad, const char* name, hipStream_t s) {
+    GradPtrs ptrs;
+    for (int k = 0; k < K; ++k) {
+        if (!g[k] || !sdp::aligned16(g[k])) return SDP_ERR_INVALID_ARG;
+        ptrs.p[k] = g[k];
+    }
+    for (int k = K; k < SDP_MAX_WORKERS; ++k) ptrs.p[k] = nullptr;
+    const AdamArgs a = ad ? *ad : AdamArgs{};
+    sdp::ProfileScope ps(name, s);
+    if (D % 8 == 0) {
+        const int segs = (D + 511) / 512;
+        const int64_t items = R * segs;
+        const int64_t blocks64 = (items + 3) / 4; // 4 waves per workgroup
+        const unsigned blocks = (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
+        if (gdtype == SDP_BF16) {
+            if (ad) avg_rows_kernel<1, 1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+            else avg_rows_kernel<1, 0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+        } else {
+            if (ad) avg_rows_kernel<0, 1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+            else avg_rows_kernel<0, 0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+        }
+    } else {
+        const int64_t n = R * D;
+        const int64_t blocks64 = (n + 255) / 256;
+        const unsigned blocks = (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
+        if (gdtype == SDP_BF16) {
+            if (ad) avg_elems_kernel<1, 1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+            else avg_elems_kernel<1, 0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+        } else {
+            if (ad) avg_elems_kernel<0, 1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+            else avg_elems_kernel<0, 0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+        }
+    }
+    return sdp::launch_status();
 }
 
 } // namespace
@@ -131,32 +249,30 @@ extern "C" int sdp_coverage_grad_avg(int K, int64_t R, int D, int gdtype, const 
     if (R == 0) return SDP_OK; // nothing to average: empty buffers may legitimately be null
     if (!mask || !out) return SDP_ERR_INVALID_ARG;
     if (R > ((int64_t)1 << 40) / D) return SDP_ERR_SHAPE;
-    GradPtrs ptrs;
-    for (int k = 0; k < K; ++k) {
-        if (!g[k] || !sdp::aligned16(g[k])) return SDP_ERR_INVALID_ARG;
-        ptrs.p[k] = g[k];
-    }
-    for (int k = K; k < SDP_MAX_WORKERS; ++k) ptrs.p[k] = nullptr;
     if (!sdp::aligned16(out)) return SDP_ERR_INVALID_ARG;
-    hipStream_t s = (hipStream_t)stream;
-    sdp::ProfileScope ps("coverage_grad_avg", s);
-    if (D % 8 == 0) {
-        const int segs = (D + 511) / 512;
-        const int64_t items = R * segs;
-        const int64_t blocks64 = (items + 3) / 4; // 4 waves per workgroup
-        const unsigned blocks = (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
-        if (gdtype == SDP_BF16)
-            avg_rows_kernel<1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov);
-        else
-            avg_rows_kernel<0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov);
-    } else {
-        const int64_t n = R * D;
-        const int64_t blocks64 = (n + 255) / 256;
-        const unsigned blocks = (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
-        if (gdtype == SDP_BF16)
-            avg_elems_kernel<1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov);
-        else
-            avg_elems_kernel<0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov);
-    }
-    return sdp::launch_status();
+    return launch_average(K, R, D, gdtype, g, mask, out, cov, nullptr, "coverage_grad_avg", (hipStream_t)stream);
+}
+
+extern "C" int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
+                                      float* theta, float* m, float* v, void* theta_bf16, uint8_t* cov,
+                                      const sdp_adamw_params* hp, void* stream) {
+    if (K < 1 || K > SDP_MAX_WORKERS || R < 0 || D < 1) return SDP_ERR_INVALID_ARG;
+    if (gdtype != SDP_F32 && gdtype != SDP_BF16) return SDP_ERR_INVALID_ARG;
+    if (!g || !hp) return SDP_ERR_INVALID_ARG;
+    if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) ||
+        !(hp->eps > 0.f) || !(hp->weight_decay >= 0.f) || hp->step < 1 || !std::isfinite(hp->grad_scale))
+        return SDP_ERR_INVALID_ARG;
+    if (R == 0) return SDP_OK;
+    if (!mask || !theta || !m || !v) return SDP_ERR_INVALID_ARG;
+    if (R > ((int64_t)1 << 40) / D) return SDP_ERR_SHAPE;
+    for (const void* q : {(const void*)theta, (const void*)m, (const void*)v, (const void*)theta_bf16})
+        if (q && !sdp::aligned16(q)) return SDP_ERR_INVALID_ARG;
+    AdamArgs a;
+    a.theta = theta, a.m = m, a.v = v, a.theta_bf16 = (uint16_t*)theta_bf16;
+    a.decay = 1.0f - hp->lr * hp->weight_decay;
+    a.beta1 = hp->beta1, a.beta2 = hp->beta2, a.eps = hp->eps, a.grad_scale = hp->grad_scale;
+    // bias corrections in double on the host (beta^t loses digits in fp32 for large t)
+    a.step_size = (float)((double)hp->lr / (1.0 - std::pow((double)hp->beta1, (double)hp->step)));
+    a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)hp->beta2, (double)hp->step)));
+    return launch_average(K, R, D, gdtype, g, mask, nullptr, cov, &a, "coverage_avg_adamw", (hipStream_t)stream);
 }

@@ -80,6 +80,14 @@ def test_argument_errors_are_caught_on_the_host():
     # average
     ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
     assert L.sdp_coverage_grad_avg(0, 4, 8, 1, ptrs, FAKE, FAKE, FAKE, None) == -1
+    hp = sdp.binding.AdamWParams(4e-3, 0.9, 0.95, 1e-8, 0.1, 1.0, 1)
+    adam = lambda *a: L.sdp_coverage_avg_adamw(*a)
+    assert adam(2, 4, 8, 1, ptrs, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None) == -1            # no hyper-parameters
+    assert adam(2, 4, 8, 1, ptrs, FAKE, None, FAKE, FAKE, None, FAKE, ctypes.byref(hp), None) == -1  # no theta
+    assert adam(0, 4, 8, 1, ptrs, FAKE, FAKE, FAKE, FAKE, None, FAKE, ctypes.byref(hp), None) == -1
+    bad_hp = sdp.binding.AdamWParams(4e-3, 1.0, 0.95, 1e-8, 0.1, 1.0, 1)
+    assert adam(2, 4, 8, 1, ptrs, FAKE, FAKE, FAKE, FAKE, None, FAKE, ctypes.byref(bad_hp), None) == -1
+    assert adam(2, 0, 8, 1, ptrs, FAKE, FAKE, FAKE, FAKE, None, FAKE, ctypes.byref(hp), None) == 0   # nothing to do
     out = ctypes.c_double(0.0)
     assert L.sdp_probe_mfma_tflops(None, 4, 4, FAKE, ctypes.byref(out), None) == -1
     assert L.sdp_probe_mfma_tflops(FAKE, 0, 4, FAKE, ctypes.byref(out), None) == -1

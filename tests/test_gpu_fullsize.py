@@ -113,3 +113,37 @@ def test_fullsize_config5_average_sampled(sdp, orc):
     want, wc = orc.gated_average(sub, want_mask[:, rows])
     assert (wc == wcov[rows]).all()
     assert_close(out[trows].cpu().numpy(), want, 1e-5, "config5 average (sampled rows)")
+
+
+def test_fullsize_config5_adamw_sampled(sdp, orc):
+    """The fused average + AdamW pass at the 1B-parameter size, sampled rows against the oracle."""
+    c = workloads.CONFIG5
+    hp = dict(lr=4e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    print(f"  {c.name} + AdamW: K={c.K} R={c.R} D={c.D} p={c.p}", flush=True)
+    want_mask = orc.make_masks(c.K, c.R, c.p, c.mask_seed, False)
+    dmask = torch.from_numpy(want_mask).cuda()
+    grads = workloads.grad_buffers(c.K, c.R, c.D, c.sigma, "bf16", device="cuda", poison_mask=dmask)
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    theta = torch.randn((c.R, c.D), generator=gen, device="cuda") * 0.02
+    m = torch.randn((c.R, c.D), generator=gen, device="cuda") * 1e-4
+    v = (torch.randn((c.R, c.D), generator=gen, device="cuda") * 1e-4) ** 2
+    _, _, _, wcov = orc.index_masks(want_mask, idx_ld=1)
+    uncovered = np.flatnonzero(wcov == 0)
+    rng = np.random.default_rng(6)
+    rows = _sample(c.R, 1200, rng, list(uncovered[:50]) + [0, 1, 2, 3, c.R - 3, c.R - 2, c.R - 1])
+    trows = torch.from_numpy(rows).cuda()
+    before = [t[trows].cpu().numpy() for t in (theta, m, v)]
+    cov = sdp.coverage_avg_adamw(grads, dmask, theta, m, v, step=12, **hp)
+    torch.cuda.synchronize()
+    assert (cov.cpu().numpy() == wcov).all()
+    assert bool(torch.isfinite(theta).all()) and bool(torch.isfinite(m).all()) and bool(torch.isfinite(v).all())
+    sub = [workloads.bf16_bits(g[trows]) for g in grads]
+    wth, wm, wv, wc = orc.avg_adamw(sub, want_mask[:, rows], *before, step=12, **hp)
+    got = [t[trows].cpu().numpy() for t in (theta, m, v)]
+    off = wc == 0
+    for b, g_ in zip(before, got):
+        assert (g_[off] == b[off]).all()                           # uncovered rows: state untouched, bit for bit
+    assert_close(got[1], wm, 1e-5, "config5 AdamW m (sampled rows)")
+    assert_close(got[2], wv, 1e-5, "config5 AdamW v (sampled rows)")
+    assert_close(got[0], wth, 1e-5, "config5 AdamW theta (sampled rows)")
+    assert_close(got[0].astype(np.float64) - before[0], wth - before[0], 1e-4, "config5 AdamW update (sampled rows)")
