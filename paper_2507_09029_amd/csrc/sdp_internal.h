@@ -104,4 +104,15 @@ bool gemm_mfma_supported(const GemmDesc& g);
 int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t* rows, int R, int C, void* out,
                    int64_t ld_out, const char* name, hipStream_t s);
 
+// Several such transposes as one launch (16-bit elements with 8-element aligned shapes; otherwise one launch each).
+constexpr int kMaxTransposeJobs = 4;
+struct TransposeJob {
+    const void* in;
+    void* out;
+    int64_t ld_in, ld_out;
+    const int32_t* rows; // optional gather of input rows
+    int R, C;
+};
+int transpose_batch(int elem_bytes, const TransposeJob* jobs, int n, const char* name, hipStream_t s);
+
 } // namespace sdp

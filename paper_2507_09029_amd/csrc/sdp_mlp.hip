@@ -146,13 +146,12 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     const size_t nm_b = round_up((size_t)p * ld_tokens(T) * e, 256);
     void *dGn = w, *dUn = w + nm_b, *Actn = w + 2 * nm_b; // [p][T(+pad)]: neuron-major
 
-    rc = transpose_rows((int)e, W1, d, gather, n, d, W1c, n, "mlp_wt_bwd", s);
-    if (rc != SDP_OK) return rc;
-    rc = transpose_rows((int)e, W3, d, gather, n, d, W3c, n, "mlp_wt_bwd", s);
-    if (rc != SDP_OK) return rc;
-    rc = transpose_rows((int)e, X, d, nullptr, T, d, XT, ld_tokens(T), "mlp_xt", s);
-    if (rc != SDP_OK) return rc;
-    rc = transpose_rows((int)e, dY, d, nullptr, T, d, dYT, ld_tokens(T), "mlp_xt", s);
+    // the four operand copies of the backward pass as one launch
+    const TransposeJob tj[4] = {{W1, W1c, d, n, gather, n, d},
+                                {W3, W3c, d, n, gather, n, d},
+                                {X, XT, d, ld_tokens(T), nullptr, T, d},
+                                {dY, dYT, d, ld_tokens(T), nullptr, T, d}};
+    rc = transpose_batch((int)e, tj, 4, "mlp_tr_bwd", s);
     if (rc != SDP_OK) return rc;
 
     // weight-gradient contraction (set up first: whether it can take the MFMA path decides what the
