@@ -304,6 +304,14 @@ def main():
                     "launches_timed": calls, "flop_per_launch": flops_per_launch(dominant, w),
                     "share_of_step": ms / a.steps / ms_per_step}
 
+    # forward and backward separately (sums of the survey's per-kernel means, per worker)
+    fwd_names = ("mlp_wt_fwd", "mlp_gate_up", "mlp_down")
+    fwd_bwd = None
+    if kernels:
+        f = sum(v["avg_ms"] * v["launches_per_step"] / w.K for k, v in kernels.items() if k in fwd_names)
+        b = sum(v["avg_ms"] * v["launches_per_step"] / w.K for k, v in kernels.items() if k.startswith("mlp_") and k not in fwd_names)
+        fwd_bwd = {"forward": f, "backward": b}
+
     rec = {
         "metric": "masked-MLP fwd+bwd active TFLOP/s (% bf16 MFMA peak) + grad-avg GB/s (% HBM)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -314,6 +322,7 @@ def main():
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS if w.dtype == "bf16" else None,
         "roofline": roofline,
         "kernels": kernels,
+        "fwd_bwd_ms_per_worker": fwd_bwd,
         "kernels_note": "per-kernel table from an untimed survey of up to 3 steps with HIP events around every kernel "
                         "(that instrumentation slows a step by about a tenth); roofline is timed live in the K timed steps",
     }

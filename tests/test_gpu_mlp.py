@@ -74,6 +74,9 @@ SMALL = [
     MlpWorkload("aligned_bf16_fm", "bf16", 512, 256, 1024, 512, 4, "fm", 15),
     MlpWorkload("aligned_bf16_bm", "bf16", 512, 256, 1024, 768, 4, "bm", 16),
     MlpWorkload("full_cover_bf16_bm", "bf16", 256, 128, 256, 256, 2, "bm", 17),
+    MlpWorkload("tiny_bf16_fm", "bf16", 8, 16, 32, 16, 2, "fm", 20),            # one MFMA tile, almost all of it out of range
+    MlpWorkload("tiny_bf16_bm", "bf16", 16, 16, 48, 16, 3, "bm", 21),
+    MlpWorkload("full_cover_bf16_fm", "bf16", 48, 64, 128, 128, 2, "fm", 22),   # C = 1 on the MFMA path
 ]
 
 
