@@ -65,6 +65,12 @@ def lib():
             ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
             ctypes.POINTER(ctypes.c_void_p), _u8p, _f64p, _u8p,
         ]
+        L.orc_attn_fwd.restype = None
+        L.orc_attn_fwd.argtypes = [ctypes.c_int64] * 5 + [_f64p] * 10
+        L.orc_attn_bwd.restype = None
+        L.orc_attn_bwd.argtypes = [ctypes.c_int64] * 5 + [_f64p] * 18
+        L.orc_attn_worker_step.restype = ctypes.c_int64
+        L.orc_attn_worker_step.argtypes = [ctypes.c_int64] * 5 + [_u8p] + [_f64p] * 19
         L.orc_rho2.restype = ctypes.c_double
         L.orc_rho2.argtypes = [ctypes.c_int, ctypes.c_int64, _u8p]
         _lib = L
@@ -219,3 +225,50 @@ def rho2(mask):
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     K, F = mask.shape
     return float(lib().orc_rho2(K, F, _p(mask, _u8p)))
+
+
+def attn_fwd(Bt, S, hd, X, Wq, Wk, Wv, WoT):
+    """Dense causal multi-head attention block forward -> dict(Q, K, V, O, Y), fp64; see orc_attn_fwd."""
+    X, Wq, Wk, Wv, WoT = map(_f64, (X, Wq, Wk, Wv, WoT))
+    T, d = X.shape
+    E = Wq.shape[0]
+    assert T == Bt * S and E % hd == 0
+    for w in (Wq, Wk, Wv, WoT):
+        assert w.shape == (E, d)
+    Q = np.empty((T, E)); K = np.empty((T, E)); V = np.empty((T, E)); O = np.empty((T, E)); Y = np.empty((T, d))
+    lib().orc_attn_fwd(Bt, S, d, E // hd, hd, *[_p(a, _f64p) for a in (X, Wq, Wk, Wv, WoT, Q, K, V, O, Y)])
+    return dict(Q=Q, K=K, V=V, O=O, Y=Y)
+
+
+def attn_bwd(Bt, S, hd, X, dY, Wq, Wk, Wv, WoT, Q, K, V, O):
+    """Dense attention block backward -> dict(dQ, dK, dV, dX, dWq, dWk, dWv, dWoT), fp64; see orc_attn_bwd."""
+    X, dY, Wq, Wk, Wv, WoT, Q, K, V, O = map(_f64, (X, dY, Wq, Wk, Wv, WoT, Q, K, V, O))
+    T, d = X.shape
+    E = Wq.shape[0]
+    dQ = np.empty((T, E)); dK = np.empty((T, E)); dV = np.empty((T, E)); dX = np.empty((T, d))
+    dWq = np.empty((E, d)); dWk = np.empty((E, d)); dWv = np.empty((E, d)); dWoT = np.empty((E, d))
+    lib().orc_attn_bwd(Bt, S, d, E // hd, hd,
+                       *[_p(a, _f64p) for a in (X, dY, Wq, Wk, Wv, WoT, Q, K, V, O, dQ, dK, dV, dX, dWq, dWk, dWv, dWoT)])
+    return dict(dQ=dQ, dK=dK, dV=dV, dX=dX, dWq=dWq, dWk=dWk, dWv=dWv, dWoT=dWoT)
+
+
+def attn_worker_step(Bt, S, hd, head_mask, X, dY, Wq, Wk, Wv, WoT):
+    """One worker's attention forward + backward with heads masked forward (Sec. 3.1, Sec. 4.1).
+
+    Returns full-size fp64 arrays Q, K, V, O [T][H hd]; Y, dX [T][d]; dWq, dWk, dWv, dWoT [H hd][d] and
+    `nonzero_off_mask` (gradient entries of unheld heads that are not exactly zero; must be 0).
+    """
+    head_mask = np.ascontiguousarray(head_mask, dtype=np.uint8)
+    X, dY, Wq, Wk, Wv, WoT = map(_f64, (X, dY, Wq, Wk, Wv, WoT))
+    T, d = X.shape
+    E = Wq.shape[0]
+    H = E // hd
+    assert head_mask.shape == (H,) and T == Bt * S
+    names = ["Q", "K", "V", "O", "Y", "dQ", "dK", "dV", "dX", "dWq", "dWk", "dWv", "dWoT"]
+    shapes = [(T, E)] * 4 + [(T, d)] + [(T, E)] * 3 + [(T, d)] + [(E, d)] * 4
+    out = {n: np.empty(s) for n, s in zip(names, shapes)}
+    nz = lib().orc_attn_worker_step(Bt, S, d, H, hd, _p(head_mask, _u8p),
+                                    *[_p(a, _f64p) for a in (X, dY, Wq, Wk, Wv, WoT)],
+                                    *[_p(out[n], _f64p) for n in names])
+    out["nonzero_off_mask"] = int(nz)
+    return out

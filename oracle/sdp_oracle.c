@@ -21,7 +21,9 @@
  * index/coverage against brute force; the dense MLP forward against a library
  * einsum; its gradients against central finite differences; forward masking
  * against the compact-slice route and the zero-gradient property; backward
- * masking and the gated average against their C = 1 (DDP) reductions.
+ * masking and the gated average against their C = 1 (DDP) reductions; the
+ * attention block against a library attention routine with autograd, central
+ * finite differences, causality, and the block built from the held heads alone.
  */
 #include <math.h>
 #include <stdint.h>
@@ -434,4 +436,190 @@ double orc_rho2(int K, int64_t F, const uint8_t* mask) {
         }
     }
     return acc;
+}
+
+/* ========================================================================= */
+/* Head-level masking of the attention block (Sec. 4.1: the neuron-level      */
+/* variant masks attention heads on W_Q, W_K, W_V and W_O).                    */
+/*                                                                             */
+/* Bias-free causal multi-head self-attention over Bt sequences of S tokens    */
+/* (token t = b S + s), H heads of width hd, every weight neuron-major:        */
+/*   Wq, Wk, Wv [H hd][d]  (row h hd + r = feature r of head h),               */
+/*   WoT        [H hd][d]  (row j = column j of W_O),                          */
+/*   Q = X Wq^T, K = X Wk^T, V = X Wv^T                      [T][H hd]         */
+/*   P_h[s][s'] = softmax over s' <= s of Q_h[s].K_h[s'] / sqrt(hd)            */
+/*   O_h = P_h V_h,   Y = sum_h O_h WoT_h.                                     */
+/* Head h owns rows h hd .. h hd + hd - 1 of each of the four matrices; the    */
+/* gate of Sec. 3.1 zeroes them for a head the worker does not hold.           */
+/* ========================================================================= */
+
+/* Dense forward.  Q, K, V, O are [T][H hd] outputs, Y is [T][d].              */
+void orc_attn_fwd(int64_t Bt, int64_t S, int64_t d, int64_t H, int64_t hd, const double* X,
+                  const double* Wq, const double* Wk, const double* Wv, const double* WoT,
+                  double* Q, double* Kp, double* V, double* O, double* Y) {
+    const int64_t T = Bt * S, E = H * hd;
+    const double scale = 1.0 / sqrt((double)hd);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t j = 0; j < E; ++j) {
+            double q = 0.0, k = 0.0, v = 0.0;
+            for (int64_t e = 0; e < d; ++e) {
+                q += X[t * d + e] * Wq[j * d + e];
+                k += X[t * d + e] * Wk[j * d + e];
+                v += X[t * d + e] * Wv[j * d + e];
+            }
+            Q[t * E + j] = q, Kp[t * E + j] = k, V[t * E + j] = v;
+        }
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < Bt; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            double* P = (double*)malloc(sizeof(double) * (size_t)S);
+            for (int64_t s = 0; s < S; ++s) {
+                const int64_t t = b * S + s;
+                double mx = -INFINITY;
+                for (int64_t s2 = 0; s2 <= s; ++s2) {
+                    double z = 0.0;
+                    for (int64_t r = 0; r < hd; ++r) z += Q[t * E + h * hd + r] * Kp[(b * S + s2) * E + h * hd + r];
+                    P[s2] = z * scale;
+                    if (P[s2] > mx) mx = P[s2];
+                }
+                double den = 0.0;
+                for (int64_t s2 = 0; s2 <= s; ++s2) {
+                    P[s2] = exp(P[s2] - mx);
+                    den += P[s2];
+                }
+                for (int64_t r = 0; r < hd; ++r) {
+                    double o = 0.0;
+                    for (int64_t s2 = 0; s2 <= s; ++s2) o += (P[s2] / den) * V[(b * S + s2) * E + h * hd + r];
+                    O[t * E + h * hd + r] = o;
+                }
+            }
+            free(P);
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t e = 0; e < d; ++e) Y[t * d + e] = 0.0;
+        for (int64_t j = 0; j < E; ++j)
+            for (int64_t e = 0; e < d; ++e) Y[t * d + e] += O[t * E + j] * WoT[j * d + e];
+    }
+}
+
+/* Dense backward of L = <dY, Y>.  Q, K, V, O come from the forward.           */
+/*   dO = dY W_O^T-rows: dO[t][j] = dY[t].WoT[j];   dWoT[j] = sum_t O[t][j] dY[t] */
+/*   per (b, h), with P recomputed row by row:                                 */
+/*     dV[s'] += P[s][s'] dO[s];   dP[s][s'] = dO[s].V[s']                     */
+/*     dZ[s][s'] = P[s][s'] (dP[s][s'] - sum_u P[s][u] dP[s][u])               */
+/*     dQ[s] += dZ[s][s'] K[s'] / sqrt(hd);   dK[s'] += dZ[s][s'] Q[s] / sqrt(hd) */
+/*   dWq[j] = sum_t dQ[t][j] X[t] (same for k, v);  dX = dQ Wq + dK Wk + dV Wv. */
+/* dQ, dK, dV are [T][H hd] outputs (returned so that tests can look at them).  */
+void orc_attn_bwd(int64_t Bt, int64_t S, int64_t d, int64_t H, int64_t hd, const double* X,
+                  const double* dY, const double* Wq, const double* Wk, const double* Wv,
+                  const double* WoT, const double* Q, const double* Kp, const double* V,
+                  const double* O, double* dQ, double* dK, double* dV, double* dX, double* dWq,
+                  double* dWk, double* dWv, double* dWoT) {
+    const int64_t T = Bt * S, E = H * hd;
+    const double scale = 1.0 / sqrt((double)hd);
+    double* dO = (double*)malloc(sizeof(double) * (size_t)(T * E));
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t j = 0; j < E; ++j) {
+            double a = 0.0;
+            for (int64_t e = 0; e < d; ++e) a += dY[t * d + e] * WoT[j * d + e];
+            dO[t * E + j] = a;
+            dQ[t * E + j] = dK[t * E + j] = dV[t * E + j] = 0.0;
+        }
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < Bt; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            double* P = (double*)malloc(sizeof(double) * (size_t)S);
+            double* dP = (double*)malloc(sizeof(double) * (size_t)S);
+            for (int64_t s = 0; s < S; ++s) {
+                const int64_t t = b * S + s;
+                double mx = -INFINITY;
+                for (int64_t s2 = 0; s2 <= s; ++s2) {
+                    double z = 0.0;
+                    for (int64_t r = 0; r < hd; ++r) z += Q[t * E + h * hd + r] * Kp[(b * S + s2) * E + h * hd + r];
+                    P[s2] = z * scale;
+                    if (P[s2] > mx) mx = P[s2];
+                }
+                double den = 0.0;
+                for (int64_t s2 = 0; s2 <= s; ++s2) {
+                    P[s2] = exp(P[s2] - mx);
+                    den += P[s2];
+                }
+                double dot = 0.0;
+                for (int64_t s2 = 0; s2 <= s; ++s2) {
+                    P[s2] /= den;
+                    double a = 0.0;
+                    for (int64_t r = 0; r < hd; ++r) a += dO[t * E + h * hd + r] * V[(b * S + s2) * E + h * hd + r];
+                    dP[s2] = a;
+                    dot += P[s2] * a;
+                }
+                for (int64_t s2 = 0; s2 <= s; ++s2) {
+                    const int64_t t2 = b * S + s2;
+                    const double dz = P[s2] * (dP[s2] - dot);
+                    for (int64_t r = 0; r < hd; ++r) {
+                        dV[t2 * E + h * hd + r] += P[s2] * dO[t * E + h * hd + r];
+                        dQ[t * E + h * hd + r] += dz * Kp[t2 * E + h * hd + r] * scale;
+                        dK[t2 * E + h * hd + r] += dz * Q[t * E + h * hd + r] * scale;
+                    }
+                }
+            }
+            free(P);
+            free(dP);
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t e = 0; e < d; ++e) dX[t * d + e] = 0.0;
+        for (int64_t j = 0; j < E; ++j)
+            for (int64_t e = 0; e < d; ++e)
+                dX[t * d + e] += dQ[t * E + j] * Wq[j * d + e] + dK[t * E + j] * Wk[j * d + e] +
+                                 dV[t * E + j] * Wv[j * d + e];
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < E; ++j) {
+        for (int64_t e = 0; e < d; ++e) dWq[j * d + e] = dWk[j * d + e] = dWv[j * d + e] = dWoT[j * d + e] = 0.0;
+        for (int64_t t = 0; t < T; ++t)
+            for (int64_t e = 0; e < d; ++e) {
+                dWq[j * d + e] += dQ[t * E + j] * X[t * d + e];
+                dWk[j * d + e] += dK[t * E + j] * X[t * d + e];
+                dWv[j * d + e] += dV[t * E + j] * X[t * d + e];
+                dWoT[j * d + e] += O[t * E + j] * dY[t * d + e];
+            }
+    }
+    free(dO);
+}
+
+/* One worker's attention step under forward masking of heads (Sec. 3.1 with   */
+/* m_fwd = m_bwd = the head mask): loss and gradient are evaluated at the      */
+/* gated parameters.  head_mask[H]; outputs are full size.  Returns the number */
+/* of weight-gradient entries of unheld heads that are not exactly zero        */
+/* (the remark of Sec. 3.1 says there are none).                               */
+int64_t orc_attn_worker_step(int64_t Bt, int64_t S, int64_t d, int64_t H, int64_t hd,
+                             const uint8_t* head_mask, const double* X, const double* dY,
+                             const double* Wq, const double* Wk, const double* Wv, const double* WoT,
+                             double* Q, double* Kp, double* V, double* O, double* Y, double* dQ,
+                             double* dK, double* dV, double* dX, double* dWq, double* dWk,
+                             double* dWv, double* dWoT) {
+    const int64_t E = H * hd;
+    const size_t wn = (size_t)E * d;
+    uint8_t* row_mask = (uint8_t*)malloc((size_t)E);
+    for (int64_t j = 0; j < E; ++j) row_mask[j] = head_mask[j / hd];
+    double* g[4];
+    const double* w[4] = {Wq, Wk, Wv, WoT};
+    for (int i = 0; i < 4; ++i) {
+        g[i] = (double*)malloc(sizeof(double) * wn);
+        orc_gate_rows(E, d, row_mask, w[i], g[i]);
+    }
+    orc_attn_fwd(Bt, S, d, H, hd, X, g[0], g[1], g[2], g[3], Q, Kp, V, O, Y);
+    orc_attn_bwd(Bt, S, d, H, hd, X, dY, g[0], g[1], g[2], g[3], Q, Kp, V, O, dQ, dK, dV, dX, dWq, dWk, dWv, dWoT);
+    int64_t nz = 0;
+    for (int64_t j = 0; j < E; ++j)
+        if (!row_mask[j])
+            for (int64_t e = 0; e < d; ++e)
+                nz += (dWq[j * d + e] != 0.0) + (dWk[j * d + e] != 0.0) + (dWv[j * d + e] != 0.0) +
+                      (dWoT[j * d + e] != 0.0);
+    for (int i = 0; i < 4; ++i) free(g[i]);
+    free(row_mask);
+    return nz;
 }
