@@ -1,0 +1,658 @@
+// One worker's attention block under head-level masks (the paper's Sec. 4.1: the neuron-level variant of
+// Sec. 3.2 masks attention heads on W_Q, W_K, W_V and W_O), forward masking (Sec. 3.1): the block is
+// evaluated at the gated parameters, i.e. as the smaller dense block made of the worker's ph heads.
+//
+// With E = ph * hd, rows_qkv = the 3 E rows of [Wq; Wk; Wv] that belong to the held heads and rows_o the E
+// rows of WoT (columns of W_O):
+//   forward   qkv   : [Q | K | V] = X . Wqkv[rows_qkv]^T      (T x 3E, depth d; rows gathered in the load)
+//             core  : O_h = softmax_causal(Q_h K_h^T / sqrt(hd)) V_h, per sequence and held head
+//             out   : Y = O . WoT[rows_o]                     (T x d, depth E)
+//   backward  dO = dY . WoT[rows_o]^T (T x E);  core backward -> dQ, dK, dV (T x 3E);
+//             dWqkv[rows_qkv] = dQKV^T . X, dWoT[rows_o] = O^T . dY (depth T);  dX = dQKV . Wqkv[rows_qkv]
+// The contractions are the ones of the MLP path (same kernels, other shapes).  The core is written here:
+// causal attention on 32x32x16 bf16 MFMA tiles for hd = 64, with the running-maximum formulation of
+// the softmax (logits in base 2), so that no T x T matrix is stored.
+//
+// Accumulator convention.  v_mfma_f32_32x32x16 computes D[m][n] += sum_k A[m][k] B[k][n]; lane L supplies
+// A[L % 32][8 (L / 32) + e] and B[8 (L / 32) + e][L % 32], e = 0..7, and holds D[8 q + 4 (L / 32) + r][L % 32]
+// in element 4 q + r.  Every product below puts the index that owns per-row softmax statistics on n, so that
+// a lane keeps one query (or one key) and its statistics are plain per-lane scalars.  The probabilities then
+// feed the next product straight from the accumulator registers: elements 8 s .. 8 s + 7 of a 32-wide tile
+// are, for this lane, the depth indices {16 s + 4 (L / 32) + r} and {16 s + 8 + 4 (L / 32) + r}, and the other
+// operand is read from LDS in that same order with two transposing reads (ds_read_tr16_b64), which turn a
+// row-major [depth][column] tile into the per-lane layout of an A operand.
+#include "sdp_internal.h"
+
+#include <cmath>
+
+namespace sdp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+constexpr int HD = 64;              // head width of the MFMA core
+constexpr int RSB = 144;            // bytes per LDS tile row: 64 bf16 + 16 bytes (bank spread), 16-byte aligned
+constexpr int TILE_BYTES = 64 * RSB; // one 64 x 64 tile
+constexpr int BQ = 128;             // rows (queries, or keys in the dK/dV kernel) per workgroup: 4 waves x 32
+
+struct CoreArgs {
+    const uint16_t* qkv; // [T][ldq]: Q | K | V of the held heads, head i at columns i * 64 of each part
+    int64_t ldq;
+    const uint16_t* o;   // [T][ldo] attention output (forward: written; backward: read)
+    uint16_t* o_out;
+    const uint16_t* dO;  // [T][ldo]
+    int64_t ldo;
+    float* lse;          // [Bt][ph][S]: base-2 log-sum-exp of the scaled logits
+    float* delta;        // [Bt][ph][S]: sum_h dO[t][h] O[t][h]
+    uint16_t* dqkv;      // [T][ldq]
+    int S, ph;
+    float scale, scale2; // 1 / sqrt(hd), and that times log2(e)
+};
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ inline float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// elements 8 s .. 8 s + 7 of an accumulator tile as a bf16 operand
+__device__ inline bf16x8 pack_operand(const f32x16& a, int s) {
+    const u32x4 v = {pack_bf16(a[8 * s], a[8 * s + 1]), pack_bf16(a[8 * s + 2], a[8 * s + 3]),
+                     pack_bf16(a[8 * s + 4], a[8 * s + 5]), pack_bf16(a[8 * s + 6], a[8 * s + 7])};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// operand whose depth runs along a tile row: row `row` of the tile, depth 16 s + 8 lhi .. + 7
+__device__ inline bf16x8 frag_rows(const unsigned char* tile, int row, int s, int lhi) {
+    return __builtin_bit_cast(bf16x8, *(const u32x4*)(tile + row * RSB + 32 * s + 16 * lhi));
+}
+
+// A operand whose depth runs down the tile rows: for lane L, column col0 + L % 32 and the rows
+// krow + 4 (L / 32) + e (e = 0..3), then krow + 8 + 4 (L / 32) + e.  Within each block of 16 lanes a
+// transposing read hands lane n the e-th 16-bit element (e = 0..3) of what lane 4 e + n / 4 addressed,
+// at position n % 4 of its 8 bytes: the 16 lanes address 4 rows x 4 groups of 4 columns.
+__device__ inline bf16x8 frag_cols(const unsigned char* tile, int krow, int col0, int lane) {
+    const int gi = lane >> 4, li = lane & 15;
+    const unsigned char* p = tile + (krow + 4 * (gi >> 1) + (li >> 2)) * RSB + (col0 + 16 * (gi & 1) + 4 * (li & 3)) * 2;
+    const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+    const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * RSB));
+    const u32x2 a = __builtin_bit_cast(u32x2, h0), b = __builtin_bit_cast(u32x2, h1);
+    return __builtin_bit_cast(bf16x8, u32x4{a[0], a[1], b[0], b[1]});
+}
+
+// the 16-byte pieces of a 64-row x 64-column tile that thread `tid` of 256 moves: rows clamped to the
+// last valid one (such rows only meet masked logits)
+struct TilePieces {
+    u32x4 v[2];
+    __device__ void fetch(const uint16_t* g, int64_t ld, int row0, int last_row, int tid) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = tid + 256 * i;
+            int row = row0 + (c >> 3);
+            row = row < last_row ? row : last_row;
+            v[i] = *(const u32x4*)(g + (int64_t)row * ld + (c & 7) * 8);
+        }
+    }
+    __device__ void stash(unsigned char* tile, int tid) const {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = tid + 256 * i;
+            *(u32x4*)(tile + (c >> 3) * RSB + (c & 7) * 16) = v[i];
+        }
+    }
+};
+
+// a row of 64 bf16 as the depth-along-row operand of lane (row, lhi): sub-step s holds depth 16 s + 8 lhi .. + 7
+__device__ inline void load_row_operand(const uint16_t* g, int64_t ld, int row, int lhi, bf16x8 (&f)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) f[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(g + (int64_t)row * ld + 16 * s + 8 * lhi));
+}
+
+// accumulator tiles D[h][row] (two 32-row blocks of h) -> out[row][32 j + 8 q + 4 lhi + r], scaled, 8-byte stores
+__device__ inline void store_rows(uint16_t* out_row, const f32x16 (&acc)[2], float f, int lhi) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *(u32x2*)(out_row + 32 * j + 8 * q + 4 * lhi) =
+                u32x2{pack_bf16(acc[j][4 * q] * f, acc[j][4 * q + 1] * f), pack_bf16(acc[j][4 * q + 2] * f, acc[j][4 * q + 3] * f)};
+}
+
+__device__ inline float other_half(float x) { return __shfl_xor(x, 32, 64); }
+
+// ---------------------------------------------------------------------------------------------------
+// Forward.  Workgroup = 128 queries of one (sequence, head); wave w keeps queries q0 + 32 w .. + 31 as a
+// register operand and walks the key/value tiles of 64 keys up to the diagonal.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_fwd_kernel(CoreArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q0 = (gridDim.x - 1 - blockIdx.x) * BQ; // long rows first
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int S = a.S;
+    const uint16_t* gQ = a.qkv + (int64_t)b * S * a.ldq + head * HD;
+    const uint16_t* gK = gQ + a.ph * HD;
+    const uint16_t* gV = gK + a.ph * HD;
+    const int qrow0 = q0 + 32 * wave, qrow = qrow0 + l32;
+    bf16x8 qf[4];
+    load_row_operand(gQ, a.ldq, qrow < S ? qrow : S - 1, lhi, qf);
+
+    const int kv_end = q0 + BQ < S ? q0 + BQ : S;
+    const int ntiles = (kv_end + 63) / 64;
+    f32x16 acc_o[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[j][e] = 0.f;
+    float m = -INFINITY, lsum = 0.f;
+
+    TilePieces pk, pv;
+    pk.fetch(gK, a.ldq, 0, S - 1, tid);
+    pv.fetch(gV, a.ldq, 0, S - 1, tid);
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads(); // every wave is done with the previous tile
+        pk.stash(sK, tid);
+        pv.stash(sV, tid);
+        __syncthreads();
+        if (t + 1 < ntiles) {
+            pk.fetch(gK, a.ldq, 64 * (t + 1), S - 1, tid);
+            pv.fetch(gV, a.ldq, 64 * (t + 1), S - 1, tid);
+        }
+        const int kv0 = 64 * t;
+        if (kv0 > qrow0 + 31) continue; // wave-uniform: every key of the tile lies after the wave's queries
+
+        // logits, transposed: sc[tb] = D[key 32 tb + ..][query]
+        f32x16 sc[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[tb][e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                sc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sK, 32 * tb + l32, s, lhi), qf[s], sc[tb], 0, 0, 0);
+        }
+        const bool edge = kv0 + 63 > qrow0 || kv0 + 64 > S; // wave-uniform: some logits are masked
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                float z = sc[tb][e] * a.scale2;
+                if (edge && (key > qrow || key >= S)) z = -INFINITY;
+                sc[tb][e] = z;
+                mx = fmaxf(mx, z);
+            }
+        mx = fmaxf(mx, other_half(mx));
+        // the first tile holds key 0, which no query masks: the running maximum is finite from then on
+        const float m_new = fmaxf(m, mx);
+        const float alpha = exp2f(m - m_new);
+        m = m_new;
+        float ps = 0.f;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = exp2f(sc[tb][e] - m_new);
+                sc[tb][e] = p;
+                ps += p;
+            }
+        lsum = lsum * alpha + ps;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_o[j][e] *= alpha;
+        // O^T[h][query] += sum_key V[key][h] P[query][key]
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bf16x8 pf = pack_operand(sc[tb], s);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc_o[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(sV, 32 * tb + 16 * s, 32 * j, lane), pf, acc_o[j], 0, 0, 0);
+            }
+    }
+    lsum += other_half(lsum);
+    if (qrow < S) {
+        store_rows(a.o_out + ((int64_t)b * S + qrow) * a.ldo + head * HD, acc_o, 1.f / lsum, lhi);
+        if (lhi == 0) a.lse[((int64_t)b * a.ph + head) * S + qrow] = m + log2f(lsum);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Backward, dQ (and delta).  Same walk as the forward: wave w keeps its 32 queries' Q and dO rows as
+// register operands; P is recomputed from the stored log-sum-exp.
+//   dP[q][k] = dO[q] . V[k];  dZ = P (dP - delta[q]);  dQ[q] = scale sum_k dZ[q][k] K[k]
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(CoreArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q0 = (gridDim.x - 1 - blockIdx.x) * BQ;
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int S = a.S;
+    const uint16_t* gQ = a.qkv + (int64_t)b * S * a.ldq + head * HD;
+    const uint16_t* gK = gQ + a.ph * HD;
+    const uint16_t* gV = gK + a.ph * HD;
+    const int qrow0 = q0 + 32 * wave, qrow = qrow0 + l32;
+    const int qc = qrow < S ? qrow : S - 1;
+    bf16x8 qf[4], dof[4];
+    load_row_operand(gQ, a.ldq, qc, lhi, qf);
+    const int64_t orow = ((int64_t)b * S + qc) * a.ldo + head * HD;
+    load_row_operand(a.dO + orow, 0, 0, lhi, dof);
+    float delta = 0.f;
+    {
+        bf16x8 of[4];
+        load_row_operand(a.o + orow, 0, 0, lhi, of);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) delta += (float)dof[s][e] * (float)of[s][e];
+        delta += other_half(delta);
+    }
+    const int64_t stat = ((int64_t)b * a.ph + head) * S;
+    if (qrow < S && lhi == 0) a.delta[stat + qrow] = delta;
+    const float L2 = a.lse[stat + qc];
+
+    const int kv_end = q0 + BQ < S ? q0 + BQ : S;
+    const int ntiles = (kv_end + 63) / 64;
+    f32x16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+    TilePieces pk, pv;
+    pk.fetch(gK, a.ldq, 0, S - 1, tid);
+    pv.fetch(gV, a.ldq, 0, S - 1, tid);
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+        pk.stash(sK, tid);
+        pv.stash(sV, tid);
+        __syncthreads();
+        if (t + 1 < ntiles) {
+            pk.fetch(gK, a.ldq, 64 * (t + 1), S - 1, tid);
+            pv.fetch(gV, a.ldq, 64 * (t + 1), S - 1, tid);
+        }
+        const int kv0 = 64 * t;
+        if (kv0 > qrow0 + 31) continue;
+        const bool edge = kv0 + 63 > qrow0 || kv0 + 64 > S;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            f32x16 sc, dp;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[e] = 0.f, dp[e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sK, 32 * tb + l32, s, lhi), qf[s], sc, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sV, 32 * tb + l32, s, lhi), dof[s], dp, 0, 0, 0);
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                float p = exp2f(sc[e] * a.scale2 - L2);
+                if (edge && (key > qrow || key >= S)) p = 0.f;
+                sc[e] = p * (dp[e] - delta);
+            }
+            // dQ^T[h][query] += sum_key K[key][h] dZ[query][key]
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bf16x8 zf = pack_operand(sc, s);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(sK, 32 * tb + 16 * s, 32 * j, lane), zf, acc[j], 0, 0, 0);
+            }
+        }
+    }
+    if (qrow < S) store_rows(a.dqkv + ((int64_t)b * S + qrow) * a.ldq + head * HD, acc, a.scale, lhi);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Backward, dK and dV.  Workgroup = 128 keys of one (sequence, head); wave w keeps keys k0 + 32 w .. + 31
+// (K and V rows) as register operands and walks the query tiles from the diagonal to the end of the
+// sequence; Q, dO and the per-query statistics of a tile of 64 queries are staged in LDS.
+//   dV[k] = sum_q P[q][k] dO[q];   dK[k] = scale sum_q dZ[q][k] Q[q]
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(CoreArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char sQ[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sO[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) float sL[64];
+    __shared__ __attribute__((aligned(16))) float sD[64];
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int k0 = blockIdx.x * BQ; // the first key blocks meet the most queries
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int S = a.S;
+    const uint16_t* gQ = a.qkv + (int64_t)b * S * a.ldq + head * HD;
+    const uint16_t* gK = gQ + a.ph * HD;
+    const uint16_t* gV = gK + a.ph * HD;
+    const uint16_t* gO = a.dO + (int64_t)b * S * a.ldo + head * HD;
+    const int64_t stat = ((int64_t)b * a.ph + head) * S;
+    const int krow0 = k0 + 32 * wave, krow = krow0 + l32;
+    const int kc = krow < S ? krow : S - 1;
+    bf16x8 kf[4], vf[4];
+    load_row_operand(gK, a.ldq, kc, lhi, kf);
+    load_row_operand(gV, a.ldq, kc, lhi, vf);
+
+    f32x16 acc_k[2], acc_v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_k[j][e] = 0.f, acc_v[j][e] = 0.f;
+
+    const int t0 = k0 / 64, t1 = (S + 63) / 64; // query tiles [t0, t1); t0 < t1 because k0 < S
+    TilePieces pq, po;
+    float pstat = 0.f;
+    auto fetch = [&](int t) {
+        pq.fetch(gQ, a.ldq, 64 * t, S - 1, tid);
+        po.fetch(gO, a.ldo, 64 * t, S - 1, tid);
+        if (tid < 128) {
+            int q = 64 * t + (tid & 63);
+            q = q < S ? q : S - 1;
+            pstat = tid < 64 ? a.lse[stat + q] : a.delta[stat + q];
+        }
+    };
+    fetch(t0);
+    for (int t = t0; t < t1; ++t) {
+        __syncthreads();
+        pq.stash(sQ, tid);
+        po.stash(sO, tid);
+        if (tid < 64) sL[tid] = pstat;
+        else if (tid < 128) sD[tid - 64] = pstat;
+        __syncthreads();
+        if (t + 1 < t1) fetch(t + 1);
+        const int qt0 = 64 * t;
+        if (qt0 + 63 < krow0) continue; // wave-uniform: every query of the tile lies before the wave's keys
+        const bool edge = qt0 < krow0 + 31 || qt0 + 64 > S;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            // sc = D[query 32 tb + ..][key], dp likewise
+            f32x16 sc, dp;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[e] = 0.f, dp[e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sQ, 32 * tb + l32, s, lhi), kf[s], sc, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sO, 32 * tb + l32, s, lhi), vf[s], dp, 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 l4 = *(const f32x4*)(sL + 32 * tb + 8 * q + 4 * lhi);
+                const f32x4 d4 = *(const f32x4*)(sD + 32 * tb + 8 * q + 4 * lhi);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int query = qt0 + 32 * tb + 8 * q + 4 * lhi + r;
+                    float p = exp2f(sc[4 * q + r] * a.scale2 - l4[r]);
+                    if (edge && (krow > query || query >= S)) p = 0.f;
+                    sc[4 * q + r] = p;
+                    dp[4 * q + r] = p * (dp[4 * q + r] - d4[r]);
+                }
+            }
+            // dV^T[h][key] += sum_query dO[query][h] P[query][key];  dK^T[h][key] += sum_query Q[query][h] dZ[query][key]
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bf16x8 pf = pack_operand(sc, s), zf = pack_operand(dp, s);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    acc_v[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(sO, 32 * tb + 16 * s, 32 * j, lane), pf, acc_v[j], 0, 0, 0);
+                    acc_k[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(sQ, 32 * tb + 16 * s, 32 * j, lane), zf, acc_k[j], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (krow < S) {
+        uint16_t* row = a.dqkv + ((int64_t)b * S + krow) * a.ldq + head * HD;
+        store_rows(row + a.ph * HD, acc_k, a.scale, lhi);
+        store_rows(row + 2 * a.ph * HD, acc_v, 1.f, lhi);
+    }
+}
+
+// rows of [Wq; Wk; Wv] ([3 H hd][d]) and of WoT ([H hd][d]) that belong to the held heads
+__global__ void head_rows_kernel(const int32_t* __restrict__ head_idx, int ph, int H, int hd, int32_t* __restrict__ rows_qkv,
+                                 int32_t* __restrict__ rows_o) {
+    const int E = ph * hd;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 3 * E) return;
+    const int part = i / E, rem = i - part * E;
+    const int row = head_idx[rem / hd] * hd + rem % hd;
+    rows_qkv[i] = part * H * hd + row;
+    if (part == 0) rows_o[rem] = row;
+}
+
+int64_t ld_tokens(int64_t T) { return T + 64; } // see the MLP path: rows must not sit a power of two apart
+
+int check(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+    if (dtype != SDP_BF16) return SDP_ERR_UNSUPPORTED;
+    if (Bt < 1 || S < 1 || d < 1 || H < 1) return SDP_ERR_INVALID_ARG;
+    if (hd != HD) return SDP_ERR_UNSUPPORTED;
+    if (ph < 1 || ph > H) return SDP_ERR_SHAPE;
+    if (d % 8) return SDP_ERR_SHAPE;
+    if (Bt > 65535 || ph > 65535) return SDP_ERR_SHAPE;
+    if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)Bt * S * 3 * H * hd >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
+    return SDP_OK;
+}
+
+struct FwdWs {
+    int32_t *rows_qkv, *rows_o;
+    void* WoC;
+    size_t bytes;
+};
+FwdWs fwd_ws(char* w, int d, int E) {
+    FwdWs r;
+    size_t off = 0;
+    auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
+    r.rows_qkv = (int32_t*)take((size_t)3 * E * 4);
+    r.rows_o = (int32_t*)take((size_t)E * 4);
+    r.WoC = take((size_t)d * E * 2);
+    r.bytes = off;
+    return r;
+}
+
+struct BwdWs {
+    int32_t *rows_qkv, *rows_o;
+    void *dO, *dQKV, *dQKVt, *Ot, *Xt, *dYt, *Wc;
+    float* delta;
+    size_t bytes;
+};
+BwdWs bwd_ws(char* w, int64_t T, int d, int E, int64_t stats) {
+    BwdWs r;
+    size_t off = 0;
+    auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
+    r.rows_qkv = (int32_t*)take((size_t)3 * E * 4);
+    r.rows_o = (int32_t*)take((size_t)E * 4);
+    r.dO = take((size_t)T * E * 2);
+    r.dQKV = take((size_t)T * 3 * E * 2);
+    r.delta = (float*)take((size_t)stats * 4);
+    r.dQKVt = take((size_t)3 * E * ld_tokens(T) * 2);
+    r.Ot = take((size_t)E * ld_tokens(T) * 2);
+    r.Xt = take((size_t)d * ld_tokens(T) * 2);
+    r.dYt = take((size_t)d * ld_tokens(T) * 2);
+    r.Wc = take((size_t)d * 3 * E * 2);
+    r.bytes = off;
+    return r;
+}
+
+int run(const GemmDesc& g, hipStream_t s) {
+    if (gemm_mfma_supported(g)) return gemm_mfma_bf16(g, s);
+    return gemm_simple(SDP_BF16, g, s);
+}
+
+int head_rows(const int32_t* head_idx, int ph, int H, int hd, int32_t* rows_qkv, int32_t* rows_o, hipStream_t s) {
+    ProfileScope ps("attn_rows", s);
+    const int n = 3 * ph * hd;
+    head_rows_kernel<<<(n + 255) / 256, 256, 0, s>>>(head_idx, ph, H, hd, rows_qkv, rows_o);
+    return launch_status();
+}
+
+} // namespace
+} // namespace sdp
+
+using namespace sdp;
+
+extern "C" size_t sdp_masked_attn_fwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+    if (check(dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
+    return fwd_ws(nullptr, d, ph * hd).bytes;
+}
+
+extern "C" size_t sdp_masked_attn_bwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+    if (check(dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
+    return bwd_ws(nullptr, (int64_t)Bt * S, d, ph * hd, (int64_t)Bt * ph * S).bytes;
+}
+
+extern "C" int sdp_masked_attn_fwd(int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* Wqkv,
+                                   const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save, void* O_save,
+                                   float* LSE_save, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check(dtype, Bt, S, d, H, hd, ph);
+    if (rc != SDP_OK) return rc;
+    if (!X || !Wqkv || !WoT || !head_idx_k || !Y || !QKV_save || !O_save || !LSE_save) return SDP_ERR_INVALID_ARG;
+    for (const void* q : {X, Wqkv, WoT, (const void*)Y, (const void*)QKV_save, (const void*)O_save, (const void*)LSE_save})
+        if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_fwd_workspace_bytes(dtype, Bt, S, d, H, hd, ph))
+        return SDP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int T = Bt * S, E = ph * hd;
+    const FwdWs w = fwd_ws((char*)ws, d, E);
+
+    rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc pj;
+    pj.name = "attn_qkv";
+    pj.M = T, pj.N = 3 * E, pj.K = d;
+    pj.A = X, pj.lda = d;
+    pj.B = Wqkv, pj.ldb = d, pj.b_gather = w.rows_qkv, pj.b_rows = (int64_t)3 * H * hd;
+    pj.epilogue = EPI_STORE;
+    pj.C = QKV_save, pj.ldc = 3 * E;
+    rc = run(pj, s);
+    if (rc != SDP_OK) return rc;
+
+    CoreArgs a{};
+    a.qkv = (const uint16_t*)QKV_save, a.ldq = 3 * E;
+    a.o_out = (uint16_t*)O_save, a.ldo = E;
+    a.lse = LSE_save;
+    a.S = S, a.ph = ph;
+    a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
+    {
+        ProfileScope ps("attn_core_fwd", s);
+        attn_fwd_kernel<<<dim3((S + BQ - 1) / BQ, ph, Bt), 256, 0, s>>>(a);
+        rc = launch_status();
+        if (rc != SDP_OK) return rc;
+    }
+
+    rc = transpose_rows(2, WoT, d, w.rows_o, E, d, w.WoC, E, "attn_wt_fwd", s);
+    if (rc != SDP_OK) return rc;
+    GemmDesc op;
+    op.name = "attn_out";
+    op.M = T, op.N = d, op.K = E;
+    op.A = O_save, op.lda = E;
+    op.B = w.WoC, op.ldb = E;
+    op.epilogue = EPI_STORE;
+    op.C = Y, op.ldc = d;
+    return run(op, s);
+}
+
+extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* dY,
+                                   const void* Wqkv, const void* WoT, const int32_t* head_idx_k, const void* QKV_save,
+                                   const void* O_save, const float* LSE_save, void* dX, void* dWqkv, void* dWoT,
+                                   int dw_layout, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check(dtype, Bt, S, d, H, hd, ph);
+    if (rc != SDP_OK) return rc;
+    if (dw_layout != SDP_DW_COMPACT && dw_layout != SDP_DW_SCATTER) return SDP_ERR_INVALID_ARG;
+    if (!X || !dY || !Wqkv || !WoT || !head_idx_k || !QKV_save || !O_save || !LSE_save || !dX || !dWqkv || !dWoT)
+        return SDP_ERR_INVALID_ARG;
+    for (const void* q : {X, dY, Wqkv, WoT, QKV_save, O_save, (const void*)LSE_save, (const void*)dX, (const void*)dWqkv,
+                          (const void*)dWoT})
+        if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
+    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_bwd_workspace_bytes(dtype, Bt, S, d, H, hd, ph))
+        return SDP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int T = Bt * S, E = ph * hd;
+    const BwdWs w = bwd_ws((char*)ws, T, d, E, (int64_t)Bt * ph * S);
+
+    rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc go;
+    go.name = "attn_dout";
+    go.M = T, go.N = E, go.K = d;
+    go.A = dY, go.lda = d;
+    go.B = WoT, go.ldb = d, go.b_gather = w.rows_o, go.b_rows = (int64_t)H * hd;
+    go.epilogue = EPI_STORE;
+    go.C = w.dO, go.ldc = E;
+    rc = run(go, s);
+    if (rc != SDP_OK) return rc;
+
+    CoreArgs a{};
+    a.qkv = (const uint16_t*)QKV_save, a.ldq = 3 * E;
+    a.o = (const uint16_t*)O_save, a.dO = (const uint16_t*)w.dO, a.ldo = E;
+    a.lse = const_cast<float*>(LSE_save), a.delta = w.delta;
+    a.dqkv = (uint16_t*)w.dQKV;
+    a.S = S, a.ph = ph;
+    a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
+    const dim3 grid((S + BQ - 1) / BQ, ph, Bt);
+    {
+        ProfileScope ps("attn_core_bwd_dq", s);
+        attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a);
+        rc = launch_status();
+        if (rc != SDP_OK) return rc;
+    }
+    {
+        ProfileScope ps("attn_core_bwd_dkv", s); // reads the delta written by the dQ kernel
+        attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a);
+        rc = launch_status();
+        if (rc != SDP_OK) return rc;
+    }
+
+    const int64_t ldt = ld_tokens(T);
+    const TransposeJob tj[4] = {{w.dQKV, w.dQKVt, 3 * E, ldt, nullptr, T, 3 * E},
+                                {O_save, w.Ot, E, ldt, nullptr, T, E},
+                                {X, w.Xt, d, ldt, nullptr, T, d},
+                                {dY, w.dYt, d, ldt, nullptr, T, d}};
+    rc = transpose_batch(2, tj, 4, "attn_tr_bwd", s);
+    if (rc != SDP_OK) return rc;
+    rc = transpose_rows(2, Wqkv, d, w.rows_qkv, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc dw;
+    dw.name = "attn_dwqkv";
+    dw.M = 3 * E, dw.N = d, dw.K = T;
+    dw.A = w.dQKVt, dw.lda = ldt;
+    dw.B = w.Xt, dw.ldb = ldt;
+    dw.epilogue = EPI_STORE;
+    dw.C = dWqkv, dw.ldc = d;
+    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_qkv : nullptr;
+    rc = run(dw, s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc dwo;
+    dwo.name = "attn_dwo";
+    dwo.M = E, dwo.N = d, dwo.K = T;
+    dwo.A = w.Ot, dwo.lda = ldt;
+    dwo.B = w.dYt, dwo.ldb = ldt;
+    dwo.epilogue = EPI_STORE;
+    dwo.C = dWoT, dwo.ldc = d;
+    dwo.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_o : nullptr;
+    rc = run(dwo, s);
+    if (rc != SDP_OK) return rc;
+
+    GemmDesc dx;
+    dx.name = "attn_dx";
+    dx.M = T, dx.N = d, dx.K = 3 * E;
+    dx.A = w.dQKV, dx.lda = 3 * E;
+    dx.B = w.Wc, dx.ldb = 3 * E;
+    dx.epilogue = EPI_STORE;
+    dx.C = dX, dx.ldc = d;
+    return run(dx, s);
+}

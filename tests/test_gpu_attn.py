@@ -1,0 +1,128 @@
+"""GPU parity of the head-masked attention block (forward and backward) against the fp64 oracle.
+
+Every output element is compared; tolerance 2e-2 for bf16 inputs with fp32 accumulation (metric in
+helpers.err_report).  Head masks come from the library's sampler at head granularity and are checked bit for
+bit against the oracle's.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import assert_close, assert_close_rows
+from workloads import AttnWorkload
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+# Weight gradients behind the attention core pass through two more bf16 roundings than the MLP's (the
+# probabilities and the logit gradients are MFMA operands) on top of those of dO, dQ/dK/dV and the result; the
+# relative error per element then has a standard deviation near 0.4 % of the tensor's rms (the normwise
+# figure), and the largest of 10^5 - 10^6 elements lies 4.5 - 5.5 deviations out.  The benchmark spec's bound of
+# 2e-2 is kept for the normwise error; the elementwise maximum gets 3e-2.
+TOL_ELEM_DW = 3e-2
+
+
+@pytest.fixture(scope="module")
+def sdp():
+    import paper_2507_09029_amd as m
+
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def held_rows(heads, hd):
+    return np.concatenate([np.arange(h * hd, (h + 1) * hd) for h in heads])
+
+
+def run_case(sdp, orc, w, workers, dw_layout="compact"):
+    Wqkv, WoT = workloads.attn_weights(w)
+    dWqkv, dWoT = Wqkv.cuda(), WoT.cuda()
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    want_mask = orc.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    assert (mask.cpu().numpy() == want_mask).all()
+    W64 = [workloads.to_f64(Wqkv[i]) for i in range(3)] + [workloads.to_f64(WoT)]
+    E_all = w.H * w.hd
+    for k in workers:
+        print(f"  {w.name} worker {k} Bt={w.Bt} S={w.S} d={w.d} H={w.H} ph={w.ph} {dw_layout}", flush=True)
+        X, dY = workloads.attn_batch(w, k)
+        heads = np.flatnonzero(want_mask[k])
+        assert (idx[k].cpu().numpy() == heads).all()
+        Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), dWqkv, dWoT, idx[k])
+        out = None
+        if dw_layout == "scatter":
+            out = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"),
+                   torch.full((3, E_all, w.d), float("nan"), dtype=X.dtype, device="cuda"),
+                   torch.full((E_all, w.d), float("nan"), dtype=X.dtype, device="cuda"))
+        dX, gWqkv, gWoT = sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), dWqkv, dWoT, idx[k], QKV, O, LSE,
+                                              dw_layout=dw_layout, out=out)
+        torch.cuda.synchronize()
+        ref = orc.attn_worker_step(w.Bt, w.S, w.hd, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64)
+        assert ref["nonzero_off_mask"] == 0
+        rows = held_rows(heads, w.hd)
+        E = rows.size
+        # per-token tensors: one scale per row (a token's output averages over all earlier tokens, so the row
+        # norms fall with the position); weight gradients: one scale per tensor
+        assert_close_rows(workloads.to_f64(Y), ref["Y"], TOL, "Y")
+        got_qkv = workloads.to_f64(QKV)
+        for i, name in enumerate("QKV"):
+            assert_close_rows(got_qkv[:, i * E:(i + 1) * E], ref[name][:, rows], TOL, name)
+        assert_close_rows(workloads.to_f64(O), ref["O"][:, rows], TOL, "O")
+        # base-2 log-sum-exp of the scaled logits, from the oracle's Q and K
+        q = ref["Q"][:, rows].reshape(w.Bt, w.S, -1, w.hd)
+        kk = ref["K"][:, rows].reshape(w.Bt, w.S, -1, w.hd)
+        z = np.einsum("bshr,buhr->bhsu", q, kk) / np.sqrt(w.hd)
+        z = np.where(np.tril(np.ones((w.S, w.S), bool)), z, -np.inf)
+        zmax = z.max(axis=-1, keepdims=True)
+        lse2 = (zmax[..., 0] + np.log(np.exp(z - zmax).sum(axis=-1))) / np.log(2.0)
+        assert np.abs(LSE.cpu().numpy() - lse2).max() <= TOL * max(1.0, np.abs(lse2).max())
+        assert_close_rows(workloads.to_f64(dX), ref["dX"], TOL, "dX")
+        g = workloads.to_f64(gWqkv)
+        go = workloads.to_f64(gWoT)
+        if dw_layout == "scatter":
+            off = np.setdiff1d(np.arange(E_all), rows)
+            assert np.isnan(g[:, off]).all() and np.isnan(go[off]).all(), "rows of heads not held must stay untouched"
+            g, go = g[:, rows], go[rows]
+        for i, name in enumerate(("dWq", "dWk", "dWv")):
+            if w.S == 1 and i < 2:
+                # a softmax over one key is constant: the exact gradient is zero, and what is left of the
+                # cancellation dP - delta in fp32 must be negligible next to the other gradients
+                assert not ref[name].any()
+                assert np.abs(g[i]).max() <= 1e-5 * np.sqrt(np.mean(ref["dWv"][rows] ** 2))
+                continue
+            assert_close(g[i], ref[name][rows], TOL, name, elem_tol=TOL_ELEM_DW)
+        assert_close(go, ref["dWoT"][rows], TOL, "dWoT", elem_tol=TOL_ELEM_DW)
+
+
+CASES = [
+    AttnWorkload("one_tile", 1, 64, 64, 2, 64, 1, 2, 31),
+    AttnWorkload("one_token", 3, 1, 64, 2, 64, 2, 2, 32),
+    AttnWorkload("two_heads_of_four", 2, 128, 128, 4, 64, 2, 4, 33),
+    AttnWorkload("ragged_seq_all_heads", 2, 200, 136, 3, 64, 3, 2, 34),     # C = 1: the dense block; S % 64 = 8
+    AttnWorkload("ragged_depth", 1, 300, 72, 4, 64, 1, 4, 35),             # d % 16 != 0: plain contraction kernels
+    AttnWorkload("several_blocks", 2, 520, 256, 8, 64, 4, 4, 36),          # 5 query blocks, tail of 8
+    AttnWorkload("odd_tokens", 1, 77, 64, 2, 64, 1, 2, 37),                # T % 8 != 0
+]
+
+
+@pytest.mark.parametrize("w", CASES, ids=[w.name for w in CASES])
+def test_attention_all_outputs(sdp, orc, w):
+    run_case(sdp, orc, w, range(min(w.K, 2)))
+
+
+def test_scatter_layout_leaves_other_heads_alone(sdp, orc):
+    run_case(sdp, orc, CASES[2], [1], dw_layout="scatter")
+
+
+def test_argument_errors(sdp):
+    w = CASES[2]
+    Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(w))
+    X, _ = workloads.attn_batch(w, 0)
+    idx = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
+    with pytest.raises(sdp.SdpError):  # fp32 is not built for the attention block
+        sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.float().cuda(), Wqkv.float(), WoT.float(), idx)
+    with pytest.raises(sdp.SdpError):  # head width other than 64
+        sdp.masked_attn_fwd(w.Bt, w.S, 32, X.cuda(), Wqkv, WoT, idx)
+    with pytest.raises(sdp.SdpError):  # more held heads than heads
+        sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), Wqkv, WoT, torch.arange(5, dtype=torch.int32, device="cuda"))

@@ -52,6 +52,36 @@ class AvgWorkload:
         return self.K * self.p * self.D * 2 + self.R * self.D * 4 + self.K * self.R + self.R
 
 
+@dataclass(frozen=True)
+class AttnWorkload:
+    """Head-masked causal self-attention block: Bt sequences of S tokens, H heads of width hd, ph held per worker."""
+    name: str
+    Bt: int
+    S: int
+    d: int
+    H: int
+    hd: int
+    ph: int
+    K: int
+    mask_seed: int = BASE_SEED + 7
+    dtype: str = "bf16"
+
+    @property
+    def T(self):
+        return self.Bt * self.S
+
+    @property
+    def active_flop_per_worker(self):
+        # projections (forward 2, backward 4 flop per multiply-add pair): Q, K, V, O on the held heads;
+        # core: causal half of 2 S^2 hd products, 2 forward (Q K^T, P V) and 5 backward
+        E = self.ph * self.hd
+        proj = 6 * self.T * self.d * 4 * E
+        core = 7 * self.Bt * self.ph * self.S * self.S * self.hd
+        return proj + core
+
+
+ATTN_500M = AttnWorkload("attn_bf16_fm_500M", 4, 2048, 1536, 24, 64, 12, 4)
+
 CONFIG1 = MlpWorkload("config1_f32_fm", "f32", 256, 256, 1024, 512, 4, "fm")
 CONFIG2 = MlpWorkload("config2_bf16_fm_500M", "bf16", 8192, 1536, 4096, 2048, 4, "fm")
 CONFIG3 = MlpWorkload("config3_bf16_fm_1B", "bf16", 16384, 2048, 5504, 4128, 8, "fm")
@@ -84,6 +114,19 @@ def mlp_batch(w, k, stream_base=0, rows=None):
     T = w.T if rows is None else rows
     X = _draw((T, w.d), 1.0, stream_base + 100 + 2 * k, w.dtype)
     dY = _draw((T, w.d), 1.0, stream_base + 101 + 2 * k, w.dtype)
+    return X, dY
+
+
+def attn_weights(w, stream_base=0):
+    """Wqkv [3][H hd][d] (W_Q, W_K, W_V stacked, neuron-major) and WoT [H hd][d], N(0, 0.02^2)."""
+    E = w.H * w.hd
+    return _draw((3, E, w.d), 0.02, stream_base + 11, w.dtype), _draw((E, w.d), 0.02, stream_base + 12, w.dtype)
+
+
+def attn_batch(w, k, stream_base=0):
+    """Worker k's block input X_k and upstream gradient dY_k, [Bt S][d], N(0, 1)."""
+    X = _draw((w.T, w.d), 1.0, stream_base + 300 + 2 * k, w.dtype)
+    dY = _draw((w.T, w.d), 1.0, stream_base + 301 + 2 * k, w.dtype)
     return X, dY
 
 
