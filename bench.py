@@ -9,6 +9,7 @@ full-size bf16 gradient buffer, then the coverage-normalised average of the K bu
 Prints ONE JSON line.  `value` is active TFLOP/s (18 T d p per worker and step under forward
 masking; the dense work the method avoids is not counted).  `roofline` is for the kernel that takes
 most of the step; `grad_avg` reports the HBM-bound average alone at 1B-parameter scale;
+`attention` reports one worker's head-masked attention block (not part of `value`);
 `cpu_baseline` is the fp64 oracle timed on this host on a bounded sample.
 """
 import argparse
@@ -48,6 +49,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-grad-avg-1b", action="store_true", help="skip the 1B-parameter average measurement")
     ap.add_argument("--avg-steps", type=int, default=20)
+    ap.add_argument("--no-attention", action="store_true", help="skip the head-masked attention block measurement")
     ap.add_argument("--events", type=int, default=1, help="1: per-kernel HIP events recorded during the timed steps")
     ap.add_argument("--graph", type=int, default=0, help="1: capture one step into a HIP graph and replay it (no per-kernel events)")
     ap.add_argument("--streams", type=int, default=1,
@@ -147,6 +149,59 @@ def bench_grad_avg_1b(sdp, torch, steps):
         "note": "covered gradient rows (bf16) + masks read; theta, m, v (fp32) of covered rows read and written",
     }
     return res
+
+
+def bench_attention(sdp, torch, steps):
+    """One worker's head-masked attention block (forward + backward) at the 500M-like width: not part of `value`."""
+    import workloads
+
+    w = workloads.ATTN_500M
+    Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(w))
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    X, dY = (t.cuda() for t in workloads.attn_batch(w, 0))
+    wsf = torch.empty(sdp.masked_attn_fwd_workspace_bytes(X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(sdp.masked_attn_bwd_workspace_bytes(X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
+    E = w.ph * w.hd
+    fo = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), torch.empty((w.T, 3 * E), dtype=X.dtype, device="cuda"),
+          torch.empty((w.T, E), dtype=X.dtype, device="cuda"), torch.empty((w.Bt, w.ph, w.S), dtype=torch.float32, device="cuda"))
+    bo = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), torch.empty((3, E, w.d), dtype=X.dtype, device="cuda"),
+          torch.empty((E, w.d), dtype=X.dtype, device="cuda"))
+
+    def one_pass():
+        for k in range(w.K):
+            Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X, Wqkv, WoT, idx[k], out=fo, ws=wsf)
+            sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X, dY, Wqkv, WoT, idx[k], QKV, O, LSE, out=bo, ws=wsb)
+
+    for _ in range(2):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_pass()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    sdp.profile_reset()
+    sdp.profile_enable(True)
+    one_pass()
+    torch.cuda.synchronize()
+    prof = sdp.profile_read()
+    sdp.profile_enable(False)
+    kern = {name: tot / calls for name, (calls, tot) in prof.items() if name.startswith("attn_")}
+    core_fwd = 2 * w.Bt * w.ph * w.S * w.S * w.hd
+    core_bwd = 5 * w.Bt * w.ph * w.S * w.S * w.hd
+    core_ms = kern["attn_core_fwd"] + kern["attn_core_bwd_dq"] + kern["attn_core_bwd_dkv"]
+    return {
+        "workload": w.name, "sequences": w.Bt, "seq_len": w.S, "d_model": w.d, "heads": w.H, "head_dim": w.hd,
+        "held_heads": w.ph, "workers_simulated": w.K, "active_flop_per_worker": w.active_flop_per_worker,
+        "ms_per_worker": ms / w.K, "value": w.active_flop_per_worker * w.K / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "kernels_avg_ms": kern,
+        "core": {"forward_tflops": core_fwd / (kern["attn_core_fwd"] * 1e-3) / 1e12,
+                 "backward_tflops": core_bwd / ((core_ms - kern["attn_core_fwd"]) * 1e-3) / 1e12,
+                 "roofline": {"bound": "mfma", "achieved": (core_fwd + core_bwd) / (core_ms * 1e-3) / 1e12,
+                              "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                              "frac": (core_fwd + core_bwd) / (core_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "traffic": None},
+                 "note": "causal: the half of the S x S products that is computed is counted (2 S^2 hd per head forward, 5 S^2 hd backward)"},
+    }
 
 
 def main():
@@ -342,6 +397,8 @@ def main():
         del Xs, dYs, bufs, avg, per
         torch.cuda.empty_cache()
         rec["grad_avg"] = bench_grad_avg_1b(sdp, torch, a.avg_steps)
+    if not a.no_attention:
+        rec["attention"] = bench_attention(sdp, torch, max(2, a.steps // 4))
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(rec))

@@ -147,3 +147,46 @@ def test_fullsize_config5_adamw_sampled(sdp, orc):
     assert_close(got[2], wv, 1e-5, "config5 AdamW v (sampled rows)")
     assert_close(got[0], wth, 1e-5, "config5 AdamW theta (sampled rows)")
     assert_close(got[0].astype(np.float64) - before[0], wth - before[0], 1e-4, "config5 AdamW update (sampled rows)")
+
+
+def test_attention_500M_one_sequence_and_sampled_gradient_rows(sdp, orc):
+    """Head-masked attention block at the size bench.py times (4 sequences of 2048 tokens, 12 of 24 heads).
+
+    Sequences do not interact: the oracle runs the dense block made of the worker's held heads on the last
+    sequence alone (all of Y, O and dX of that sequence are compared).  A weight-gradient row sums over all
+    tokens: the oracle's per-sequence gradients are summed over the four sequences for the held heads' rows of
+    one head (first and last row blocks included).
+    """
+    from helpers import assert_close_rows
+
+    w = workloads.ATTN_500M
+    Wqkv, WoT = workloads.attn_weights(w)
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    want_mask = orc.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    assert (mask.cpu().numpy() == want_mask).all()
+    k = w.K - 1
+    heads = np.flatnonzero(want_mask[k])
+    rows = np.concatenate([np.arange(h * w.hd, (h + 1) * w.hd) for h in heads])
+    E = rows.size
+    X, dY = workloads.attn_batch(w, k)
+    print(f"  {w.name} worker {k}: GPU forward + backward", flush=True)
+    Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), Wqkv.cuda(), WoT.cuda(), idx[k])
+    dX, gWqkv, gWoT = sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), Wqkv.cuda(), WoT.cuda(), idx[k], QKV, O, LSE)
+    torch.cuda.synchronize()
+    Wc = [workloads.to_f64(Wqkv[i])[rows] for i in range(3)] + [workloads.to_f64(WoT)[rows]]
+    X64, dY64 = workloads.to_f64(X), workloads.to_f64(dY)
+    gq = np.zeros((E, w.d)); gk = np.zeros((E, w.d)); gv = np.zeros((E, w.d)); go = np.zeros((E, w.d))
+    for b in range(w.Bt):
+        print(f"  oracle: sequence {b}", flush=True)
+        sl = slice(b * w.S, (b + 1) * w.S)
+        f = orc.attn_fwd(1, w.S, w.hd, X64[sl], *Wc)
+        r = orc.attn_bwd(1, w.S, w.hd, X64[sl], dY64[sl], *Wc, f["Q"], f["K"], f["V"], f["O"])
+        gq += r["dWq"]; gk += r["dWk"]; gv += r["dWv"]; go += r["dWoT"]
+        if b == w.Bt - 1:
+            assert_close_rows(workloads.to_f64(Y[sl]), f["Y"], TOL_BF16, "Y")
+            assert_close_rows(workloads.to_f64(O[sl]), f["O"], TOL_BF16, "O")
+            assert_close_rows(workloads.to_f64(dX[sl]), r["dX"], TOL_BF16, "dX")
+    g = workloads.to_f64(gWqkv)
+    for i, (name, want) in enumerate((("dWq", gq), ("dWk", gk), ("dWv", gv))):
+        assert_close(g[i], want, TOL_BF16, name, elem_tol=3e-2)
+    assert_close(workloads.to_f64(gWoT), go, TOL_BF16, "dWoT", elem_tol=3e-2)
