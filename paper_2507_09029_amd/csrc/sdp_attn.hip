@@ -128,11 +128,14 @@ __device__ inline void store_rows(uint16_t* out_row, const f32x16 (&acc)[2], flo
 
 __device__ inline float other_half(float x) { return __shfl_xor(x, 32, 64); }
 
+// 2^x for x <= 0 (or -inf): the hardware instruction alone; results below the normal range may flush to zero
+__device__ inline float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ---------------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 128 queries of one (sequence, head); wave w keeps queries q0 + 32 w .. + 31 as a
 // register operand and walks the key/value tiles of 64 keys up to the diagonal.
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_fwd_kernel(CoreArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(CoreArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
@@ -181,37 +184,43 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(CoreArgs a) {
             for (int s = 0; s < 4; ++s)
                 sc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sK, 32 * tb + l32, s, lhi), qf[s], sc[tb], 0, 0, 0);
         }
-        const bool edge = kv0 + 63 > qrow0 || kv0 + 64 > S; // wave-uniform: some logits are masked
+        if (kv0 + 63 > qrow0 || kv0 + 64 > S) { // wave-uniform: some logits of this tile are masked
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                    if (key > qrow || key >= S) sc[tb][e] = -INFINITY;
+                }
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
-                float z = sc[tb][e] * a.scale2;
-                if (edge && (key > qrow || key >= S)) z = -INFINITY;
-                sc[tb][e] = z;
-                mx = fmaxf(mx, z);
-            }
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[tb][e]);
         mx = fmaxf(mx, other_half(mx));
-        // the first tile holds key 0, which no query masks: the running maximum is finite from then on
-        const float m_new = fmaxf(m, mx);
-        const float alpha = exp2f(m - m_new);
+        // the first tile holds key 0, which no query masks: the running maximum is finite from then on.
+        // m is kept in units of the scaled base-2 logits; the scale rides in the exponent's multiply-add.
+        const float m_new = fmaxf(m, mx * a.scale2);
+        const float alpha = exp2_neg(m - m_new);
+        const bool grew = m_new != m;
         m = m_new;
         float ps = 0.f;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(sc[tb][e] - m_new);
+                const float p = exp2_neg(__builtin_fmaf(sc[tb][e], a.scale2, -m_new));
                 sc[tb][e] = p;
                 ps += p;
             }
         lsum = lsum * alpha + ps;
+        if (__any(grew)) { // wave-uniform; alpha = 1 in every lane otherwise
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc_o[j][e] *= alpha;
+                for (int e = 0; e < 16; ++e) acc_o[j][e] *= alpha;
+        }
         // O^T[h][query] += sum_key V[key][h] P[query][key]
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
@@ -235,7 +244,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(CoreArgs a) {
 // register operands; P is recomputed from the stored log-sum-exp.
 //   dP[q][k] = dO[q] . V[k];  dZ = P (dP - delta[q]);  dQ[q] = scale sum_k dZ[q][k] K[k]
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(CoreArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(CoreArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
@@ -299,13 +308,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(CoreArgs a) {
                 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sK, 32 * tb + l32, s, lhi), qf[s], sc, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sV, 32 * tb + l32, s, lhi), dof[s], dp, 0, 0, 0);
             }
+            if (edge) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
-                float p = exp2f(sc[e] * a.scale2 - L2);
-                if (edge && (key > qrow || key >= S)) p = 0.f;
-                sc[e] = p * (dp[e] - delta);
+                for (int e = 0; e < 16; ++e) {
+                    const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                    if (key > qrow || key >= S) sc[e] = -INFINITY;
+                }
             }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[e] = exp2_neg(__builtin_fmaf(sc[e], a.scale2, -L2)) * (dp[e] - delta);
             // dQ^T[h][query] += sum_key K[key][h] dZ[query][key]
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
@@ -325,7 +336,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(CoreArgs a) {
 // sequence; Q, dO and the per-query statistics of a tile of 64 queries are staged in LDS.
 //   dV[k] = sum_q P[q][k] dO[q];   dK[k] = scale sum_q dZ[q][k] Q[q]
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(CoreArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_kernel(CoreArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char sQ[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sO[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) float sL[64];
@@ -393,9 +404,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(CoreArgs a) {
                 const f32x4 d4 = *(const f32x4*)(sD + 32 * tb + 8 * q + 4 * lhi);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int query = qt0 + 32 * tb + 8 * q + 4 * lhi + r;
-                    float p = exp2f(sc[4 * q + r] * a.scale2 - l4[r]);
-                    if (edge && (krow > query || query >= S)) p = 0.f;
+                    float z = sc[4 * q + r];
+                    if (edge) {
+                        const int query = qt0 + 32 * tb + 8 * q + 4 * lhi + r;
+                        if (krow > query || query >= S) z = -INFINITY;
+                    }
+                    const float p = exp2_neg(__builtin_fmaf(z, a.scale2, -l4[r]));
                     sc[4 * q + r] = p;
                     dp[4 * q + r] = p * (dp[4 * q + r] - d4[r]);
                 }
