@@ -639,27 +639,35 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
     rc = transpose_rows(2, Wqkv, d, w.rows_qkv, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
     if (rc != SDP_OK) return rc;
 
+    // the four weight gradients share one shape (E x d, depth T): dWq, dWk, dWv from the three row blocks of
+    // dQKV^T against X^T, dWoT from O^T against dY^T; one batched launch fills the CUs four times better than
+    // the four launches would
     GemmDesc dw;
-    dw.name = "attn_dwqkv";
-    dw.M = 3 * E, dw.N = d, dw.K = T;
-    dw.A = w.dQKVt, dw.lda = ldt;
-    dw.B = w.Xt, dw.ldb = ldt;
+    dw.name = "attn_dw";
+    dw.M = E, dw.N = d, dw.K = T;
+    dw.lda = ldt, dw.ldb = ldt;
     dw.epilogue = EPI_STORE;
-    dw.C = dWqkv, dw.ldc = d;
-    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_qkv : nullptr;
-    rc = run(dw, s);
-    if (rc != SDP_OK) return rc;
-
-    GemmDesc dwo;
-    dwo.name = "attn_dwo";
-    dwo.M = E, dwo.N = d, dwo.K = T;
-    dwo.A = w.Ot, dwo.lda = ldt;
-    dwo.B = w.dYt, dwo.ldb = ldt;
-    dwo.epilogue = EPI_STORE;
-    dwo.C = dWoT, dwo.ldc = d;
-    dwo.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_o : nullptr;
-    rc = run(dwo, s);
-    if (rc != SDP_OK) return rc;
+    dw.ldc = d;
+    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_o : nullptr; // rows of the held heads inside each matrix
+    const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : E) * d;
+    dw.nbatch = 4;
+    for (int i = 0; i < 3; ++i) {
+        dw.Ab[i] = (const uint16_t*)w.dQKVt + (int64_t)i * E * ldt;
+        dw.Bb[i] = w.Xt;
+        dw.Cb[i] = (uint16_t*)dWqkv + i * part;
+    }
+    dw.Ab[3] = w.Ot, dw.Bb[3] = w.dYt, dw.Cb[3] = dWoT;
+    if (gemm_mfma_supported(dw)) {
+        rc = gemm_mfma_bf16(dw, s);
+        if (rc != SDP_OK) return rc;
+    } else {
+        dw.nbatch = 0;
+        for (int i = 0; i < 4; ++i) {
+            dw.A = dw.Ab[i], dw.B = dw.Bb[i], dw.C = dw.Cb[i];
+            rc = gemm_simple(SDP_BF16, dw, s);
+            if (rc != SDP_OK) return rc;
+        }
+    }
 
     GemmDesc dx;
     dx.name = "attn_dx";

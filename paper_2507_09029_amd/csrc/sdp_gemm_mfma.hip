@@ -73,8 +73,8 @@ struct Dev {
     int tiles_m, tiles_n, ntot; // ntot = tiles of all problems of the launch
     int group_m, nbatch;
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
-    const uint16_t *Ab[3], *Bb[3];
-    uint16_t* Cb[3];
+    const uint16_t *Ab[kMaxBatch], *Bb[kMaxBatch];
+    uint16_t* Cb[kMaxBatch];
 };
 
 // two fp32 -> packed bf16, round to nearest even (the hardware's v_cvt_pk_bf16_f32)
@@ -158,9 +158,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     const uint16_t* gB = g.B;
     uint16_t* gC = g.C;
     if (OP == OP_DW) {
-        gA = batch == 0 ? g.Ab[0] : (batch == 1 ? g.Ab[1] : g.Ab[2]);
-        gB = batch == 0 ? g.Bb[0] : (batch == 1 ? g.Bb[1] : g.Bb[2]);
-        gC = batch == 0 ? g.Cb[0] : (batch == 1 ? g.Cb[1] : g.Cb[2]);
+        // selected by comparisons: a runtime index into a by-value kernel argument would go through scratch
+        static_assert(kMaxBatch == 4, "one comparison per problem");
+        gA = batch == 0 ? g.Ab[0] : (batch == 1 ? g.Ab[1] : (batch == 2 ? g.Ab[2] : g.Ab[3]));
+        gB = batch == 0 ? g.Bb[0] : (batch == 1 ? g.Bb[1] : (batch == 2 ? g.Bb[2] : g.Bb[3]));
+        gC = batch == 0 ? g.Cb[0] : (batch == 1 ? g.Cb[1] : (batch == 2 ? g.Cb[2] : g.Cb[3]));
     }
     const int m0 = tile_m * BM;
     const int n0 = kFwd ? tile_n * (BN / 2) : tile_n * BN; // SWIGLU_FWD: BN columns = BN/2 neurons x {gate, up}
@@ -576,7 +578,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     g.ntot = (int)(ntiles * nbatch);
     g.nbatch = nbatch;
     int na = 1, nbo = 1; // distinct A / B operands among the problems of a batch
-    for (int z = 0; z < 3; ++z) {
+    for (int z = 0; z < kMaxBatch; ++z) {
         g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
     }
     if (OP == OP_DW) {
@@ -640,7 +642,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     if ((d.b_rows > 0 ? d.b_rows : (int64_t)d.N) * d.ldb * 2 >= ((int64_t)1 << 32)) return false;
     if (d.b_gather && d.b_rows <= 0) return false;
     if (d.nbatch > 0) {
-        if (d.nbatch > 3 || d.epilogue != EPI_STORE) return false;
+        if (d.nbatch > kMaxBatch || d.epilogue != EPI_STORE) return false;
         for (int z = 0; z < d.nbatch; ++z)
             if (!d.Ab[z] || !d.Bb[z] || !d.Cb[z] || !aligned16(d.Ab[z]) || !aligned16(d.Bb[z]) || !aligned16(d.Cb[z]))
                 return false;

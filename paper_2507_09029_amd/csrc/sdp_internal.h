@@ -46,6 +46,8 @@ enum Epilogue {
                          //   (ld = ldcc): column c of Cc / Cc2 / Cc3 is column cidx[c] of dG / dU / act
 };
 
+constexpr int kMaxBatch = 4;
+
 struct GemmDesc {
     int M = 0, N = 0, K = 0;
     const void* A = nullptr;
@@ -82,12 +84,12 @@ struct GemmDesc {
     void* Ct3 = nullptr;
     int64_t ldct = 0;
     const char* name = "gemm";
-    // batched launch of up to three problems with the same shape, strides and scatter (the
+    // batched launch of up to kMaxBatch problems with the same shape, strides and scatter (the
     // weight-gradient contractions): nbatch > 0 selects Ab/Bb/Cb instead of A/B/C
     int nbatch = 0;
-    const void* Ab[3] = {nullptr, nullptr, nullptr};
-    const void* Bb[3] = {nullptr, nullptr, nullptr};
-    void* Cb[3] = {nullptr, nullptr, nullptr};
+    const void* Ab[4] = {nullptr, nullptr, nullptr, nullptr};
+    const void* Bb[4] = {nullptr, nullptr, nullptr, nullptr};
+    void* Cb[4] = {nullptr, nullptr, nullptr, nullptr};
     int force_tile = 0; // 0 = choose; 256 / 192 / 128 force a tile shape (tuning and tests)
 };
 
