@@ -36,6 +36,16 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
+#ifndef SDP_ATTN_WPE_FWD
+#define SDP_ATTN_WPE_FWD 3
+#endif
+#ifndef SDP_ATTN_FWD_QF
+#define SDP_ATTN_FWD_QF 1
+#endif
+#ifndef SDP_ATTN_FWD_NW
+#define SDP_ATTN_FWD_NW 4
+#endif
+
 constexpr int HD = 64;              // head width of the MFMA core
 constexpr int RSB = 144;            // bytes per LDS tile row: 64 bf16 + 16 bytes (bank spread), 16-byte aligned
 constexpr int TILE_BYTES = 64 * RSB; // one 64 x 64 tile
@@ -132,111 +142,195 @@ __device__ inline float other_half(float x) { return __shfl_xor(x, 32, 64); }
 __device__ inline float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---------------------------------------------------------------------------------------------------
-// Forward.  Workgroup = 128 queries of one (sequence, head); wave w keeps queries q0 + 32 w .. + 31 as a
-// register operand and walks the key/value tiles of 64 keys up to the diagonal.
+// Forward.  Workgroup = NW waves; wave w keeps QF blocks of 32 queries (q0 + 32 QF w ..) as register
+// operands and walks the key/value tiles of 64 keys up to the diagonal.  K and V tiles are double-buffered
+// in LDS (one barrier per tile): while tile t is used, tile t + 1 moves from registers into the other
+// buffer and tile t + 2 is fetched from memory.  Every K and V fragment read from LDS serves all QF query
+// blocks of the wave.
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(CoreArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
+template <int NW>
+struct TileMover {
+    static constexpr int PER = 512 / (64 * NW); // 16-byte pieces per thread and tile
+    u32x4 v[PER];
+    __device__ void fetch(const uint16_t* g, int64_t ld, int row0, int last_row, int tid) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + 64 * NW * i;
+            int row = row0 + (c >> 3);
+            row = row < last_row ? row : last_row;
+            v[i] = *(const u32x4*)(g + (int64_t)row * ld + (c & 7) * 8);
+        }
+    }
+    __device__ void stash(unsigned char* tile, int tid) const {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + 64 * NW * i;
+            *(u32x4*)(tile + (c >> 3) * RSB + (c & 7) * 16) = v[i];
+        }
+    }
+};
+
+template <int QF, int NW>
+__device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int head, const int b,
+                                      unsigned char (&sK)[2][TILE_BYTES], unsigned char (&sV)[2][TILE_BYTES]) {
+    constexpr int ROWS = 32 * QF * NW; // queries per block
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int q0 = (gridDim.x - 1 - blockIdx.x) * BQ; // long rows first
-    const int head = blockIdx.y, b = blockIdx.z;
     const int S = a.S;
     const uint16_t* gQ = a.qkv + (int64_t)b * S * a.ldq + head * HD;
     const uint16_t* gK = gQ + a.ph * HD;
     const uint16_t* gV = gK + a.ph * HD;
-    const int qrow0 = q0 + 32 * wave, qrow = qrow0 + l32;
-    bf16x8 qf[4];
-    load_row_operand(gQ, a.ldq, qrow < S ? qrow : S - 1, lhi, qf);
+    const int qrow0 = q0 + 32 * QF * wave; // first query of the wave
+    bf16x8 qf[QF][4];
+#pragma unroll
+    for (int f = 0; f < QF; ++f) {
+        const int qrow = qrow0 + 32 * f + l32;
+        load_row_operand(gQ, a.ldq, qrow < S ? qrow : S - 1, lhi, qf[f]);
+    }
 
-    const int kv_end = q0 + BQ < S ? q0 + BQ : S;
+    const int kv_end = q0 + ROWS < S ? q0 + ROWS : S;
     const int ntiles = (kv_end + 63) / 64;
-    f32x16 acc_o[2];
+    f32x16 acc_o[QF][2];
+    float m[QF], lsum[QF];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int f = 0; f < QF; ++f) {
+        m[f] = -INFINITY, lsum[f] = 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc_o[j][e] = 0.f;
-    float m = -INFINITY, lsum = 0.f;
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_o[f][j][e] = 0.f;
+    }
 
-    TilePieces pk, pv;
+    TileMover<NW> pk, pv;
     pk.fetch(gK, a.ldq, 0, S - 1, tid);
     pv.fetch(gV, a.ldq, 0, S - 1, tid);
+    pk.stash(sK[0], tid);
+    pv.stash(sV[0], tid);
+    if (ntiles > 1) {
+        pk.fetch(gK, a.ldq, 64, S - 1, tid);
+        pv.fetch(gV, a.ldq, 64, S - 1, tid);
+    }
+    __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
-        __syncthreads(); // every wave is done with the previous tile
-        pk.stash(sK, tid);
-        pv.stash(sV, tid);
-        __syncthreads();
-        if (t + 1 < ntiles) {
-            pk.fetch(gK, a.ldq, 64 * (t + 1), S - 1, tid);
-            pv.fetch(gV, a.ldq, 64 * (t + 1), S - 1, tid);
+        const unsigned char* tK = sK[t & 1];
+        const unsigned char* tV = sV[t & 1];
+        if (t + 1 < ntiles) { // the other buffer was last read before the barrier that ended step t - 1
+            pk.stash(sK[(t + 1) & 1], tid);
+            pv.stash(sV[(t + 1) & 1], tid);
+        }
+        if (t + 2 < ntiles) {
+            pk.fetch(gK, a.ldq, 64 * (t + 2), S - 1, tid);
+            pv.fetch(gV, a.ldq, 64 * (t + 2), S - 1, tid);
         }
         const int kv0 = 64 * t;
-        if (kv0 > qrow0 + 31) continue; // wave-uniform: every key of the tile lies after the wave's queries
-
-        // logits, transposed: sc[tb] = D[key 32 tb + ..][query]
-        f32x16 sc[2];
+        if (kv0 <= qrow0 + 32 * QF - 1) { // wave-uniform: otherwise every key lies after the wave's queries
+            // logits, transposed: sc[f][tb] = D[key 32 tb + ..][query of block f]
+            f32x16 sc[QF][2];
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
+            for (int f = 0; f < QF; ++f)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sc[tb][e] = 0.f;
+                for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                sc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sK, 32 * tb + l32, s, lhi), qf[s], sc[tb], 0, 0, 0);
-        }
-        if (kv0 + 63 > qrow0 || kv0 + 64 > S) { // wave-uniform: some logits of this tile are masked
+                    for (int e = 0; e < 16; ++e) sc[f][tb][e] = 0.f;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
-                    if (key > qrow || key >= S) sc[tb][e] = -INFINITY;
+                for (int s = 0; s < 4; ++s) {
+                    const bf16x8 kfr = frag_rows(tK, 32 * tb + l32, s, lhi);
+#pragma unroll
+                    for (int f = 0; f < QF; ++f)
+                        sc[f][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, qf[f][s], sc[f][tb], 0, 0, 0);
+                }
+            if (kv0 + 63 > qrow0 || kv0 + 64 > S) { // wave-uniform: some logits of this tile are masked
+#pragma unroll
+                for (int f = 0; f < QF; ++f) {
+                    const int qrow = qrow0 + 32 * f + l32;
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int key = kv0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                            if (key > qrow || key >= S) sc[f][tb][e] = -INFINITY;
+                        }
+                }
+            }
+#pragma unroll
+            for (int f = 0; f < QF; ++f) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[f][tb][e]);
+                mx = fmaxf(mx, other_half(mx));
+                // the first tile holds key 0, which no query masks: the running maximum is finite from then
+                // on.  m is kept in units of the scaled base-2 logits; the scale rides in the multiply-add.
+                const float m_new = fmaxf(m[f], mx * a.scale2);
+                const float alpha = exp2_neg(m[f] - m_new);
+                const bool grew = m_new != m[f];
+                m[f] = m_new;
+                float ps = 0.f;
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float p = exp2_neg(__builtin_fmaf(sc[f][tb][e], a.scale2, -m_new));
+                        sc[f][tb][e] = p;
+                        ps += p;
+                    }
+                lsum[f] = lsum[f] * alpha + ps;
+                if (__any(grew)) { // wave-uniform; alpha = 1 in every lane otherwise
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc_o[f][j][e] *= alpha;
+                }
+            }
+            // O^T[h][query] += sum_key V[key][h] P[query][key]
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    bf16x8 pf[QF];
+#pragma unroll
+                    for (int f = 0; f < QF; ++f) pf[f] = pack_operand(sc[f][tb], s);
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const bf16x8 vfr = frag_cols(tV, 32 * tb + 16 * s, 32 * j, lane);
+#pragma unroll
+                        for (int f = 0; f < QF; ++f)
+                            acc_o[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, pf[f], acc_o[f][j], 0, 0, 0);
+                    }
                 }
         }
-        float mx = -INFINITY;
+        __syncthreads(); // tile t is released, tile t + 1 is in place
+    }
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[tb][e]);
-        mx = fmaxf(mx, other_half(mx));
-        // the first tile holds key 0, which no query masks: the running maximum is finite from then on.
-        // m is kept in units of the scaled base-2 logits; the scale rides in the exponent's multiply-add.
-        const float m_new = fmaxf(m, mx * a.scale2);
-        const float alpha = exp2_neg(m - m_new);
-        const bool grew = m_new != m;
-        m = m_new;
-        float ps = 0.f;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float p = exp2_neg(__builtin_fmaf(sc[tb][e], a.scale2, -m_new));
-                sc[tb][e] = p;
-                ps += p;
-            }
-        lsum = lsum * alpha + ps;
-        if (__any(grew)) { // wave-uniform; alpha = 1 in every lane otherwise
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc_o[j][e] *= alpha;
+    for (int f = 0; f < QF; ++f) {
+        const int qrow = qrow0 + 32 * f + l32;
+        const float l = lsum[f] + other_half(lsum[f]);
+        if (qrow < S) {
+            store_rows(a.o_out + ((int64_t)b * S + qrow) * a.ldo + head * HD, acc_o[f], 1.f / l, lhi);
+            if (lhi == 0) a.lse[((int64_t)b * a.ph + head) * S + qrow] = m[f] + log2f(l);
         }
-        // O^T[h][query] += sum_key V[key][h] P[query][key]
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const bf16x8 pf = pack_operand(sc[tb], s);
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc_o[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(sV, 32 * tb + 16 * s, 32 * j, lane), pf, acc_o[j], 0, 0, 0);
-            }
     }
-    lsum += other_half(lsum);
-    if (qrow < S) {
-        store_rows(a.o_out + ((int64_t)b * S + qrow) * a.ldo + head * HD, acc_o, 1.f / lsum, lhi);
-        if (lhi == 0) a.lse[((int64_t)b * a.ph + head) * S + qrow] = m + log2f(lsum);
-    }
+}
+
+// Causal rows differ in length: block i of a sequence meets i + 1 blocks of keys.  A workgroup therefore
+// takes blocks i and n - 1 - i of one (sequence, head), one after the other, so that all workgroups do
+// the same amount of work (they are all resident at once: nothing else would even them out).
+__device__ inline int paired_blocks(int nblocks, int x, int (&blk)[2]) {
+    blk[0] = nblocks - 1 - x, blk[1] = x;
+    return blk[0] == blk[1] ? 1 : 2;
+}
+
+template <int QF, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SDP_ATTN_WPE_FWD, SDP_ATTN_WPE_FWD)))
+void attn_fwd_kernel(CoreArgs a, int nblocks) {
+    __shared__ __attribute__((aligned(16))) unsigned char sK[2][TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV[2][TILE_BYTES];
+    int blk[2];
+    const int n = paired_blocks(nblocks, blockIdx.x, blk);
+    for (int i = 0; i < n; ++i) attn_fwd_block<QF, NW>(a, blk[i] * 32 * QF * NW, blockIdx.y, blockIdx.z, sK, sV);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -244,13 +338,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // register operands; P is recomputed from the stored log-sum-exp.
 //   dP[q][k] = dO[q] . V[k];  dZ = P (dP - delta[q]);  dQ[q] = scale sum_k dZ[q][k] K[k]
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(CoreArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
+__device__ inline void attn_bwd_dq_block(const CoreArgs& a, const int q0, const int head, const int b,
+                                         unsigned char (&sK)[TILE_BYTES], unsigned char (&sV)[TILE_BYTES]) {
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int q0 = (gridDim.x - 1 - blockIdx.x) * BQ;
-    const int head = blockIdx.y, b = blockIdx.z;
     const int S = a.S;
     const uint16_t* gQ = a.qkv + (int64_t)b * S * a.ldq + head * HD;
     const uint16_t* gK = gQ + a.ph * HD;
@@ -330,21 +421,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (qrow < S) store_rows(a.dqkv + ((int64_t)b * S + qrow) * a.ldq + head * HD, acc, a.scale, lhi);
 }
 
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(CoreArgs a, int nblocks) {
+    __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
+    int blk[2];
+    const int n = paired_blocks(nblocks, blockIdx.x, blk);
+    for (int i = 0; i < n; ++i) attn_bwd_dq_block(a, blk[i] * BQ, blockIdx.y, blockIdx.z, sK, sV);
+}
+
 // ---------------------------------------------------------------------------------------------------
 // Backward, dK and dV.  Workgroup = 128 keys of one (sequence, head); wave w keeps keys k0 + 32 w .. + 31
 // (K and V rows) as register operands and walks the query tiles from the diagonal to the end of the
 // sequence; Q, dO and the per-query statistics of a tile of 64 queries are staged in LDS.
 //   dV[k] = sum_q P[q][k] dO[q];   dK[k] = scale sum_q dZ[q][k] Q[q]
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_kernel(CoreArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char sQ[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sO[TILE_BYTES];
-    __shared__ __attribute__((aligned(16))) float sL[64];
-    __shared__ __attribute__((aligned(16))) float sD[64];
+__device__ inline void attn_bwd_dkv_block(const CoreArgs& a, const int k0, const int head, const int b,
+                                          unsigned char (&sQ)[TILE_BYTES], unsigned char (&sO)[TILE_BYTES], float (&sL)[64],
+                                          float (&sD)[64]) {
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int k0 = blockIdx.x * BQ; // the first key blocks meet the most queries
-    const int head = blockIdx.y, b = blockIdx.z;
     const int S = a.S;
     const uint16_t* gQ = a.qkv + (int64_t)b * S * a.ldq + head * HD;
     const uint16_t* gK = gQ + a.ph * HD;
@@ -431,6 +526,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         store_rows(row + a.ph * HD, acc_k, a.scale, lhi);
         store_rows(row + 2 * a.ph * HD, acc_v, 1.f, lhi);
     }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_kernel(CoreArgs a, int nblocks) {
+    __shared__ __attribute__((aligned(16))) unsigned char sQ[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sO[TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) float sL[64];
+    __shared__ __attribute__((aligned(16))) float sD[64];
+    int blk[2];
+    const int n = paired_blocks(nblocks, blockIdx.x, blk); // the first key blocks meet the most queries: same pairing
+    for (int i = 0; i < n; ++i) attn_bwd_dkv_block(a, blk[i] * BQ, blockIdx.y, blockIdx.z, sQ, sO, sL, sD);
 }
 
 // rows of [Wq; Wk; Wv] ([3 H hd][d]) and of WoT ([H hd][d]) that belong to the held heads
@@ -560,7 +665,9 @@ extern "C" int sdp_masked_attn_fwd(int dtype, int Bt, int S, int d, int H, int h
     a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
     {
         ProfileScope ps("attn_core_fwd", s);
-        attn_fwd_kernel<<<dim3((S + BQ - 1) / BQ, ph, Bt), 256, 0, s>>>(a);
+        constexpr int QF = SDP_ATTN_FWD_QF, NW = SDP_ATTN_FWD_NW, ROWS = 32 * QF * NW;
+        const int nblocks = (S + ROWS - 1) / ROWS;
+        attn_fwd_kernel<QF, NW><<<dim3((nblocks + 1) / 2, ph, Bt), 64 * NW, 0, s>>>(a, nblocks);
         rc = launch_status();
         if (rc != SDP_OK) return rc;
     }
@@ -615,16 +722,17 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
     a.dqkv = (uint16_t*)w.dQKV;
     a.S = S, a.ph = ph;
     a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
-    const dim3 grid((S + BQ - 1) / BQ, ph, Bt);
+    const int nblocks = (S + BQ - 1) / BQ;
+    const dim3 grid((nblocks + 1) / 2, ph, Bt);
     {
         ProfileScope ps("attn_core_bwd_dq", s);
-        attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a);
+        attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a, nblocks);
         rc = launch_status();
         if (rc != SDP_OK) return rc;
     }
     {
         ProfileScope ps("attn_core_bwd_dkv", s); // reads the delta written by the dQ kernel
-        attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a);
+        attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a, nblocks);
         rc = launch_status();
         if (rc != SDP_OK) return rc;
     }
