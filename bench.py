@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--no-grad-avg-1b", action="store_true", help="skip the 1B-parameter average measurement")
     ap.add_argument("--avg-steps", type=int, default=20)
     ap.add_argument("--no-attention", action="store_true", help="skip the head-masked attention block measurement")
+    ap.add_argument("--attention-only", action="store_true",
+                    help="measure the head-masked attention block alone and print its object (for profiler runs)")
     ap.add_argument("--events", type=int, default=1, help="1: per-kernel HIP events recorded during the timed steps")
     ap.add_argument("--graph", type=int, default=0, help="1: capture one step into a HIP graph and replay it (no per-kernel events)")
     ap.add_argument("--streams", type=int, default=1,
@@ -220,6 +222,9 @@ def main():
         sys.exit(3)
     sdp.lib()
     torch.cuda.set_device(0)
+    if a.attention_only:
+        print(json.dumps({"attention": bench_attention(sdp, torch, max(2, a.steps // 4))}))
+        return
     w = workloads.MLP_CONFIGS[a.workload]
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = "cuda"

@@ -581,7 +581,7 @@ FwdWs fwd_ws(char* w, int d, int E) {
 
 struct BwdWs {
     int32_t *rows_qkv, *rows_o;
-    void *dO, *dQKV, *dQKVt, *Ot, *Xt, *dYt, *Wc;
+    void *dO, *dQKV, *dQKVt, *Ot, *Xt, *dYt, *Wc, *split;
     float* delta;
     size_t bytes;
 };
@@ -599,6 +599,8 @@ BwdWs bwd_ws(char* w, int64_t T, int d, int E, int64_t stats) {
     r.Xt = take((size_t)d * ld_tokens(T) * 2);
     r.dYt = take((size_t)d * ld_tokens(T) * 2);
     r.Wc = take((size_t)d * 3 * E * 2);
+    const size_t sp = gemm_split_ws_bytes(E, d, (int)T, 4); // partial sums of the batched weight-gradient launch
+    r.split = sp ? take(sp) : nullptr;
     r.bytes = off;
     return r;
 }
@@ -765,6 +767,7 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
         dw.Cb[i] = (uint16_t*)dWqkv + i * part;
     }
     dw.Ab[3] = w.Ot, dw.Bb[3] = w.dYt, dw.Cb[3] = dWoT;
+    dw.split_ws = w.split;
     if (gemm_mfma_supported(dw)) {
         rc = gemm_mfma_bf16(dw, s);
         if (rc != SDP_OK) return rc;

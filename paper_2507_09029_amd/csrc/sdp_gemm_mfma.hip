@@ -46,6 +46,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -75,6 +76,10 @@ struct Dev {
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
     const uint16_t *Ab[kMaxBatch], *Bb[kMaxBatch];
     uint16_t* Cb[kMaxBatch];
+    // OP_DW_SPLIT: the depth is cut into ksplit ranges of ksteps steps; each (range, problem) is a "problem" of
+    // the launch and leaves its fp32 partial sums in partial[range][problem][M][N]
+    int ksplit, ksteps;
+    float* partial;
 };
 
 // two fp32 -> packed bf16, round to nearest even (the hardware's v_cvt_pk_bf16_f32)
@@ -141,7 +146,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         const int base = g.ntot / NUM_XCD, rem = g.ntot % NUM_XCD;
         bid = x * base + (x < rem ? x : rem) + j;
     }
-    const int nb = OP == OP_DW ? g.nbatch : 1;
+    constexpr bool kBatched = OP == OP_DW || OP == OP_DW_SPLIT;
+    constexpr bool kSplit = OP == OP_DW_SPLIT;
+    const int nb = kBatched ? g.nbatch * (kSplit ? g.ksplit : 1) : 1;
     int tile_m, tile_n, batch;
     {
         const int per_group = g.group_m * g.tiles_n * nb;
@@ -157,7 +164,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     const uint16_t* gA = g.A;
     const uint16_t* gB = g.B;
     uint16_t* gC = g.C;
-    if (OP == OP_DW) {
+    int kpart = 0; // depth range of this workgroup (OP_DW_SPLIT)
+    if (kSplit) kpart = batch / g.nbatch, batch -= kpart * g.nbatch;
+    if (kBatched) {
         // selected by comparisons: a runtime index into a by-value kernel argument would go through scratch
         static_assert(kMaxBatch == 4, "one comparison per problem");
         gA = batch == 0 ? g.Ab[0] : (batch == 1 ? g.Ab[1] : (batch == 2 ? g.Ab[2] : g.Ab[3]));
@@ -169,7 +178,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
 
     // ---- depth steps; a partial last step (K % 64 in {16, 32, 48}) reads its missing chunks from a
     // zero buffer, so that every step issues the same loads and runs all four MFMA sub-steps ----
-    const int nk1 = (g.K + BK - 1) / BK;
+    const int nk_all = (g.K + BK - 1) / BK;
+    const int kt0 = kSplit ? kpart * g.ksteps : 0; // first depth step of this workgroup
+    const int nk1 = kSplit ? (nk_all - kt0 < g.ksteps ? nk_all - kt0 : g.ksteps) : nk_all;
     const int nk = EPI == EPI_DUAL_ACC ? 2 * nk1 : nk1;
 
     // ---- per-lane global source of every slab this wave fills: byte offsets from a uniform base.
@@ -206,7 +217,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     auto issue_a = [&](int kt, auto tail_c, int first, int last) {
         constexpr bool TAIL = decltype(tail_c)::value;
         const bool second = EPI == EPI_DUAL_ACC && kt >= nk1;
-        const int k0 = (second ? kt - nk1 : kt) * BK;
+        const int k0 = (kt0 + (second ? kt - nk1 : kt)) * BK;
         const int krem = g.K - k0;
         unsigned char* sa = lds_a + (kt & 1) * A_BYTES;
         const unsigned char* abase = (const unsigned char*)(second ? g.A2 : gA) + (int64_t)k0 * 2;
@@ -221,7 +232,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     auto issue_b = [&](int kt, int slot, auto tail_c, int first, int last) {
         constexpr bool TAIL = decltype(tail_c)::value;
         const bool second = EPI == EPI_DUAL_ACC && kt >= nk1;
-        const int k0 = (second ? kt - nk1 : kt) * BK;
+        const int k0 = (kt0 + (second ? kt - nk1 : kt)) * BK;
         const int krem = g.K - k0;
         unsigned char* sb = lds_b + slot * B_BYTES;
         const unsigned char* bbase0 = (const unsigned char*)(second ? g.B2 : gB) + (int64_t)k0 * 2;
@@ -377,6 +388,24 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // ================================ epilogue ================================
     // acc[i][j][4q + r] = C(m, n),  m = m0 + WM wm + 32 i + l32,
     //                               n = n0 + (column base of fragment j) + 8 q + 4 lhi + r.
+    if constexpr (kSplit) {
+        // fp32 partial sums of this depth range, 16 bytes (4 columns) per store; N % 8 == 0
+        float* P = g.partial + ((int64_t)kpart * g.nbatch + batch) * g.M * g.N;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + WM * wm + 32 * i + l32;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + WN * wn + 32 * j + 8 * q + 4 * lhi;
+                    if (m < g.M && n < g.N)
+                        *(f32x4*)(P + (int64_t)m * g.N + n) =
+                            f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                }
+        }
+        return;
+    }
     __syncthreads(); // all waves are done with the operand tiles: LDS becomes per-wave strips
     constexpr int SW = Geo::SW, RS = Geo::RS;
     constexpr int CPR = SW / 8;               // 16-byte chunks per strip row
@@ -573,23 +602,28 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     const int ncols = EPI == EPI_SWIGLU_FWD ? BN / 2 : BN;
     g.tiles_n = (d.N + ncols - 1) / ncols;
     const int64_t ntiles = (int64_t)g.tiles_m * g.tiles_n;
-    const int nbatch = OP == OP_DW ? d.nbatch : 1;
+    constexpr bool kBatched = OP == OP_DW || OP == OP_DW_SPLIT;
+    const int ksplit = OP == OP_DW_SPLIT ? d.ksplit : 1;
+    const int nbatch = (kBatched ? d.nbatch : 1) * ksplit; // problems of the launch
     if (ntiles * nbatch > 0x7FFFFFFF) return SDP_ERR_SHAPE;
     g.ntot = (int)(ntiles * nbatch);
-    g.nbatch = nbatch;
+    g.nbatch = kBatched ? d.nbatch : 1;
+    g.ksplit = ksplit;
+    g.ksteps = ((d.K + BK - 1) / BK + ksplit - 1) / ksplit;
+    g.partial = (float*)d.split_ws;
     int na = 1, nbo = 1; // distinct A / B operands among the problems of a batch
     for (int z = 0; z < kMaxBatch; ++z) {
         g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
     }
-    if (OP == OP_DW) {
+    if (kBatched) {
         na = nbo = 0;
-        for (int z = 0; z < nbatch; ++z) {
+        for (int z = 0; z < d.nbatch; ++z) {
             bool newa = true, newb = true;
             for (int y = 0; y < z; ++y) newa &= d.Ab[y] != d.Ab[z], newb &= d.Bb[y] != d.Bb[z];
             na += newa, nbo += newb;
         }
     }
-    g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na, nbo, BM, BN);
+    g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na * ksplit, nbo * ksplit, BM, BN);
     if (const char* e = getenv("SDP_GROUP_M")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
     auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, OP>;
     static bool attr_set = false; // one flag per instantiation
@@ -615,7 +649,7 @@ template <int EPI, int OP>
 int launch(const GemmDesc& d, hipStream_t s) {
     // columns of tile space (gate and up interleaved double the tile columns)
     const int ncols = EPI == EPI_SWIGLU_FWD ? 2 * d.N : d.N;
-    const int nbatch = OP == OP_DW ? d.nbatch : 1;
+    const int nbatch = OP == OP_DW ? d.nbatch : (OP == OP_DW_SPLIT ? d.nbatch * d.ksplit : 1);
     const double c256 = shape_cost(d.M, ncols, nbatch, 256, 256, 1.0);
     const double c192 = shape_cost(d.M, ncols, nbatch, 256, 192, 1.08);
     const double c128 = shape_cost(d.M, ncols, nbatch, 128, 128, 1.6);
@@ -631,7 +665,56 @@ int launch(const GemmDesc& d, hipStream_t s) {
     return launch_cfg<128, 128, 2, 2, EPI, OP>(d, s);
 }
 
+// sum of the depth ranges' fp32 partial results -> bf16 rows of the problems' outputs (optional row scatter);
+// one thread per 8 columns
+struct ReduceArgs {
+    const float* partial;
+    int ksplit, nbatch, M, N;
+    uint16_t* Cb[kMaxBatch];
+    int64_t ldc;
+    const int32_t* cs;
+};
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceArgs r) {
+    const int64_t per = (int64_t)r.M * (r.N / 8);
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= per * r.nbatch) return;
+    const int z = (int)(i / per);
+    const int64_t rem = i - z * per;
+    const int m = (int)(rem / (r.N / 8)), n = (int)(rem % (r.N / 8)) * 8;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
+    for (int k = 0; k < r.ksplit; ++k) { // ranges in depth order
+        const float* p = r.partial + (((int64_t)k * r.nbatch + z) * r.M + m) * r.N + n;
+        a += *(const f32x4*)p;
+        b += *(const f32x4*)(p + 4);
+    }
+    uint16_t* out = z == 0 ? r.Cb[0] : (z == 1 ? r.Cb[1] : (z == 2 ? r.Cb[2] : r.Cb[3]));
+    const int64_t row = r.cs ? r.cs[m] : m;
+    *(u32x4*)(out + row * r.ldc + n) = u32x4{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3])};
+}
+
 } // namespace
+
+// A batched launch with few tiles and a deep K leaves most CUs idle for the whole depth of a tile.  Cutting
+// the depth into r ranges multiplies the workgroups by r at the price of writing and re-reading r fp32
+// copies of the outputs: taken when the 256 x 192 tiling has at most half as many tiles as there are CUs,
+// r = as many as fit in one round (at most 4), every range at least 16 steps deep.
+int gemm_choose_ksplit(int M, int N, int K, int nbatch) {
+    if (nbatch < 1 || N % 8) return 1;
+    const int64_t tiles = (int64_t)((M + 255) / 256) * ((N + 191) / 192) * nbatch;
+    const int nk = (K + BK - 1) / BK;
+    if (tiles * 2 > kNumCU) return 1;
+    int r = (int)(kNumCU / tiles);
+    r = r > 4 ? 4 : r;
+    while (r > 1 && nk / r < 16) --r;
+    if (r < 2) return 1;
+    const int steps = (nk + r - 1) / r;
+    return (nk + steps - 1) / steps; // no empty range
+}
+
+size_t gemm_split_ws_bytes(int M, int N, int K, int nbatch) {
+    const int r = gemm_choose_ksplit(M, N, K, nbatch);
+    return r > 1 ? (size_t)r * nbatch * M * N * sizeof(float) : 0;
+}
 
 bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return false;
@@ -674,7 +757,20 @@ bool gemm_mfma_supported(const GemmDesc& d) {
 int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
     if (!gemm_mfma_supported(d)) return SDP_ERR_UNSUPPORTED;
     // OP only gives every call site its own kernel symbol, so that profiles name the step
-    if (d.epilogue == EPI_STORE && d.nbatch > 0) return launch<EPI_STORE, OP_DW>(d, s);
+    if (d.epilogue == EPI_STORE && d.nbatch > 0) {
+        const int r = d.split_ws ? gemm_choose_ksplit(d.M, d.N, d.K, d.nbatch) : 1;
+        if (r < 2) return launch<EPI_STORE, OP_DW>(d, s);
+        GemmDesc ds = d;
+        ds.ksplit = r;
+        int rc = launch<EPI_STORE, OP_DW_SPLIT>(ds, s);
+        if (rc != SDP_OK) return rc;
+        ReduceArgs ra{(const float*)d.split_ws, r, d.nbatch, d.M, d.N, {}, d.ldc, d.c_scatter};
+        for (int z = 0; z < kMaxBatch; ++z) ra.Cb[z] = (uint16_t*)d.Cb[z];
+        const int64_t threads = (int64_t)d.nbatch * d.M * (d.N / 8);
+        ProfileScope ps("splitk_reduce", s);
+        splitk_reduce_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(ra);
+        return launch_status();
+    }
     if (d.epilogue == EPI_STORE && d.nbatch == 0) return launch<EPI_STORE, OP_DOWN>(d, s);
     if (d.epilogue == EPI_DUAL_ACC) return launch<EPI_DUAL_ACC, OP_DX>(d, s);
     if (d.epilogue == EPI_SWIGLU_FWD) return launch<EPI_SWIGLU_FWD, OP_GATE_UP>(d, s);

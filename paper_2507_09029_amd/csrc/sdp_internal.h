@@ -91,16 +91,24 @@ struct GemmDesc {
     const void* Bb[4] = {nullptr, nullptr, nullptr, nullptr};
     void* Cb[4] = {nullptr, nullptr, nullptr, nullptr};
     int force_tile = 0; // 0 = choose; 256 / 192 / 128 force a tile shape (tuning and tests)
+    // batched launches only: optional fp32 scratch of gemm_split_ws_bytes(M, N, K, nbatch) bytes.  With it, a
+    // launch that has few tiles and a deep K cuts the depth into ranges that run as extra problems, and a second
+    // kernel sums the ranges' partial results (gemm_choose_ksplit decides; 1 = no cut).
+    void* split_ws = nullptr;
+    int ksplit = 1; // set by gemm_mfma_bf16
 };
 
 // tags that give each call site of the MFMA contraction its own kernel symbol
-enum GemmOp { OP_GATE_UP = 0, OP_DOWN = 1, OP_DACT = 2, OP_DX = 3, OP_DW = 4 };
+enum GemmOp { OP_GATE_UP = 0, OP_DOWN = 1, OP_DACT = 2, OP_DX = 3, OP_DW = 4, OP_DW_SPLIT = 5 };
 
 // Plain LDS-tiled FMA contraction, any shape; element type float or bf16 (dtype as sdp_dtype).
 int gemm_simple(int dtype, const GemmDesc& g, hipStream_t s);
 // bf16 MFMA contraction; returns SDP_ERR_UNSUPPORTED when the shape / alignment does not fit.
 int gemm_mfma_bf16(const GemmDesc& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmDesc& g);
+// depth ranges a batched launch of nbatch problems of shape M x N x K would be cut into, and the scratch that takes
+int gemm_choose_ksplit(int M, int N, int K, int nbatch);
+size_t gemm_split_ws_bytes(int M, int N, int K, int nbatch);
 
 // out[c][r] = in[rows ? rows[r] : r][c] for r < R, c < C: (gathered) transpose, element size 2 or 4.
 int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t* rows, int R, int C, void* out,
