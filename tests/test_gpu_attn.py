@@ -126,3 +126,39 @@ def test_argument_errors(sdp):
         sdp.masked_attn_fwd(w.Bt, w.S, 32, X.cuda(), Wqkv, WoT, idx)
     with pytest.raises(sdp.SdpError):  # more held heads than heads
         sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), Wqkv, WoT, torch.arange(5, dtype=torch.int32, device="cuda"))
+
+
+def test_attention_full_step_average(sdp, orc):
+    """Whole N-SDP step at head granularity: head masks -> K workers' forward + backward (scatter layout into
+    full-size gradient buffers) -> coverage-normalised average with one mask byte per parameter row."""
+    from helpers import err_report
+
+    w = AttnWorkload("step", 2, 96, 128, 8, 64, 4, 4, 41)
+    Wqkv, WoT = workloads.attn_weights(w)
+    dWqkv, dWoT = Wqkv.cuda(), WoT.cuda()
+    W64 = [workloads.to_f64(Wqkv[i]) for i in range(3)] + [workloads.to_f64(WoT)]
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    want_mask = orc.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    assert (mask.cpu().numpy() == want_mask).all()
+    E_all = w.H * w.hd
+    bufs = [torch.full((4 * E_all, w.d), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(w.K)]
+    refs = []
+    for k in range(w.K):
+        X, dY = workloads.attn_batch(w, k)
+        Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), dWqkv, dWoT, idx[k])
+        out = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), bufs[k][: 3 * E_all].view(3, E_all, w.d), bufs[k][3 * E_all:])
+        sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), dWqkv, dWoT, idx[k], QKV, O, LSE, dw_layout="scatter", out=out)
+        r = orc.attn_worker_step(w.Bt, w.S, w.hd, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64)
+        refs.append(np.concatenate([r["dWq"], r["dWk"], r["dWv"], r["dWoT"]]))
+    # head h owns rows h hd .. of each of the four matrices
+    row_mask_host = np.tile(np.repeat(want_mask, w.hd, axis=1), (1, 4))
+    row_mask = mask.repeat_interleave(w.hd, dim=1).repeat(1, 4).contiguous()
+    assert (row_mask.cpu().numpy() == row_mask_host).all()
+    avg, c = sdp.coverage_grad_avg(bufs, row_mask)
+    torch.cuda.synchronize()
+    host = [workloads.bf16_bits(b) for b in bufs]
+    same_in, wc = orc.gated_average(host, row_mask_host)
+    assert (c.cpu().numpy() == wc).all() and wc.min() >= 1
+    assert_close(avg.cpu().numpy(), same_in, 1e-5, "average of the GPU's gradients")
+    want, _ = orc.gated_average(refs, row_mask_host)
+    assert err_report(avg.cpu().numpy(), want)[1] <= TOL, "averaged gradient, normwise"
