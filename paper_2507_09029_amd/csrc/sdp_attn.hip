@@ -39,6 +39,9 @@ typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 #ifndef SDP_ATTN_WPE_FWD
 #define SDP_ATTN_WPE_FWD 3
 #endif
+#ifndef SDP_ATTN_WPE_DQ
+#define SDP_ATTN_WPE_DQ 3
+#endif
 #ifndef SDP_ATTN_FWD_QF
 #define SDP_ATTN_FWD_QF 1
 #endif
@@ -98,27 +101,34 @@ __device__ inline bf16x8 frag_cols(const unsigned char* tile, int krow, int col0
     return __builtin_bit_cast(bf16x8, u32x4{a[0], a[1], b[0], b[1]});
 }
 
-// the 16-byte pieces of a 64-row x 64-column tile that thread `tid` of 256 moves: rows clamped to the
-// last valid one (such rows only meet masked logits)
-struct TilePieces {
-    u32x4 v[2];
-    __device__ void fetch(const uint16_t* g, int64_t ld, int row0, int last_row, int tid) {
+// The 16-byte pieces of a 64-row x 64-column tile that thread `tid` of a workgroup of NW waves moves from
+// global memory to LDS through registers.  Rows are clamped to the last valid one (such rows only meet masked
+// logits).  `g` is uniform over the workgroup; the per-thread part of the address is a 32-bit byte offset
+// (the host checks that a sequence's rows span less than 4 GiB), which keeps the address arithmetic to a
+// minimum, one multiply and add per piece.
+template <int NW>
+struct TileMover {
+    static constexpr int PER = 512 / (64 * NW); // pieces per thread and tile
+    u32x4 v[PER];
+    __device__ void fetch(const uint16_t* g, uint32_t ld, int row0, int last_row, int tid) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int c = tid + 256 * i;
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + 64 * NW * i;
             int row = row0 + (c >> 3);
             row = row < last_row ? row : last_row;
-            v[i] = *(const u32x4*)(g + (int64_t)row * ld + (c & 7) * 8);
+            const uint32_t off = ((uint32_t)row * ld + (uint32_t)(c & 7) * 8u) * 2u;
+            v[i] = *(const u32x4*)((const unsigned char*)g + off);
         }
     }
     __device__ void stash(unsigned char* tile, int tid) const {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int c = tid + 256 * i;
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + 64 * NW * i;
             *(u32x4*)(tile + (c >> 3) * RSB + (c & 7) * 16) = v[i];
         }
     }
 };
+typedef TileMover<4> TilePieces;
 
 // a row of 64 bf16 as the depth-along-row operand of lane (row, lhi): sub-step s holds depth 16 s + 8 lhi .. + 7
 __device__ inline void load_row_operand(const uint16_t* g, int64_t ld, int row, int lhi, bf16x8 (&f)[4]) {
@@ -148,28 +158,6 @@ __device__ inline float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
 // buffer and tile t + 2 is fetched from memory.  Every K and V fragment read from LDS serves all QF query
 // blocks of the wave.
 // ---------------------------------------------------------------------------------------------------
-template <int NW>
-struct TileMover {
-    static constexpr int PER = 512 / (64 * NW); // 16-byte pieces per thread and tile
-    u32x4 v[PER];
-    __device__ void fetch(const uint16_t* g, int64_t ld, int row0, int last_row, int tid) {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int c = tid + 64 * NW * i;
-            int row = row0 + (c >> 3);
-            row = row < last_row ? row : last_row;
-            v[i] = *(const u32x4*)(g + (int64_t)row * ld + (c & 7) * 8);
-        }
-    }
-    __device__ void stash(unsigned char* tile, int tid) const {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int c = tid + 64 * NW * i;
-            *(u32x4*)(tile + (c >> 3) * RSB + (c & 7) * 16) = v[i];
-        }
-    }
-};
-
 template <int QF, int NW>
 __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int head, const int b,
                                       unsigned char (&sK)[2][TILE_BYTES], unsigned char (&sV)[2][TILE_BYTES]) {
@@ -202,26 +190,24 @@ __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int
     }
 
     TileMover<NW> pk, pv;
-    pk.fetch(gK, a.ldq, 0, S - 1, tid);
-    pv.fetch(gV, a.ldq, 0, S - 1, tid);
+    const uint32_t ld = (uint32_t)a.ldq;
+    pk.fetch(gK, ld, 0, S - 1, tid);
+    pv.fetch(gV, ld, 0, S - 1, tid);
     pk.stash(sK[0], tid);
     pv.stash(sV[0], tid);
-    if (ntiles > 1) {
-        pk.fetch(gK, a.ldq, 64, S - 1, tid);
-        pv.fetch(gV, a.ldq, 64, S - 1, tid);
-    }
+    // fetches and stashes run unconditionally (rows are clamped, and a tile beyond the last one is never
+    // read): no branch, hence no register copies, around the loop-carried pieces
+    pk.fetch(gK, ld, 64, S - 1, tid);
+    pv.fetch(gV, ld, 64, S - 1, tid);
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const unsigned char* tK = sK[t & 1];
         const unsigned char* tV = sV[t & 1];
-        if (t + 1 < ntiles) { // the other buffer was last read before the barrier that ended step t - 1
-            pk.stash(sK[(t + 1) & 1], tid);
-            pv.stash(sV[(t + 1) & 1], tid);
-        }
-        if (t + 2 < ntiles) {
-            pk.fetch(gK, a.ldq, 64 * (t + 2), S - 1, tid);
-            pv.fetch(gV, a.ldq, 64 * (t + 2), S - 1, tid);
-        }
+        // the other buffer was last read before the barrier that ended step t - 1
+        pk.stash(sK[(t + 1) & 1], tid);
+        pv.stash(sV[(t + 1) & 1], tid);
+        pk.fetch(gK, ld, 64 * (t + 2), S - 1, tid);
+        pv.fetch(gV, ld, 64 * (t + 2), S - 1, tid);
         const int kv0 = 64 * t;
         if (kv0 <= qrow0 + 32 * QF - 1) { // wave-uniform: otherwise every key lies after the wave's queries
             // logits, transposed: sc[f][tb] = D[key 32 tb + ..][query of block f]
@@ -266,7 +252,6 @@ __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int
                 // on.  m is kept in units of the scaled base-2 logits; the scale rides in the multiply-add.
                 const float m_new = fmaxf(m[f], mx * a.scale2);
                 const float alpha = exp2_neg(m[f] - m_new);
-                const bool grew = m_new != m[f];
                 m[f] = m_new;
                 float ps = 0.f;
 #pragma unroll
@@ -278,12 +263,10 @@ __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int
                         ps += p;
                     }
                 lsum[f] = lsum[f] * alpha + ps;
-                if (__any(grew)) { // wave-uniform; alpha = 1 in every lane otherwise
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 2; ++j)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) acc_o[f][j][e] *= alpha;
-                }
+                    for (int e = 0; e < 16; ++e) acc_o[f][j][e] *= alpha;
             }
             // O^T[h][query] += sum_key V[key][h] P[query][key]
 #pragma unroll
@@ -375,17 +358,16 @@ __device__ inline void attn_bwd_dq_block(const CoreArgs& a, const int q0, const 
         for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
 
     TilePieces pk, pv;
-    pk.fetch(gK, a.ldq, 0, S - 1, tid);
-    pv.fetch(gV, a.ldq, 0, S - 1, tid);
+    const uint32_t ld = (uint32_t)a.ldq;
+    pk.fetch(gK, ld, 0, S - 1, tid);
+    pv.fetch(gV, ld, 0, S - 1, tid);
     for (int t = 0; t < ntiles; ++t) {
         __syncthreads();
         pk.stash(sK, tid);
         pv.stash(sV, tid);
         __syncthreads();
-        if (t + 1 < ntiles) {
-            pk.fetch(gK, a.ldq, 64 * (t + 1), S - 1, tid);
-            pv.fetch(gV, a.ldq, 64 * (t + 1), S - 1, tid);
-        }
+        pk.fetch(gK, ld, 64 * (t + 1), S - 1, tid); // unconditional: rows are clamped
+        pv.fetch(gV, ld, 64 * (t + 1), S - 1, tid);
         const int kv0 = 64 * t;
         if (kv0 > qrow0 + 31) continue;
         const bool edge = kv0 + 63 > qrow0 || kv0 + 64 > S;
@@ -421,7 +403,7 @@ __device__ inline void attn_bwd_dq_block(const CoreArgs& a, const int q0, const 
     if (qrow < S) store_rows(a.dqkv + ((int64_t)b * S + qrow) * a.ldq + head * HD, acc, a.scale, lhi);
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(CoreArgs a, int nblocks) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SDP_ATTN_WPE_DQ, SDP_ATTN_WPE_DQ))) void attn_bwd_dq_kernel(CoreArgs a, int nblocks) {
     __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
     int blk[2];
@@ -460,17 +442,14 @@ __device__ inline void attn_bwd_dkv_block(const CoreArgs& a, const int k0, const
 
     const int t0 = k0 / 64, t1 = (S + 63) / 64; // query tiles [t0, t1); t0 < t1 because k0 < S
     TilePieces pq, po;
-    float pstat = 0.f;
-    auto fetch = [&](int t) {
-        pq.fetch(gQ, a.ldq, 64 * t, S - 1, tid);
-        po.fetch(gO, a.ldo, 64 * t, S - 1, tid);
-        if (tid < 128) {
-            int q = 64 * t + (tid & 63);
-            q = q < S ? q : S - 1;
-            pstat = tid < 64 ? a.lse[stat + q] : a.delta[stat + q];
-        }
-    };
-    fetch(t0);
+    const uint32_t ldq32 = (uint32_t)a.ldq, ldo32 = (uint32_t)a.ldo;
+    // per-query statistics of a tile: threads 0..63 carry the log-sum-exp, 64..127 delta
+    const float* gstat = (tid < 64 ? a.lse : a.delta) + stat;
+    const int sq = tid & 63;
+    float pstat;
+    pq.fetch(gQ, ldq32, 64 * t0, S - 1, tid);
+    po.fetch(gO, ldo32, 64 * t0, S - 1, tid);
+    pstat = gstat[64 * t0 + sq < S ? 64 * t0 + sq : S - 1];
     for (int t = t0; t < t1; ++t) {
         __syncthreads();
         pq.stash(sQ, tid);
@@ -478,7 +457,10 @@ __device__ inline void attn_bwd_dkv_block(const CoreArgs& a, const int k0, const
         if (tid < 64) sL[tid] = pstat;
         else if (tid < 128) sD[tid - 64] = pstat;
         __syncthreads();
-        if (t + 1 < t1) fetch(t + 1);
+        // the next tile, unconditionally: rows are clamped
+        pq.fetch(gQ, ldq32, 64 * (t + 1), S - 1, tid);
+        po.fetch(gO, ldo32, 64 * (t + 1), S - 1, tid);
+        pstat = gstat[64 * (t + 1) + sq < S ? 64 * (t + 1) + sq : S - 1];
         const int qt0 = 64 * t;
         if (qt0 + 63 < krow0) continue; // wave-uniform: every query of the tile lies before the wave's keys
         const bool edge = qt0 < krow0 + 31 || qt0 + 64 > S;
@@ -560,6 +542,7 @@ int check(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (d % 8) return SDP_ERR_SHAPE;
     if (Bt > 65535 || ph > 65535) return SDP_ERR_SHAPE;
     if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)Bt * S * 3 * H * hd >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
+    if ((int64_t)S * 3 * ph * hd * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE; // 32-bit byte offsets inside a sequence
     return SDP_OK;
 }
 
