@@ -36,6 +36,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
+// Tuning knobs (compile time): waves per SIMD the forward and dQ kernels are register-allocated for, query blocks
+// per wave and waves per workgroup of the forward kernel.  Measured at 4 x 2048 tokens, 12 heads: 3 waves per
+// SIMD beat 2 (forward 86 -> 77 us) and 4 spill; 2 query blocks per wave spill and were slower.
 #ifndef SDP_ATTN_WPE_FWD
 #define SDP_ATTN_WPE_FWD 3
 #endif
@@ -73,8 +76,6 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
     const bf16x2 v = {(__bf16)lo, (__bf16)hi};
     return __builtin_bit_cast(uint32_t, v);
 }
-__device__ inline float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ inline float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 // elements 8 s .. 8 s + 7 of an accumulator tile as a bf16 operand
 __device__ inline bf16x8 pack_operand(const f32x16& a, int s) {
