@@ -651,7 +651,8 @@ int launch(const GemmDesc& d, hipStream_t s) {
     const int ncols = EPI == EPI_SWIGLU_FWD ? 2 * d.N : d.N;
     const int nbatch = OP == OP_DW ? d.nbatch : (OP == OP_DW_SPLIT ? d.nbatch * d.ksplit : 1);
     const double c256 = shape_cost(d.M, ncols, nbatch, 256, 256, 1.0);
-    const double c192 = shape_cost(d.M, ncols, nbatch, 256, 192, 1.08);
+    // the SwiGLU-forward epilogue pairs gate and up columns inside a tile and has no 192-wide variant
+    const double c192 = EPI == EPI_SWIGLU_FWD ? 1e300 : shape_cost(d.M, ncols, nbatch, 256, 192, 1.08);
     const double c128 = shape_cost(d.M, ncols, nbatch, 128, 128, 1.6);
     // SDP_FORCE_TILE=256|192|128 in the environment overrides the choice (tuning runs and tests)
     int force = d.force_tile;
