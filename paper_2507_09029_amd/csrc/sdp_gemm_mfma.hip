@@ -436,18 +436,27 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
             }
         }
     };
-    // global -> strip: the same chunk mapping, zero outside the matrix
-    auto strip_load = [&](unsigned char* strip, const uint16_t* in, int64_t ld, int i) {
+    // global -> registers -> strip: the same chunk mapping, zero outside the matrix.  The two halves are
+    // separate so that the loads of fragment row i + 1 fly while row i is computed and stored.
+    constexpr int NLD = (NCH + 63) / 64;
+    auto strip_fetch = [&](u32x4 (&v)[NLD], const uint16_t* in, int64_t ld, int i) {
 #pragma unroll
-        for (int it = 0; it < (NCH + 63) / 64; ++it) {
+        for (int it = 0; it < NLD; ++it) {
+            const int c = it * 64 + lane;
+            const int row = c / CPR, cc = c % CPR;
+            const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
+            v[it] = u32x4{0u, 0u, 0u, 0u};
+            if ((NCH % 64 == 0 || c < NCH) && m < g.M && n < g.N) v[it] = *(const u32x4*)(in + (int64_t)m * ld + n);
+        }
+    };
+    auto strip_commit = [&](unsigned char* strip, const u32x4 (&v)[NLD]) {
+#pragma unroll
+        for (int it = 0; it < NLD; ++it) {
             const int c = it * 64 + lane;
             if (NCH % 64 != 0 && c >= NCH) break;
             const int row = c / CPR, cc = c % CPR;
-            const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (m < g.M && n < g.N) v = *(const u32x4*)(in + (int64_t)m * ld + n);
-            *(u32x2*)(strip + row * RS + cc * 16) = u32x2{v[0], v[1]};
-            *(u32x2*)(strip + row * RS + cc * 16 + 8) = u32x2{v[2], v[3]};
+            *(u32x2*)(strip + row * RS + cc * 16) = u32x2{v[it][0], v[it][1]};
+            *(u32x2*)(strip + row * RS + cc * 16 + 8) = u32x2{v[it][2], v[it][3]};
         }
     };
 
@@ -491,9 +500,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     };
 
+    u32x4 gpre[NLD], upre[NLD]; // SWIGLU_BWD: G and U of the next fragment row, in flight
+    if (EPI == EPI_SWIGLU_BWD) {
+        strip_fetch(gpre, g.Gin, g.ldg, 0);
+        strip_fetch(upre, g.Uin, g.ldg, 0);
+    }
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-        // keep the scheduler from pulling the next fragment row's loads (and their registers) up here
+        // keep the scheduler from pulling later fragment rows' work (and its registers) up here
         __builtin_amdgcn_sched_barrier(0);
         if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
 #pragma unroll
@@ -524,8 +538,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         } else { // EPI_SWIGLU_BWD: three strips per wave (dG, dU, Act)
             unsigned char* strip1 = strip0 + Geo::STRIP;
             unsigned char* strip2 = strip1 + Geo::STRIP;
-            strip_load(strip0, g.Gin, g.ldg, i);
-            strip_load(strip1, g.Uin, g.ldg, i);
+            strip_commit(strip0, gpre);
+            strip_commit(strip1, upre);
+            if (i + 1 < FM) {
+                strip_fetch(gpre, g.Gin, g.ldg, i + 1);
+                strip_fetch(upre, g.Uin, g.ldg, i + 1);
+            }
             u32x2 gq[FN][4], uq[FN][4];
 #pragma unroll
             for (int j = 0; j < FN; ++j)
