@@ -70,7 +70,7 @@ def lib():
         L.orc_attn_bwd.restype = None
         L.orc_attn_bwd.argtypes = [ctypes.c_int64] * 5 + [_f64p] * 18
         L.orc_attn_worker_step.restype = ctypes.c_int64
-        L.orc_attn_worker_step.argtypes = [ctypes.c_int64] * 5 + [_u8p] + [_f64p] * 19
+        L.orc_attn_worker_step.argtypes = [ctypes.c_int] + [ctypes.c_int64] * 5 + [_u8p] + [_f64p] * 19
         L.orc_rho2.restype = ctypes.c_double
         L.orc_rho2.argtypes = [ctypes.c_int, ctypes.c_int64, _u8p]
         _lib = L
@@ -252,11 +252,13 @@ def attn_bwd(Bt, S, hd, X, dY, Wq, Wk, Wv, WoT, Q, K, V, O):
     return dict(dQ=dQ, dK=dK, dV=dV, dX=dX, dWq=dWq, dWk=dWk, dWv=dWv, dWoT=dWoT)
 
 
-def attn_worker_step(Bt, S, hd, head_mask, X, dY, Wq, Wk, Wv, WoT):
-    """One worker's attention forward + backward with heads masked forward (Sec. 3.1, Sec. 4.1).
+def attn_worker_step(Bt, S, hd, head_mask, X, dY, Wq, Wk, Wv, WoT, mode="fm"):
+    """One worker's attention forward + backward with heads masked forward ('fm') or backward ('bm')
+    (Sec. 3.1 applied to the head masks of Sec. 4.1).
 
     Returns full-size fp64 arrays Q, K, V, O [T][H hd]; Y, dX [T][d]; dWq, dWk, dWv, dWoT [H hd][d] and
-    `nonzero_off_mask` (gradient entries of unheld heads that are not exactly zero; must be 0).
+    `nonzero_off_mask` (gradient entries of unheld heads that are not exactly zero before any masking of the
+    gradient; must be 0 under forward masking).
     """
     head_mask = np.ascontiguousarray(head_mask, dtype=np.uint8)
     X, dY, Wq, Wk, Wv, WoT = map(_f64, (X, dY, Wq, Wk, Wv, WoT))
@@ -267,7 +269,7 @@ def attn_worker_step(Bt, S, hd, head_mask, X, dY, Wq, Wk, Wv, WoT):
     names = ["Q", "K", "V", "O", "Y", "dQ", "dK", "dV", "dX", "dWq", "dWk", "dWv", "dWoT"]
     shapes = [(T, E)] * 4 + [(T, d)] + [(T, E)] * 3 + [(T, d)] + [(E, d)] * 4
     out = {n: np.empty(s) for n, s in zip(names, shapes)}
-    nz = lib().orc_attn_worker_step(Bt, S, d, H, hd, _p(head_mask, _u8p),
+    nz = lib().orc_attn_worker_step({"fm": 0, "bm": 1}[mode], Bt, S, d, H, hd, _p(head_mask, _u8p),
                                     *[_p(a, _f64p) for a in (X, dY, Wq, Wk, Wv, WoT)],
                                     *[_p(out[n], _f64p) for n in names])
     out["nonzero_off_mask"] = int(nz)

@@ -590,12 +590,17 @@ void orc_attn_bwd(int64_t Bt, int64_t S, int64_t d, int64_t H, int64_t hd, const
     free(dO);
 }
 
-/* One worker's attention step under forward masking of heads (Sec. 3.1 with   */
-/* m_fwd = m_bwd = the head mask): loss and gradient are evaluated at the      */
-/* gated parameters.  head_mask[H]; outputs are full size.  Returns the number */
-/* of weight-gradient entries of unheld heads that are not exactly zero        */
-/* (the remark of Sec. 3.1 says there are none).                               */
-int64_t orc_attn_worker_step(int64_t Bt, int64_t S, int64_t d, int64_t H, int64_t hd,
+/* One worker's attention step under either masking regime of Sec. 3.1 applied  */
+/* to heads (head_mask[H]; a head owns its rows of Wq, Wk, Wv, WoT).            */
+/*   mode 0, forward masking:  m_fwd = m_bwd = m.  Loss and gradient are        */
+/*     evaluated at the gated parameters; the gradient of every head the        */
+/*     worker does not hold is then exactly zero.                               */
+/*   mode 1, backward masking: m_fwd = all ones, m_bwd = m.  Loss and dX come   */
+/*     from the full block; the weight gradient is kept for held heads only.    */
+/* Outputs are full size.  Returns the number of weight-gradient entries of     */
+/* unheld heads that are not exactly zero BEFORE any masking of the gradient    */
+/* (must be 0 in mode 0).                                                       */
+int64_t orc_attn_worker_step(int mode, int64_t Bt, int64_t S, int64_t d, int64_t H, int64_t hd,
                              const uint8_t* head_mask, const double* X, const double* dY,
                              const double* Wq, const double* Wk, const double* Wv, const double* WoT,
                              double* Q, double* Kp, double* V, double* O, double* Y, double* dQ,
@@ -605,21 +610,30 @@ int64_t orc_attn_worker_step(int64_t Bt, int64_t S, int64_t d, int64_t H, int64_
     const size_t wn = (size_t)E * d;
     uint8_t* row_mask = (uint8_t*)malloc((size_t)E);
     for (int64_t j = 0; j < E; ++j) row_mask[j] = head_mask[j / hd];
-    double* g[4];
-    const double* w[4] = {Wq, Wk, Wv, WoT};
-    for (int i = 0; i < 4; ++i) {
-        g[i] = (double*)malloc(sizeof(double) * wn);
-        orc_gate_rows(E, d, row_mask, w[i], g[i]);
-    }
-    orc_attn_fwd(Bt, S, d, H, hd, X, g[0], g[1], g[2], g[3], Q, Kp, V, O, Y);
-    orc_attn_bwd(Bt, S, d, H, hd, X, dY, g[0], g[1], g[2], g[3], Q, Kp, V, O, dQ, dK, dV, dX, dWq, dWk, dWv, dWoT);
     int64_t nz = 0;
-    for (int64_t j = 0; j < E; ++j)
-        if (!row_mask[j])
-            for (int64_t e = 0; e < d; ++e)
-                nz += (dWq[j * d + e] != 0.0) + (dWk[j * d + e] != 0.0) + (dWv[j * d + e] != 0.0) +
-                      (dWoT[j * d + e] != 0.0);
-    for (int i = 0; i < 4; ++i) free(g[i]);
+    if (mode == 0) {
+        double* g[4];
+        const double* w[4] = {Wq, Wk, Wv, WoT};
+        for (int i = 0; i < 4; ++i) {
+            g[i] = (double*)malloc(sizeof(double) * wn);
+            orc_gate_rows(E, d, row_mask, w[i], g[i]);
+        }
+        orc_attn_fwd(Bt, S, d, H, hd, X, g[0], g[1], g[2], g[3], Q, Kp, V, O, Y);
+        orc_attn_bwd(Bt, S, d, H, hd, X, dY, g[0], g[1], g[2], g[3], Q, Kp, V, O, dQ, dK, dV, dX, dWq, dWk, dWv, dWoT);
+        for (int64_t j = 0; j < E; ++j)
+            if (!row_mask[j])
+                for (int64_t e = 0; e < d; ++e)
+                    nz += (dWq[j * d + e] != 0.0) + (dWk[j * d + e] != 0.0) + (dWv[j * d + e] != 0.0) +
+                          (dWoT[j * d + e] != 0.0);
+        for (int i = 0; i < 4; ++i) free(g[i]);
+    } else {
+        orc_attn_fwd(Bt, S, d, H, hd, X, Wq, Wk, Wv, WoT, Q, Kp, V, O, Y);
+        orc_attn_bwd(Bt, S, d, H, hd, X, dY, Wq, Wk, Wv, WoT, Q, Kp, V, O, dQ, dK, dV, dX, dWq, dWk, dWv, dWoT);
+        for (int64_t j = 0; j < E; ++j)
+            if (!row_mask[j])
+                for (int64_t e = 0; e < d; ++e)
+                    dWq[j * d + e] = dWk[j * d + e] = dWv[j * d + e] = dWoT[j * d + e] = 0.0;
+    }
     free(row_mask);
     return nz;
 }

@@ -144,3 +144,34 @@ def test_forward_masked_worker_is_the_block_of_its_heads(orc, held):
     # and it differs from the dense block
     dense, _ = _dense(orc, Bt, S, hd, s)
     assert np.abs(dense["Y"] - r["Y"]).max() > 1e-3
+
+
+@pytest.mark.parametrize("held", [[2], [0, 3]])
+def test_backward_masked_worker_sees_the_dense_block(orc, held):
+    """Backward masking (m_fwd = all ones, m_bwd = m): outputs and dX are those of the dense block, the weight
+    gradient is the dense one on the held heads' rows and zero elsewhere; with every head held both regimes
+    coincide with the dense block."""
+    Bt, S, d, H, hd = 2, 11, 9, 4, 4
+    s = _setup(9, Bt, S, d, H, hd)
+    mask = np.zeros(H, np.uint8)
+    mask[held] = 1
+    f, b = _dense(orc, Bt, S, hd, s)
+    r = orc.attn_worker_step(Bt, S, hd, mask, s["X"], s["dY"], s["Wq"], s["Wk"], s["Wv"], s["WoT"], mode="bm")
+    for name in ("Q", "K", "V", "O", "Y"):
+        assert (r[name] == f[name]).all()
+    assert (r["dX"] == b["dX"]).all()
+    rows = np.concatenate([np.arange(h * hd, (h + 1) * hd) for h in held])
+    off = np.setdiff1d(np.arange(H * hd), rows)
+    for name in ("dWq", "dWk", "dWv", "dWoT"):
+        assert (r[name][rows] == b[name][rows]).all()
+        assert (r[name][off] == 0).all() and np.abs(b[name][off]).max() > 0
+    assert r["nonzero_off_mask"] == 0  # nothing is counted in this regime
+    full = orc.attn_worker_step(Bt, S, hd, np.ones(H, np.uint8), s["X"], s["dY"], s["Wq"], s["Wk"], s["Wv"], s["WoT"], mode="bm")
+    for name in ("Y", "dX", "dWq", "dWk", "dWv", "dWoT"):
+        assert (full[name] == (f[name] if name == "Y" else b[name])).all()
+    # the two regimes differ in Y and dX as soon as a head is not held; for a given upstream gradient dY the
+    # heads do not interact, so the held heads' weight gradients are the same under both
+    fm = orc.attn_worker_step(Bt, S, hd, mask, s["X"], s["dY"], s["Wq"], s["Wk"], s["Wv"], s["WoT"], mode="fm")
+    assert np.abs(fm["Y"] - r["Y"]).max() > 1e-3 and np.abs(fm["dX"] - r["dX"]).max() > 1e-3
+    for name in ("dWq", "dWk", "dWv", "dWoT"):
+        np.testing.assert_allclose(fm[name][rows], r[name][rows], rtol=1e-13, atol=1e-15)
