@@ -161,8 +161,8 @@ def bench_attention(sdp, torch, steps):
     Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(w))
     mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
     X, dY = (t.cuda() for t in workloads.attn_batch(w, 0))
-    wsf = torch.empty(sdp.masked_attn_fwd_workspace_bytes(X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
-    wsb = torch.empty(sdp.masked_attn_bwd_workspace_bytes(X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
+    wsf = torch.empty(sdp.masked_attn_fwd_workspace_bytes("fm", X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
+    wsb = torch.empty(sdp.masked_attn_bwd_workspace_bytes("fm", X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
     E = w.ph * w.hd
     fo = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), torch.empty((w.T, 3 * E), dtype=X.dtype, device="cuda"),
           torch.empty((w.T, E), dtype=X.dtype, device="cuda"), torch.empty((w.Bt, w.ph, w.S), dtype=torch.float32, device="cuda"))
@@ -171,8 +171,8 @@ def bench_attention(sdp, torch, steps):
 
     def one_pass():
         for k in range(w.K):
-            Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X, Wqkv, WoT, idx[k], out=fo, ws=wsf)
-            sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X, dY, Wqkv, WoT, idx[k], QKV, O, LSE, out=bo, ws=wsb)
+            Y, QKV, O, LSE = sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X, Wqkv, WoT, idx[k], out=fo, ws=wsf)
+            sdp.masked_attn_bwd("fm", w.Bt, w.S, w.hd, X, dY, Wqkv, WoT, idx[k], QKV, O, LSE, out=bo, ws=wsb)
 
     for _ in range(2):
         one_pass()

@@ -144,46 +144,51 @@ int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int p, const vo
 
 /* ---------------------------------------------------------------------------------------------
  * One worker's attention block with head-level masks (Sec. 4.1: the neuron-level variant masks
- * attention heads on W_Q, W_K, W_V and W_O), under forward masking (Sec. 3.1, m_fwd = m_bwd = m): the
- * block is evaluated at the gated parameters, i.e. as the smaller dense block made of the worker's ph
- * held heads head_idx_k[0..ph) -- the projections shrink to those heads' rows and the attention core
- * runs on those heads only.  Bias-free causal self-attention over Bt sequences of S tokens (token
+ * attention heads on W_Q, W_K, W_V and W_O), under either regime of Sec. 3.1:
+ *   SDP_MASK_FORWARD  (m_fwd = m_bwd = m): the block is evaluated at the gated parameters, i.e. as the
+ *     smaller dense block made of the worker's ph held heads head_idx_k[0..ph) -- the projections shrink
+ *     to those heads' rows and the attention core runs on those heads only (n = ph below).
+ *   SDP_MASK_BACKWARD (m_fwd = all ones): the dense block over all H heads; head_idx_k and ph are
+ *     ignored by the forward call (n = H below).
+ * Bias-free causal self-attention over Bt sequences of S tokens (token
  * t = b S + s, T = Bt S), H heads of width hd, logits scaled by 1 / sqrt(hd), no positional rotation
  * (the paper does not state one), every weight neuron-major as in the MLP:
  *   Wqkv [3][H hd][d] in: W_Q, W_K, W_V stacked; row h hd + r of each = feature r of head h
  *   WoT  [H hd][d]    in: row j = column j of W_O
  *   Q = X Wq[S]^T, K = X Wk[S]^T, V = X Wv[S]^T;  P_h = softmax over s' <= s of Q_h K_h^T / sqrt(hd);
- *   O_h = P_h V_h;  Y = sum over held h of O_h WoT_h.
+ *   O_h = P_h V_h;  Y = sum over the n heads of O_h WoT_h   (S = the held heads, or all of them).
  *   X [T][d] in;  head_idx_k [ph] i32 in (strictly ascending, in [0, H); trusted like idx_k above)
  *   Y [T][d] out
- *   QKV_save [T][3 ph hd] out: Q | K | V of the held heads (head i of the list at columns i hd of each)
- *   O_save [T][ph hd] out;  LSE_save [Bt][ph][S] fp32 out: log2 of the softmax denominators, logits in
+ *   QKV_save [T][3 n hd] out: Q | K | V of the n heads (head i of the list at columns i hd of each)
+ *   O_save [T][n hd] out;  LSE_save [Bt][n][S] fp32 out: log2 of the softmax denominators, logits in
  *   base 2 -- kept for sdp_masked_attn_bwd.
  *   ws: sdp_masked_attn_fwd_workspace_bytes(...).
- * Limits: dtype SDP_BF16 and hd = 64 only (else UNSUPPORTED); d a multiple of 8; Bt, ph <= 65535;
+ * Limits: dtype SDP_BF16 and hd = 64 only (else UNSUPPORTED); d a multiple of 8; Bt, H <= 65535;
  * pointers 16-byte aligned.  Errors as for the MLP calls.
  * ------------------------------------------------------------------------------------------- */
-size_t sdp_masked_attn_fwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int ph);
-int sdp_masked_attn_fwd(int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* Wqkv,
-                        const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save, void* O_save,
-                        float* LSE_save, void* ws, size_t ws_bytes, void* stream);
+size_t sdp_masked_attn_fwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph);
+int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
+                        const void* Wqkv, const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save,
+                        void* O_save, float* LSE_save, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Backward of the same block for upstream gradient dY: dX [T][d] through the held heads, and the
- * weight gradients of the held heads only (all others are exactly zero by Sec. 3.1 and are not
- * materialised).
+ * Backward of the same block for upstream gradient dY.
+ *   SDP_MASK_FORWARD : dX [T][d] through the held heads, and the weight gradients of the held heads
+ *     (all others are exactly zero by Sec. 3.1 and are not materialised).
+ *   SDP_MASK_BACKWARD: dX through the full block (all H heads); the weight gradient is computed ONLY
+ *     for the worker's held heads (m_bwd = m): their rows of the dense dW_Q, dW_K, dW_V, dW_O.
  *   dw_layout SDP_DW_COMPACT: dWqkv [3][ph hd][d], dWoT [ph hd][d]; row i hd + r belongs to head
  *     head_idx_k[i].
  *   dw_layout SDP_DW_SCATTER: full [3][H hd][d] and [H hd][d] buffers; the held heads' rows are
  *     written, all other rows are left untouched.
- *   QKV_save, O_save, LSE_save: what sdp_masked_attn_fwd stored for the same shapes and heads.
+ *   QKV_save, O_save, LSE_save: what sdp_masked_attn_fwd stored for the same mode, shapes and heads.
  *   ws: sdp_masked_attn_bwd_workspace_bytes(...).
  * ------------------------------------------------------------------------------------------- */
-size_t sdp_masked_attn_bwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int ph);
-int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* dY,
-                        const void* Wqkv, const void* WoT, const int32_t* head_idx_k, const void* QKV_save,
-                        const void* O_save, const float* LSE_save, void* dX, void* dWqkv, void* dWoT,
-                        int dw_layout, void* ws, size_t ws_bytes, void* stream);
+size_t sdp_masked_attn_bwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph);
+int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
+                        const void* dY, const void* Wqkv, const void* WoT, const int32_t* head_idx_k,
+                        const void* QKV_save, const void* O_save, const float* LSE_save, void* dX, void* dWqkv,
+                        void* dWoT, int dw_layout, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Gated average of K workers' gradients (Sec. 3.1, eq. "average"), normalised per coordinate by

@@ -65,13 +65,13 @@ def lib():
     L.sdp_masked_mlp_bwd.restype = i32
     L.sdp_masked_mlp_bwd.argtypes = [i32] * 6 + [vp] * 12 + [i32, vp, sz, vp]
     L.sdp_masked_attn_fwd_workspace_bytes.restype = sz
-    L.sdp_masked_attn_fwd_workspace_bytes.argtypes = [i32] * 7
+    L.sdp_masked_attn_fwd_workspace_bytes.argtypes = [i32] * 8
     L.sdp_masked_attn_bwd_workspace_bytes.restype = sz
-    L.sdp_masked_attn_bwd_workspace_bytes.argtypes = [i32] * 7
+    L.sdp_masked_attn_bwd_workspace_bytes.argtypes = [i32] * 8
     L.sdp_masked_attn_fwd.restype = i32
-    L.sdp_masked_attn_fwd.argtypes = [i32] * 7 + [vp] * 9 + [sz, vp]
+    L.sdp_masked_attn_fwd.argtypes = [i32] * 8 + [vp] * 9 + [sz, vp]
     L.sdp_masked_attn_bwd.restype = i32
-    L.sdp_masked_attn_bwd.argtypes = [i32] * 7 + [vp] * 11 + [i32, vp, sz, vp]
+    L.sdp_masked_attn_bwd.argtypes = [i32] * 8 + [vp] * 11 + [i32, vp, sz, vp]
     L.sdp_coverage_grad_avg.restype = i32
     L.sdp_coverage_grad_avg.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp]
     L.sdp_coverage_avg_adamw.restype = i32
@@ -219,49 +219,53 @@ def masked_mlp_bwd(mode, X, dY, W1, W3, W2T, idx_k, G_save, U_save, dw_layout="c
     return dX, dW1, dW3, dW2T
 
 
-def masked_attn_fwd_workspace_bytes(dtype, Bt, S, d, H, hd, ph):
-    return int(lib().sdp_masked_attn_fwd_workspace_bytes(_DTYPES[dtype], Bt, S, d, H, hd, ph))
+def masked_attn_fwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph):
+    return int(lib().sdp_masked_attn_fwd_workspace_bytes(_MODES[mode], _DTYPES[dtype], Bt, S, d, H, hd, ph))
 
 
-def masked_attn_bwd_workspace_bytes(dtype, Bt, S, d, H, hd, ph):
-    return int(lib().sdp_masked_attn_bwd_workspace_bytes(_DTYPES[dtype], Bt, S, d, H, hd, ph))
+def masked_attn_bwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph):
+    return int(lib().sdp_masked_attn_bwd_workspace_bytes(_MODES[mode], _DTYPES[dtype], Bt, S, d, H, hd, ph))
 
 
-def masked_attn_fwd(Bt, S, hd, X, Wqkv, WoT, head_idx_k, out=None, ws=None):
-    """One worker's head-masked attention forward.
+def masked_attn_fwd(mode, Bt, S, hd, X, Wqkv, WoT, head_idx_k, out=None, ws=None):
+    """One worker's head-masked attention forward ('fm': the held heads only; 'bm': the dense block).
 
-    X [Bt S][d]; Wqkv [3][H hd][d]; WoT [H hd][d]; head_idx_k int32 [ph].
-    Returns (Y [T][d], QKV_save [T][3 ph hd], O_save [T][ph hd], LSE_save fp32 [Bt][ph][S]).
+    X [Bt S][d]; Wqkv [3][H hd][d]; WoT [H hd][d]; head_idx_k int32 [ph].  With n = ph ('fm') or H ('bm'):
+    returns (Y [T][d], QKV_save [T][3 n hd], O_save [T][n hd], LSE_save fp32 [Bt][n][S]).
     """
+    m = _MODES[mode]
     dt = X.dtype
     T, d = X.shape
     E_all = WoT.shape[0]
     H = E_all // hd
-    ph = int(head_idx_k.numel())
+    ph = int(head_idx_k.numel()) if head_idx_k is not None else H
+    n = ph if m == MASK_FORWARD else H
     if T != Bt * S or tuple(Wqkv.shape) != (3, E_all, d) or tuple(WoT.shape) != (E_all, d) or H * hd != E_all:
         raise ValueError("attention shapes do not fit together")
     if out is None:
-        out = (torch.empty((T, d), dtype=dt, device=X.device), torch.empty((T, 3 * ph * hd), dtype=dt, device=X.device),
-               torch.empty((T, ph * hd), dtype=dt, device=X.device),
-               torch.empty((Bt, ph, S), dtype=torch.float32, device=X.device))
+        out = (torch.empty((T, d), dtype=dt, device=X.device), torch.empty((T, 3 * n * hd), dtype=dt, device=X.device),
+               torch.empty((T, n * hd), dtype=dt, device=X.device),
+               torch.empty((Bt, n, S), dtype=torch.float32, device=X.device))
     Y, QKV, O, LSE = out
     if ws is None:
-        ws = _ws(masked_attn_fwd_workspace_bytes(dt, Bt, S, d, H, hd, ph), X.device)
+        ws = _ws(masked_attn_fwd_workspace_bytes(m, dt, Bt, S, d, H, hd, ph), X.device)
     st = lib().sdp_masked_attn_fwd(
-        _DTYPES[dt], Bt, S, d, H, hd, ph, _dev(X, dt, "X"), _dev(Wqkv, dt, "Wqkv"), _dev(WoT, dt, "WoT"),
-        _dev(head_idx_k, torch.int32, "head_idx_k"), _dev(Y, dt, "Y"), _dev(QKV, dt, "QKV_save"), _dev(O, dt, "O_save"),
-        _dev(LSE, torch.float32, "LSE_save"), ws.data_ptr(), ws.numel(), _stream())
+        m, _DTYPES[dt], Bt, S, d, H, hd, ph, _dev(X, dt, "X"), _dev(Wqkv, dt, "Wqkv"), _dev(WoT, dt, "WoT"),
+        _dev(head_idx_k, torch.int32, "head_idx_k") if head_idx_k is not None else None, _dev(Y, dt, "Y"),
+        _dev(QKV, dt, "QKV_save"), _dev(O, dt, "O_save"), _dev(LSE, torch.float32, "LSE_save"), ws.data_ptr(), ws.numel(),
+        _stream())
     _check(st, "sdp_masked_attn_fwd")
     return Y, QKV, O, LSE
 
 
-def masked_attn_bwd(Bt, S, hd, X, dY, Wqkv, WoT, head_idx_k, QKV_save, O_save, LSE_save, dw_layout="compact", out=None,
-                    ws=None):
+def masked_attn_bwd(mode, Bt, S, hd, X, dY, Wqkv, WoT, head_idx_k, QKV_save, O_save, LSE_save, dw_layout="compact",
+                    out=None, ws=None):
     """One worker's head-masked attention backward.
 
     Returns (dX [T][d], dWqkv, dWoT): [3][ph hd][d] and [ph hd][d] compact, or full-size buffers with the held
-    heads' rows written (scatter).
+    heads' rows written (scatter).  'bm': dX through all heads, weight gradients of the held heads only.
     """
+    m = _MODES[mode]
     dt = X.dtype
     T, d = X.shape
     E_all = WoT.shape[0]
@@ -274,9 +278,9 @@ def masked_attn_bwd(Bt, S, hd, X, dY, Wqkv, WoT, head_idx_k, QKV_save, O_save, L
                torch.empty((rows, d), dtype=dt, device=X.device))
     dX, dWqkv, dWoT = out
     if ws is None:
-        ws = _ws(masked_attn_bwd_workspace_bytes(dt, Bt, S, d, H, hd, ph), X.device)
+        ws = _ws(masked_attn_bwd_workspace_bytes(m, dt, Bt, S, d, H, hd, ph), X.device)
     st = lib().sdp_masked_attn_bwd(
-        _DTYPES[dt], Bt, S, d, H, hd, ph, _dev(X, dt, "X"), _dev(dY, dt, "dY"), _dev(Wqkv, dt, "Wqkv"), _dev(WoT, dt, "WoT"),
+        m, _DTYPES[dt], Bt, S, d, H, hd, ph, _dev(X, dt, "X"), _dev(dY, dt, "dY"), _dev(Wqkv, dt, "Wqkv"), _dev(WoT, dt, "WoT"),
         _dev(head_idx_k, torch.int32, "head_idx_k"), _dev(QKV_save, dt, "QKV_save"), _dev(O_save, dt, "O_save"),
         _dev(LSE_save, torch.float32, "LSE_save"), _dev(dX, dt, "dX"), _dev(dWqkv, dt, "dWqkv"), _dev(dWoT, dt, "dWoT"),
         lay, ws.data_ptr(), ws.numel(), _stream())

@@ -535,17 +535,21 @@ __global__ void head_rows_kernel(const int32_t* __restrict__ head_idx, int ph, i
 
 int64_t ld_tokens(int64_t T) { return T + 64; } // see the MLP path: rows must not sit a power of two apart
 
-int check(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+int check(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+    if (mode != SDP_MASK_FORWARD && mode != SDP_MASK_BACKWARD) return SDP_ERR_INVALID_ARG;
     if (dtype != SDP_BF16) return SDP_ERR_UNSUPPORTED;
     if (Bt < 1 || S < 1 || d < 1 || H < 1) return SDP_ERR_INVALID_ARG;
     if (hd != HD) return SDP_ERR_UNSUPPORTED;
     if (ph < 1 || ph > H) return SDP_ERR_SHAPE;
     if (d % 8) return SDP_ERR_SHAPE;
-    if (Bt > 65535 || ph > 65535) return SDP_ERR_SHAPE;
+    if (Bt > 65535 || H > 65535) return SDP_ERR_SHAPE;
     if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)Bt * S * 3 * H * hd >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
-    if ((int64_t)S * 3 * ph * hd * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE; // 32-bit byte offsets inside a sequence
+    if ((int64_t)S * 3 * H * hd * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE; // 32-bit byte offsets inside a sequence
     return SDP_OK;
 }
+
+// heads the forward pass and the core run on: the held ones (forward masking) or all of them (backward masking)
+int heads_run(int mode, int H, int ph) { return mode == SDP_MASK_FORWARD ? ph : H; }
 
 struct FwdWs {
     int32_t *rows_qkv, *rows_o;
@@ -569,12 +573,13 @@ struct BwdWs {
     float* delta;
     size_t bytes;
 };
-BwdWs bwd_ws(char* w, int64_t T, int d, int E, int64_t stats) {
+// E = width the core runs on, Eh = width of the held heads (equal under forward masking)
+BwdWs bwd_ws(char* w, int64_t T, int d, int E, int Eh, int64_t stats) {
     BwdWs r;
     size_t off = 0;
     auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
-    r.rows_qkv = (int32_t*)take((size_t)3 * E * 4);
-    r.rows_o = (int32_t*)take((size_t)E * 4);
+    r.rows_qkv = (int32_t*)take((size_t)3 * Eh * 4);
+    r.rows_o = (int32_t*)take((size_t)Eh * 4);
     r.dO = take((size_t)T * E * 2);
     r.dQKV = take((size_t)T * 3 * E * 2);
     r.delta = (float*)take((size_t)stats * 4);
@@ -583,7 +588,7 @@ BwdWs bwd_ws(char* w, int64_t T, int d, int E, int64_t stats) {
     r.Xt = take((size_t)d * ld_tokens(T) * 2);
     r.dYt = take((size_t)d * ld_tokens(T) * 2);
     r.Wc = take((size_t)d * 3 * E * 2);
-    const size_t sp = gemm_split_ws_bytes(E, d, (int)T, 4); // partial sums of the batched weight-gradient launch
+    const size_t sp = gemm_split_ws_bytes(Eh, d, (int)T, 4); // partial sums of the batched weight-gradient launch
     r.split = sp ? take(sp) : nullptr;
     r.bytes = off;
     return r;
@@ -606,38 +611,45 @@ int head_rows(const int32_t* head_idx, int ph, int H, int hd, int32_t* rows_qkv,
 
 using namespace sdp;
 
-extern "C" size_t sdp_masked_attn_fwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
-    if (check(dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
-    return fwd_ws(nullptr, d, ph * hd).bytes;
+extern "C" size_t sdp_masked_attn_fwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+    if (check(mode, dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
+    return fwd_ws(nullptr, d, heads_run(mode, H, ph) * hd).bytes;
 }
 
-extern "C" size_t sdp_masked_attn_bwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int ph) {
-    if (check(dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
-    return bwd_ws(nullptr, (int64_t)Bt * S, d, ph * hd, (int64_t)Bt * ph * S).bytes;
+extern "C" size_t sdp_masked_attn_bwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
+    if (check(mode, dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
+    const int hr = heads_run(mode, H, ph);
+    return bwd_ws(nullptr, (int64_t)Bt * S, d, hr * hd, ph * hd, (int64_t)Bt * hr * S).bytes;
 }
 
-extern "C" int sdp_masked_attn_fwd(int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* Wqkv,
-                                   const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save, void* O_save,
-                                   float* LSE_save, void* ws, size_t ws_bytes, void* stream) {
-    int rc = check(dtype, Bt, S, d, H, hd, ph);
+extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
+                                   const void* Wqkv, const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save,
+                                   void* O_save, float* LSE_save, void* ws, size_t ws_bytes, void* stream) {
+    if (mode == SDP_MASK_BACKWARD) ph = H; // the forward pass is the dense block; the list is not looked at
+    int rc = check(mode, dtype, Bt, S, d, H, hd, ph);
     if (rc != SDP_OK) return rc;
-    if (!X || !Wqkv || !WoT || !head_idx_k || !Y || !QKV_save || !O_save || !LSE_save) return SDP_ERR_INVALID_ARG;
+    if (!X || !Wqkv || !WoT || !Y || !QKV_save || !O_save || !LSE_save) return SDP_ERR_INVALID_ARG;
+    if (mode == SDP_MASK_FORWARD && !head_idx_k) return SDP_ERR_INVALID_ARG;
     for (const void* q : {X, Wqkv, WoT, (const void*)Y, (const void*)QKV_save, (const void*)O_save, (const void*)LSE_save})
         if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
-    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_fwd_workspace_bytes(dtype, Bt, S, d, H, hd, ph))
+    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_fwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph))
         return SDP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    const bool gathered = mode == SDP_MASK_FORWARD;
     const int T = Bt * S, E = ph * hd;
     const FwdWs w = fwd_ws((char*)ws, d, E);
 
-    rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
-    if (rc != SDP_OK) return rc;
+    if (gathered) {
+        rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
+        if (rc != SDP_OK) return rc;
+    }
 
     GemmDesc pj;
     pj.name = "attn_qkv";
     pj.M = T, pj.N = 3 * E, pj.K = d;
     pj.A = X, pj.lda = d;
-    pj.B = Wqkv, pj.ldb = d, pj.b_gather = w.rows_qkv, pj.b_rows = (int64_t)3 * H * hd;
+    pj.B = Wqkv, pj.ldb = d;
+    if (gathered) pj.b_gather = w.rows_qkv, pj.b_rows = (int64_t)3 * H * hd;
     pj.epilogue = EPI_STORE;
     pj.C = QKV_save, pj.ldc = 3 * E;
     rc = run(pj, s);
@@ -658,7 +670,7 @@ extern "C" int sdp_masked_attn_fwd(int dtype, int Bt, int S, int d, int H, int h
         if (rc != SDP_OK) return rc;
     }
 
-    rc = transpose_rows(2, WoT, d, w.rows_o, E, d, w.WoC, E, "attn_wt_fwd", s);
+    rc = transpose_rows(2, WoT, d, gathered ? w.rows_o : nullptr, E, d, w.WoC, E, "attn_wt_fwd", s);
     if (rc != SDP_OK) return rc;
     GemmDesc op;
     op.name = "attn_out";
@@ -670,11 +682,11 @@ extern "C" int sdp_masked_attn_fwd(int dtype, int Bt, int S, int d, int H, int h
     return run(op, s);
 }
 
-extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* dY,
-                                   const void* Wqkv, const void* WoT, const int32_t* head_idx_k, const void* QKV_save,
-                                   const void* O_save, const float* LSE_save, void* dX, void* dWqkv, void* dWoT,
-                                   int dw_layout, void* ws, size_t ws_bytes, void* stream) {
-    int rc = check(dtype, Bt, S, d, H, hd, ph);
+extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
+                                   const void* dY, const void* Wqkv, const void* WoT, const int32_t* head_idx_k,
+                                   const void* QKV_save, const void* O_save, const float* LSE_save, void* dX, void* dWqkv,
+                                   void* dWoT, int dw_layout, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check(mode, dtype, Bt, S, d, H, hd, ph);
     if (rc != SDP_OK) return rc;
     if (dw_layout != SDP_DW_COMPACT && dw_layout != SDP_DW_SCATTER) return SDP_ERR_INVALID_ARG;
     if (!X || !dY || !Wqkv || !WoT || !head_idx_k || !QKV_save || !O_save || !LSE_save || !dX || !dWqkv || !dWoT)
@@ -682,11 +694,13 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
     for (const void* q : {X, dY, Wqkv, WoT, QKV_save, O_save, (const void*)LSE_save, (const void*)dX, (const void*)dWqkv,
                           (const void*)dWoT})
         if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
-    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_bwd_workspace_bytes(dtype, Bt, S, d, H, hd, ph))
+    if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_bwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph))
         return SDP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    const int T = Bt * S, E = ph * hd;
-    const BwdWs w = bwd_ws((char*)ws, T, d, E, (int64_t)Bt * ph * S);
+    const bool gathered = mode == SDP_MASK_FORWARD;
+    const int hr = heads_run(mode, H, ph);
+    const int T = Bt * S, E = hr * hd, Eh = ph * hd; // width the core runs on, width of the held heads
+    const BwdWs w = bwd_ws((char*)ws, T, d, E, Eh, (int64_t)Bt * hr * S);
 
     rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
     if (rc != SDP_OK) return rc;
@@ -695,7 +709,8 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
     go.name = "attn_dout";
     go.M = T, go.N = E, go.K = d;
     go.A = dY, go.lda = d;
-    go.B = WoT, go.ldb = d, go.b_gather = w.rows_o, go.b_rows = (int64_t)H * hd;
+    go.B = WoT, go.ldb = d;
+    if (gathered) go.b_gather = w.rows_o, go.b_rows = (int64_t)H * hd;
     go.epilogue = EPI_STORE;
     go.C = w.dO, go.ldc = E;
     rc = run(go, s);
@@ -706,10 +721,10 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
     a.o = (const uint16_t*)O_save, a.dO = (const uint16_t*)w.dO, a.ldo = E;
     a.lse = const_cast<float*>(LSE_save), a.delta = w.delta;
     a.dqkv = (uint16_t*)w.dQKV;
-    a.S = S, a.ph = ph;
+    a.S = S, a.ph = hr;
     a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
     const int nblocks = (S + BQ - 1) / BQ;
-    const dim3 grid((nblocks + 1) / 2, ph, Bt);
+    const dim3 grid((nblocks + 1) / 2, hr, Bt);
     {
         ProfileScope ps("attn_core_bwd_dq", s);
         attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a, nblocks);
@@ -730,20 +745,22 @@ extern "C" int sdp_masked_attn_bwd(int dtype, int Bt, int S, int d, int H, int h
                                 {dY, w.dYt, d, ldt, nullptr, T, d}};
     rc = transpose_batch(2, tj, 4, "attn_tr_bwd", s);
     if (rc != SDP_OK) return rc;
-    rc = transpose_rows(2, Wqkv, d, w.rows_qkv, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
+    rc = transpose_rows(2, Wqkv, d, gathered ? w.rows_qkv : nullptr, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
     if (rc != SDP_OK) return rc;
 
-    // the four weight gradients share one shape (E x d, depth T): dWq, dWk, dWv from the three row blocks of
+    // the four weight gradients share one shape (Eh x d, depth T): dWq, dWk, dWv from the three row blocks of
     // dQKV^T against X^T, dWoT from O^T against dY^T; one batched launch fills the CUs four times better than
-    // the four launches would
+    // the four launches would.  Under backward masking the row blocks hold all heads and the contraction reads
+    // the held heads' rows only (row gather on the left operand): the gradient is computed on the mask.
     GemmDesc dw;
     dw.name = "attn_dw";
-    dw.M = E, dw.N = d, dw.K = T;
+    dw.M = Eh, dw.N = d, dw.K = T;
     dw.lda = ldt, dw.ldb = ldt;
+    if (!gathered) dw.a_gather = w.rows_o, dw.a_rows = E;
     dw.epilogue = EPI_STORE;
     dw.ldc = d;
     dw.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_o : nullptr; // rows of the held heads inside each matrix
-    const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : E) * d;
+    const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : Eh) * d;
     dw.nbatch = 4;
     for (int i = 0; i < 3; ++i) {
         dw.Ab[i] = (const uint16_t*)w.dQKVt + (int64_t)i * E * ldt;

@@ -62,7 +62,7 @@ struct Dev {
     int M, N, K;
     const uint16_t *A, *A2, *B, *B2;
     int64_t lda, ldb;
-    const int32_t *bg, *cs;
+    const int32_t *ag, *bg, *cs;
     uint16_t *C, *C2, *C3;
     int64_t ldc;
     const uint16_t *Gin, *Uin;
@@ -195,7 +195,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         const int c = (lane & 7) ^ ((r >> 1) & 7);
         int m = m0 + r;
         m = m < g.M ? m : g.M - 1;
-        a_off[i] = (uint32_t)(((int64_t)m * g.lda + c * 8) * 2);
+        const int64_t arow = g.ag ? g.ag[m] : m;
+        a_off[i] = (uint32_t)((arow * g.lda + c * 8) * 2);
         a_k[i] = c * 8;
     }
 #pragma unroll
@@ -611,7 +612,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     Dev g;
     g.M = d.M, g.N = d.N, g.K = d.K;
     g.A = (const uint16_t*)d.A, g.A2 = (const uint16_t*)d.A2, g.B = (const uint16_t*)d.B, g.B2 = (const uint16_t*)d.B2;
-    g.lda = d.lda, g.ldb = d.ldb, g.bg = d.b_gather, g.cs = d.c_scatter;
+    g.lda = d.lda, g.ldb = d.ldb, g.ag = d.a_gather, g.bg = d.b_gather, g.cs = d.c_scatter;
     g.C = (uint16_t*)d.C, g.C2 = (uint16_t*)d.C2, g.C3 = (uint16_t*)d.C3, g.ldc = d.ldc;
     g.Gin = (const uint16_t*)d.Gin, g.Uin = (const uint16_t*)d.Uin, g.ldg = d.ldg;
     g.Ct = (uint16_t*)d.Ct, g.Ct2 = (uint16_t*)d.Ct2, g.Ct3 = (uint16_t*)d.Ct3, g.ldct = d.ldct;
@@ -740,7 +741,8 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     // 16-byte global chunks, 16-deep MFMA steps, 32-bit byte offsets inside each operand
     if (d.K % 16 || d.lda % 8 || d.ldb % 8 || d.N % 8 || d.ldc % 8) return false;
     if (d.a_km) return false; // depth-major A goes through the transposing pre-pass or the plain kernel
-    if ((int64_t)d.M * d.lda * 2 >= ((int64_t)1 << 32)) return false;
+    if ((d.a_rows > 0 ? d.a_rows : (int64_t)d.M) * d.lda * 2 >= ((int64_t)1 << 32)) return false;
+    if (d.a_gather && (d.a_rows <= 0 || d.epilogue == EPI_DUAL_ACC)) return false;
     if ((d.b_rows > 0 ? d.b_rows : (int64_t)d.N) * d.ldb * 2 >= ((int64_t)1 << 32)) return false;
     if (d.b_gather && d.b_rows <= 0) return false;
     if (d.nbatch > 0) {

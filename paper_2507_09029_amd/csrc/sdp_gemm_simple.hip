@@ -38,6 +38,7 @@ struct Dev {
     int64_t lda, ldb;
     const int32_t *bg, *cs;
     int a_km;
+    const int32_t* ag;
     void *C, *C2, *C3;
     int64_t ldc;
     const void *Gin, *Uin;
@@ -80,7 +81,10 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
                 for (int e = tid; e < BM * BK; e += NT) {
                     const int m = e / BK, k = e % BK;
                     float v = 0.f;
-                    if (m0 + m < g.M && k0 + k < g.K) v = ld<T>(A + (int64_t)(m0 + m) * g.lda + k0 + k);
+                    if (m0 + m < g.M && k0 + k < g.K) {
+                        const int64_t row = g.ag ? g.ag[m0 + m] : (m0 + m);
+                        v = ld<T>(A + row * g.lda + k0 + k);
+                    }
                     As[k][m] = v;
                 }
             } else {
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
 
 template <typename T, int EPI>
 int launch(const GemmDesc& d, hipStream_t s) {
-    Dev g{d.M, d.N, d.K, d.A, d.A2, d.B, d.B2, d.lda, d.ldb, d.b_gather, d.c_scatter, d.a_km,
+    Dev g{d.M, d.N, d.K, d.A, d.A2, d.B, d.B2, d.lda, d.ldb, d.b_gather, d.c_scatter, d.a_km, d.a_gather,
           d.C, d.C2, d.C3, d.ldc, d.Gin, d.Uin, d.ldg, d.Cc, d.Cc2, d.Cc3, d.ldcc, d.cidx, d.pc};
     dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM);
     ProfileScope ps(d.name, s);
@@ -187,6 +191,7 @@ int dispatch(const GemmDesc& d, hipStream_t s) {
 
 int gemm_simple(int dtype, const GemmDesc& d, hipStream_t s) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return SDP_ERR_SHAPE;
+    if (d.a_gather && d.a_km) return SDP_ERR_UNSUPPORTED;
     if ((d.N + BN - 1) / BN > 0x7FFFFFFF || (d.M + BM - 1) / BM > 65535) return SDP_ERR_SHAPE;
     return dtype == SDP_F32 ? dispatch<float>(d, s) : dispatch<uint16_t>(d, s);
 }

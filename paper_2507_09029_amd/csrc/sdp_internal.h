@@ -32,9 +32,10 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- contraction descriptor --------------------------------------------------------------------
 // C[M][N] = sum_k A(m,k) * B(k,n), fp32 accumulation, all matrices row-major.
-//   A(m,k) = a_km ? A[k * lda + m] : A[m * lda + k]      (a_km: A is stored depth-major, [K][M])
+//   A(m,k) = a_km ? A[k * lda + m] : A[ra(m) * lda + k]  (a_km: A is stored depth-major, [K][M])
 //   B(k,n) = B[rb(n) * ldb + k]                           (B is stored [N][K], rows contiguous along k)
-// rb is the identity when b_gather is null, else a lookup in an int32 table (active-neuron rows).
+// rb is the identity when b_gather is null, else a lookup in an int32 table (active-neuron rows); ra likewise
+// with a_gather (not together with a_km).
 // A second operand pair (A2, B2) with the same shapes and strides is used by two of the epilogues.
 enum Epilogue {
     EPI_STORE = 0,       // C[rc(m) * ldc + n] = acc                      (rc: optional row scatter)
@@ -54,6 +55,8 @@ struct GemmDesc {
     const void* A2 = nullptr;
     int64_t lda = 0;
     int a_km = 0;
+    const int32_t* a_gather = nullptr;
+    int64_t a_rows = 0; // number of rows of the stored A (bounds the gathered row index); 0 = M
     const void* B = nullptr;
     const void* B2 = nullptr;
     int64_t ldb = 0;

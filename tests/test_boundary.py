@@ -150,26 +150,33 @@ def test_attention_arguments_are_checked_on_the_host():
 
     L = sdp.lib()
     big = ctypes.c_size_t(1 << 40)
-    BF16, F32 = 1, 0
+    BF16, F32, FM, BM = 1, 0, 0, 1
     assert sdp.binding._DTYPES[torch.bfloat16] == BF16 and sdp.binding._DTYPES[torch.float32] == F32
-    ws = sdp.masked_attn_fwd_workspace_bytes(torch.bfloat16, 4, 2048, 1536, 24, 64, 12)
+    assert sdp.binding._MODES["fm"] == FM and sdp.binding._MODES["bm"] == BM
+    ws = sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 64, 12)
     assert ws >= 4 * 768 * 4 + 1536 * 768 * 2
-    wb = sdp.masked_attn_bwd_workspace_bytes(torch.bfloat16, 4, 2048, 1536, 24, 64, 12)
+    wb = sdp.masked_attn_bwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 64, 12)
     assert wb >= 8192 * 768 * 2 * (1 + 3 + 3 + 1) + 2 * 1536 * 8192 * 2
-    assert sdp.masked_attn_fwd_workspace_bytes(torch.float32, 4, 2048, 1536, 24, 64, 12) == 0  # bf16 only
-    assert sdp.masked_attn_fwd_workspace_bytes(torch.bfloat16, 4, 2048, 1536, 24, 50, 12) == 0  # head width 64 only
-    assert sdp.masked_attn_bwd_workspace_bytes(torch.bfloat16, 4, 2048, 1532, 24, 64, 12) == 0  # d % 8
+    # backward masking runs the core on all 24 heads: twice the activations of 12 held heads
+    assert sdp.masked_attn_bwd_workspace_bytes("bm", torch.bfloat16, 4, 2048, 1536, 24, 64, 12) >= 8192 * 1536 * 2 * (1 + 3 + 3 + 1)
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.float32, 4, 2048, 1536, 24, 64, 12) == 0  # bf16 only
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 50, 12) == 0  # head width 64 only
+    assert sdp.masked_attn_bwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1532, 24, 64, 12) == 0  # d % 8
     fwd = lambda *a: L.sdp_masked_attn_fwd(*a)
-    args = [BF16, 2, 128, 128, 4, 64, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, big, None]
+    # mode, dtype, Bt, S, d, H, hd, ph, then X, Wqkv, WoT, head_idx, Y, QKV, O, LSE, ws, ws_bytes, stream
+    args = [FM, BF16, 2, 128, 128, 4, 64, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, big, None]
     unsupported, invalid, shape, workspace = -5, -1, -2, -3
-    assert fwd(*([F32] + args[1:])) == unsupported
-    assert fwd(*(args[:5] + [32] + args[6:])) == unsupported
-    assert fwd(*(args[:6] + [5] + args[7:])) == shape          # more held heads than heads
-    assert fwd(*(args[:1] + [0] + args[2:])) == invalid        # no sequence
-    assert fwd(*(args[:7] + [None] + args[8:])) == invalid     # X missing
-    assert fwd(*(args[:7] + [ctypes.c_void_p(0x1004)] + args[8:])) == invalid  # misaligned
-    assert fwd(*(args[:16] + [ctypes.c_size_t(16), None])) == workspace
-    bargs = [BF16, 2, 128, 128, 4, 64, 2] + [FAKE] * 11 + [0, FAKE, big, None]
-    assert L.sdp_masked_attn_bwd(*(bargs[:18] + [7] + bargs[19:])) == invalid   # unknown gradient layout
-    assert L.sdp_masked_attn_bwd(*(bargs[:19] + [None, big, None])) == workspace
-    assert L.sdp_masked_attn_bwd(*([F32] + bargs[1:])) == unsupported
+    assert fwd(*([2] + args[1:])) == invalid                   # unknown regime
+    assert fwd(*(args[:1] + [F32] + args[2:])) == unsupported
+    assert fwd(*(args[:6] + [32] + args[7:])) == unsupported
+    assert fwd(*(args[:7] + [5] + args[8:])) == shape          # more held heads than heads
+    assert fwd(*(args[:2] + [0] + args[3:])) == invalid        # no sequence
+    assert fwd(*(args[:8] + [None] + args[9:])) == invalid     # X missing
+    assert fwd(*(args[:11] + [None] + args[12:])) == invalid   # forward masking needs the head list
+    assert fwd(*(args[:8] + [ctypes.c_void_p(0x1004)] + args[9:])) == invalid  # misaligned
+    assert fwd(*(args[:17] + [ctypes.c_size_t(16), None])) == workspace
+    bargs = [FM, BF16, 2, 128, 128, 4, 64, 2] + [FAKE] * 11 + [0, FAKE, big, None]
+    assert L.sdp_masked_attn_bwd(*(bargs[:19] + [7] + bargs[20:])) == invalid   # unknown gradient layout
+    assert L.sdp_masked_attn_bwd(*(bargs[:20] + [None, big, None])) == workspace
+    assert L.sdp_masked_attn_bwd(*(bargs[:1] + [F32] + bargs[2:])) == unsupported
+    assert L.sdp_masked_attn_bwd(*([BM] + bargs[1:12] + [None] + bargs[13:])) == invalid  # the held heads are needed

@@ -36,7 +36,7 @@ def held_rows(heads, hd):
     return np.concatenate([np.arange(h * hd, (h + 1) * hd) for h in heads])
 
 
-def run_case(sdp, orc, w, workers, dw_layout="compact"):
+def run_case(sdp, orc, w, workers, dw_layout="compact", mode="fm"):
     Wqkv, WoT = workloads.attn_weights(w)
     dWqkv, dWoT = Wqkv.cuda(), WoT.cuda()
     mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
@@ -45,22 +45,24 @@ def run_case(sdp, orc, w, workers, dw_layout="compact"):
     W64 = [workloads.to_f64(Wqkv[i]) for i in range(3)] + [workloads.to_f64(WoT)]
     E_all = w.H * w.hd
     for k in workers:
-        print(f"  {w.name} worker {k} Bt={w.Bt} S={w.S} d={w.d} H={w.H} ph={w.ph} {dw_layout}", flush=True)
+        print(f"  {w.name} worker {k} {mode} Bt={w.Bt} S={w.S} d={w.d} H={w.H} ph={w.ph} {dw_layout}", flush=True)
         X, dY = workloads.attn_batch(w, k)
         heads = np.flatnonzero(want_mask[k])
         assert (idx[k].cpu().numpy() == heads).all()
-        Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), dWqkv, dWoT, idx[k])
+        Y, QKV, O, LSE = sdp.masked_attn_fwd(mode, w.Bt, w.S, w.hd, X.cuda(), dWqkv, dWoT, idx[k])
         out = None
         if dw_layout == "scatter":
             out = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"),
                    torch.full((3, E_all, w.d), float("nan"), dtype=X.dtype, device="cuda"),
                    torch.full((E_all, w.d), float("nan"), dtype=X.dtype, device="cuda"))
-        dX, gWqkv, gWoT = sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), dWqkv, dWoT, idx[k], QKV, O, LSE,
+        dX, gWqkv, gWoT = sdp.masked_attn_bwd(mode, w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), dWqkv, dWoT, idx[k], QKV, O, LSE,
                                               dw_layout=dw_layout, out=out)
         torch.cuda.synchronize()
-        ref = orc.attn_worker_step(w.Bt, w.S, w.hd, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64)
+        ref = orc.attn_worker_step(w.Bt, w.S, w.hd, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64, mode=mode)
         assert ref["nonzero_off_mask"] == 0
-        rows = held_rows(heads, w.hd)
+        held = held_rows(heads, w.hd)
+        # heads the forward pass and the core ran on: the held ones, or all of them under backward masking
+        rows = held if mode == "fm" else np.arange(E_all)
         E = rows.size
         # per-token tensors: one scale per row (a token's output averages over all earlier tokens, so the row
         # norms fall with the position); weight gradients: one scale per tensor
@@ -81,9 +83,10 @@ def run_case(sdp, orc, w, workers, dw_layout="compact"):
         g = workloads.to_f64(gWqkv)
         go = workloads.to_f64(gWoT)
         if dw_layout == "scatter":
-            off = np.setdiff1d(np.arange(E_all), rows)
+            off = np.setdiff1d(np.arange(E_all), held)
             assert np.isnan(g[:, off]).all() and np.isnan(go[off]).all(), "rows of heads not held must stay untouched"
-            g, go = g[:, rows], go[rows]
+            g, go = g[:, held], go[held]
+        rows = held  # weight gradients exist for the held heads only, in both regimes
         for i, name in enumerate(("dWq", "dWk", "dWv")):
             if w.S == 1 and i < 2:
                 # a softmax over one key is constant: the exact gradient is zero, and what is left of the
@@ -113,6 +116,16 @@ def test_attention_all_outputs(sdp, orc, w):
 
 def test_scatter_layout_leaves_other_heads_alone(sdp, orc):
     run_case(sdp, orc, CASES[2], [1], dw_layout="scatter")
+    run_case(sdp, orc, CASES[5], [0], dw_layout="scatter", mode="bm")
+
+
+BM_CASES = [CASES[0], CASES[2], CASES[3], CASES[4], CASES[5], CASES[6]]
+
+
+@pytest.mark.parametrize("w", BM_CASES, ids=[w.name for w in BM_CASES])
+def test_attention_backward_masking_all_outputs(sdp, orc, w):
+    """Dense forward and dX, weight gradients on the held heads only."""
+    run_case(sdp, orc, w, range(min(w.K, 2)), mode="bm")
 
 
 def test_argument_errors(sdp):
@@ -121,11 +134,11 @@ def test_argument_errors(sdp):
     X, _ = workloads.attn_batch(w, 0)
     idx = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
     with pytest.raises(sdp.SdpError):  # fp32 is not built for the attention block
-        sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.float().cuda(), Wqkv.float(), WoT.float(), idx)
+        sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X.float().cuda(), Wqkv.float(), WoT.float(), idx)
     with pytest.raises(sdp.SdpError):  # head width other than 64
-        sdp.masked_attn_fwd(w.Bt, w.S, 32, X.cuda(), Wqkv, WoT, idx)
+        sdp.masked_attn_fwd("fm", w.Bt, w.S, 32, X.cuda(), Wqkv, WoT, idx)
     with pytest.raises(sdp.SdpError):  # more held heads than heads
-        sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), Wqkv, WoT, torch.arange(5, dtype=torch.int32, device="cuda"))
+        sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X.cuda(), Wqkv, WoT, torch.arange(5, dtype=torch.int32, device="cuda"))
 
 
 def test_attention_full_step_average(sdp, orc):
@@ -145,9 +158,9 @@ def test_attention_full_step_average(sdp, orc):
     refs = []
     for k in range(w.K):
         X, dY = workloads.attn_batch(w, k)
-        Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), dWqkv, dWoT, idx[k])
+        Y, QKV, O, LSE = sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X.cuda(), dWqkv, dWoT, idx[k])
         out = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), bufs[k][: 3 * E_all].view(3, E_all, w.d), bufs[k][3 * E_all:])
-        sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), dWqkv, dWoT, idx[k], QKV, O, LSE, dw_layout="scatter", out=out)
+        sdp.masked_attn_bwd("fm", w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), dWqkv, dWoT, idx[k], QKV, O, LSE, dw_layout="scatter", out=out)
         r = orc.attn_worker_step(w.Bt, w.S, w.hd, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64)
         refs.append(np.concatenate([r["dWq"], r["dWk"], r["dWv"], r["dWoT"]]))
     # head h owns rows h hd .. of each of the four matrices

@@ -170,8 +170,8 @@ def test_attention_500M_one_sequence_and_sampled_gradient_rows(sdp, orc):
     E = rows.size
     X, dY = workloads.attn_batch(w, k)
     print(f"  {w.name} worker {k}: GPU forward + backward", flush=True)
-    Y, QKV, O, LSE = sdp.masked_attn_fwd(w.Bt, w.S, w.hd, X.cuda(), Wqkv.cuda(), WoT.cuda(), idx[k])
-    dX, gWqkv, gWoT = sdp.masked_attn_bwd(w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), Wqkv.cuda(), WoT.cuda(), idx[k], QKV, O, LSE)
+    Y, QKV, O, LSE = sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X.cuda(), Wqkv.cuda(), WoT.cuda(), idx[k])
+    dX, gWqkv, gWoT = sdp.masked_attn_bwd("fm", w.Bt, w.S, w.hd, X.cuda(), dY.cuda(), Wqkv.cuda(), WoT.cuda(), idx[k], QKV, O, LSE)
     torch.cuda.synchronize()
     Wc = [workloads.to_f64(Wqkv[i])[rows] for i in range(3)] + [workloads.to_f64(WoT)[rows]]
     X64, dY64 = workloads.to_f64(X), workloads.to_f64(dY)
