@@ -645,12 +645,10 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na * ksplit, nbo * ksplit, BM, BN);
     if (const char* e = getenv("SDP_GROUP_M")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
     auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, OP>;
-    static bool attr_set = false; // one flag per instantiation
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
-            return SDP_ERR_HIP;
-        attr_set = true;
-    }
+    // once per instantiation (initialisation of a function-local static is thread-safe)
+    static const hipError_t attr =
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (attr != hipSuccess) return SDP_ERR_HIP;
     ProfileScope ps(d.name, s);
     kern<<<dim3((unsigned)(ntiles * nbatch)), NTHREADS, LDS, s>>>(g);
     return launch_status();
