@@ -63,6 +63,22 @@ bool profiling_wants(const char* name) {
     return g_filter.empty() || g_filter == name;
 }
 
+// For launches that carry their own start / stop events (hipExtLaunchKernel): hands out the pair and files it
+// with the pending launches; false when this kernel is not being timed.
+bool profile_launch_events(const char* name, hipEvent_t* start, hipEvent_t* stop) {
+    if (!profiling_on() || !profiling_wants(name)) return false;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Pending p{name, take_event(), take_event()};
+    if (!p.start || !p.stop) {
+        if (p.start) g_free.push_back(p.start);
+        if (p.stop) g_free.push_back(p.stop);
+        return false;
+    }
+    g_pending.push_back(p);
+    *start = p.start, *stop = p.stop;
+    return true;
+}
+
 void profile_begin(const char* name, hipStream_t s) {
     std::lock_guard<std::mutex> lk(g_mu);
     Pending p{name, take_event(), take_event()};

@@ -38,6 +38,8 @@
 #include "sdp_internal.h"
 #include "sdp_swiglu.h"
 
+#include <hip/hip_ext.h>
+
 #include <cstdlib>
 #include <type_traits>
 
@@ -649,8 +651,14 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     static const hipError_t attr =
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return SDP_ERR_HIP;
-    ProfileScope ps(d.name, s);
-    kern<<<dim3((unsigned)(ntiles * nbatch)), NTHREADS, LDS, s>>>(g);
+    // When this kernel is being timed, the launch itself carries the two events (their timestamps are the
+    // kernel's own begin and end): events recorded around the launch would put a bubble of several
+    // microseconds on either side of it.
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (profile_launch_events(d.name, &ev0, &ev1))
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)(ntiles * nbatch)), dim3(NTHREADS), (uint32_t)LDS, s, ev0, ev1, 0u, g);
+    else
+        kern<<<dim3((unsigned)(ntiles * nbatch)), NTHREADS, LDS, s>>>(g);
     return launch_status();
 }
 

@@ -11,6 +11,8 @@ namespace sdp {
 bool profiling_on();
 bool profiling_wants(const char* name); // on, and `name` passes the filter
 void profile_begin(const char* name, hipStream_t s);
+// start / stop events for a launch that records them itself (hipExtLaunchKernel); false = not timed
+bool profile_launch_events(const char* name, hipEvent_t* start, hipEvent_t* stop);
 void profile_end(hipStream_t s);
 
 struct ProfileScope {
