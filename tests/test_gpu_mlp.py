@@ -120,3 +120,26 @@ def test_config1_full_step_average(sdp, orc):
     want, wc = orc.gated_average(ref_bufs, np.tile(want_mask, (1, 3)))
     assert (c.cpu().numpy() == wc).all() and wc.min() >= 1
     assert_close(avg.cpu().numpy(), want, 1e-5, "averaged gradient")
+
+
+@pytest.mark.parametrize("mode", ["fm", "bm"])
+def test_fp32_path_and_bf16_path_agree_on_the_same_inputs(sdp, mode):
+    """The same bf16-valued inputs through the fp32 kernels (plain FMA contractions, no intermediate rounding) and
+    through the bf16 MFMA kernels: two implementations inside the library that share no contraction code must
+    agree to the bf16 path's rounding (about 1e-2), without the oracle in between."""
+    from helpers import err_report
+
+    w = MlpWorkload("paths", "bf16", 512, 256, 1024, 512, 2, mode, 61)
+    W = workloads.mlp_weights(w)
+    X, dY = workloads.mlp_batch(w, 0)
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.F, w.p, w.mask_seed, True)
+    outs = {}
+    for name, conv in (("bf16", lambda t: t.cuda()), ("f32", lambda t: t.float().cuda())):
+        Wd = [conv(t) for t in W]
+        Y, G, U = sdp.masked_mlp_fwd(mode, conv(X), *Wd, idx[0])
+        dX, dW1, dW3, dW2T = sdp.masked_mlp_bwd(mode, conv(X), conv(dY), *Wd, idx[0], G, U)
+        torch.cuda.synchronize()
+        outs[name] = [workloads.to_f64(t) for t in (Y, G, U, dX, dW1, dW3, dW2T)]
+    for got, ref, what in zip(outs["bf16"], outs["f32"], ("Y", "G", "U", "dX", "dW1", "dW3", "dW2T")):
+        elem, norm = err_report(got, ref)
+        assert norm <= 1e-2 and elem <= 2e-2, f"{what}: elementwise {elem:.3e}, normwise {norm:.3e}"
