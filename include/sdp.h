@@ -163,8 +163,9 @@ int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int p, const vo
  *   O_save [T][n hd] out;  LSE_save [Bt][n][S] fp32 out: log2 of the softmax denominators, logits in
  *   base 2 -- kept for sdp_masked_attn_bwd.
  *   ws: sdp_masked_attn_fwd_workspace_bytes(...).
- * Limits: dtype SDP_BF16 and hd = 64 only (else UNSUPPORTED); d a multiple of 8; Bt, H <= 65535;
- * pointers 16-byte aligned.  Errors as for the MLP calls.
+ * Limits: hd <= 128 (else UNSUPPORTED); for SDP_BF16 d and hd multiples of 8 (16-byte rows); Bt, H <= 65535;
+ * pointers 16-byte aligned.  bf16 with hd = 64 runs the MFMA attention core; fp32, and bf16 with any other
+ * head width, run a plain fp32-arithmetic core.  Errors as for the MLP calls.
  * ------------------------------------------------------------------------------------------- */
 size_t sdp_masked_attn_fwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph);
 int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,

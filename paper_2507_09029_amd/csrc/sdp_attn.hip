@@ -535,16 +535,21 @@ __global__ void head_rows_kernel(const int32_t* __restrict__ head_idx, int ph, i
 
 int64_t ld_tokens(int64_t T) { return T + 64; } // see the MLP path: rows must not sit a power of two apart
 
+// the MFMA core takes bf16 with head width 64; everything else goes through the plain core
+bool mfma_core(int dtype, int hd) { return dtype == SDP_BF16 && hd == HD; }
+size_t esize(int dtype) { return dtype == SDP_F32 ? 4 : 2; }
+
 int check(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (mode != SDP_MASK_FORWARD && mode != SDP_MASK_BACKWARD) return SDP_ERR_INVALID_ARG;
-    if (dtype != SDP_BF16) return SDP_ERR_UNSUPPORTED;
-    if (Bt < 1 || S < 1 || d < 1 || H < 1) return SDP_ERR_INVALID_ARG;
-    if (hd != HD) return SDP_ERR_UNSUPPORTED;
+    if (dtype != SDP_BF16 && dtype != SDP_F32) return SDP_ERR_INVALID_ARG;
+    if (Bt < 1 || S < 1 || d < 1 || H < 1 || hd < 1) return SDP_ERR_INVALID_ARG;
+    if (hd > 128) return SDP_ERR_UNSUPPORTED;
     if (ph < 1 || ph > H) return SDP_ERR_SHAPE;
-    if (d % 8) return SDP_ERR_SHAPE;
+    if (dtype == SDP_BF16 && (d % 8 || hd % 8)) return SDP_ERR_SHAPE; // 16-byte rows
     if (Bt > 65535 || H > 65535) return SDP_ERR_SHAPE;
     if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)Bt * S * 3 * H * hd >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
-    if ((int64_t)S * 3 * H * hd * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE; // 32-bit byte offsets inside a sequence
+    // MFMA core: 32-bit byte offsets inside a sequence
+    if (mfma_core(dtype, hd) && (int64_t)S * 3 * H * hd * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE;
     return SDP_OK;
 }
 
@@ -556,13 +561,13 @@ struct FwdWs {
     void* WoC;
     size_t bytes;
 };
-FwdWs fwd_ws(char* w, int d, int E) {
+FwdWs fwd_ws(char* w, size_t e, int d, int E) {
     FwdWs r;
     size_t off = 0;
     auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
     r.rows_qkv = (int32_t*)take((size_t)3 * E * 4);
     r.rows_o = (int32_t*)take((size_t)E * 4);
-    r.WoC = take((size_t)d * E * 2);
+    r.WoC = take((size_t)d * E * e);
     r.bytes = off;
     return r;
 }
@@ -574,29 +579,29 @@ struct BwdWs {
     size_t bytes;
 };
 // E = width the core runs on, Eh = width of the held heads (equal under forward masking)
-BwdWs bwd_ws(char* w, int64_t T, int d, int E, int Eh, int64_t stats) {
+BwdWs bwd_ws(char* w, size_t e, int64_t T, int d, int E, int Eh, int64_t stats) {
     BwdWs r;
     size_t off = 0;
     auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
     r.rows_qkv = (int32_t*)take((size_t)3 * Eh * 4);
     r.rows_o = (int32_t*)take((size_t)Eh * 4);
-    r.dO = take((size_t)T * E * 2);
-    r.dQKV = take((size_t)T * 3 * E * 2);
+    r.dO = take((size_t)T * E * e);
+    r.dQKV = take((size_t)T * 3 * E * e);
     r.delta = (float*)take((size_t)stats * 4);
-    r.dQKVt = take((size_t)3 * E * ld_tokens(T) * 2);
-    r.Ot = take((size_t)E * ld_tokens(T) * 2);
-    r.Xt = take((size_t)d * ld_tokens(T) * 2);
-    r.dYt = take((size_t)d * ld_tokens(T) * 2);
-    r.Wc = take((size_t)d * 3 * E * 2);
-    const size_t sp = gemm_split_ws_bytes(Eh, d, (int)T, 4); // partial sums of the batched weight-gradient launch
+    r.dQKVt = take((size_t)3 * E * ld_tokens(T) * e);
+    r.Ot = take((size_t)E * ld_tokens(T) * e);
+    r.Xt = take((size_t)d * ld_tokens(T) * e);
+    r.dYt = take((size_t)d * ld_tokens(T) * e);
+    r.Wc = take((size_t)d * 3 * E * e);
+    const size_t sp = e == 2 ? gemm_split_ws_bytes(Eh, d, (int)T, 4) : 0; // partial sums of the batched weight-gradient launch
     r.split = sp ? take(sp) : nullptr;
     r.bytes = off;
     return r;
 }
 
-int run(const GemmDesc& g, hipStream_t s) {
-    if (gemm_mfma_supported(g)) return gemm_mfma_bf16(g, s);
-    return gemm_simple(SDP_BF16, g, s);
+int run(int dtype, const GemmDesc& g, hipStream_t s) {
+    if (dtype == SDP_BF16 && gemm_mfma_supported(g)) return gemm_mfma_bf16(g, s);
+    return gemm_simple(dtype, g, s);
 }
 
 int head_rows(const int32_t* head_idx, int ph, int H, int hd, int32_t* rows_qkv, int32_t* rows_o, hipStream_t s) {
@@ -613,13 +618,13 @@ using namespace sdp;
 
 extern "C" size_t sdp_masked_attn_fwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (check(mode, dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
-    return fwd_ws(nullptr, d, heads_run(mode, H, ph) * hd).bytes;
+    return fwd_ws(nullptr, esize(dtype), d, heads_run(mode, H, ph) * hd).bytes;
 }
 
 extern "C" size_t sdp_masked_attn_bwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (check(mode, dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
     const int hr = heads_run(mode, H, ph);
-    return bwd_ws(nullptr, (int64_t)Bt * S, d, hr * hd, ph * hd, (int64_t)Bt * hr * S).bytes;
+    return bwd_ws(nullptr, esize(dtype), (int64_t)Bt * S, d, hr * hd, ph * hd, (int64_t)Bt * hr * S).bytes;
 }
 
 extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
@@ -637,7 +642,7 @@ extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, in
     hipStream_t s = (hipStream_t)stream;
     const bool gathered = mode == SDP_MASK_FORWARD;
     const int T = Bt * S, E = ph * hd;
-    const FwdWs w = fwd_ws((char*)ws, d, E);
+    const FwdWs w = fwd_ws((char*)ws, esize(dtype), d, E);
 
     if (gathered) {
         rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
@@ -652,25 +657,30 @@ extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, in
     if (gathered) pj.b_gather = w.rows_qkv, pj.b_rows = (int64_t)3 * H * hd;
     pj.epilogue = EPI_STORE;
     pj.C = QKV_save, pj.ldc = 3 * E;
-    rc = run(pj, s);
+    rc = run(dtype, pj, s);
     if (rc != SDP_OK) return rc;
 
-    CoreArgs a{};
-    a.qkv = (const uint16_t*)QKV_save, a.ldq = 3 * E;
-    a.o_out = (uint16_t*)O_save, a.ldo = E;
-    a.lse = LSE_save;
-    a.S = S, a.ph = ph;
-    a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
-    {
+    if (mfma_core(dtype, hd)) {
+        CoreArgs a{};
+        a.qkv = (const uint16_t*)QKV_save, a.ldq = 3 * E;
+        a.o_out = (uint16_t*)O_save, a.ldo = E;
+        a.lse = LSE_save;
+        a.S = S, a.ph = ph;
+        a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
         ProfileScope ps("attn_core_fwd", s);
         constexpr int QF = SDP_ATTN_FWD_QF, NW = SDP_ATTN_FWD_NW, ROWS = 32 * QF * NW;
         const int nblocks = (S + ROWS - 1) / ROWS;
         attn_fwd_kernel<QF, NW><<<dim3((nblocks + 1) / 2, ph, Bt), 64 * NW, 0, s>>>(a, nblocks);
         rc = launch_status();
-        if (rc != SDP_OK) return rc;
+    } else {
+        AttnCoreDesc c;
+        c.qkv = QKV_save, c.ldq = 3 * E, c.o_out = O_save, c.ldo = E, c.lse = LSE_save;
+        c.Bt = Bt, c.S = S, c.n = ph, c.hd = hd;
+        rc = attn_plain_fwd(dtype, c, s);
     }
+    if (rc != SDP_OK) return rc;
 
-    rc = transpose_rows(2, WoT, d, gathered ? w.rows_o : nullptr, E, d, w.WoC, E, "attn_wt_fwd", s);
+    rc = transpose_rows((int)esize(dtype), WoT, d, gathered ? w.rows_o : nullptr, E, d, w.WoC, E, "attn_wt_fwd", s);
     if (rc != SDP_OK) return rc;
     GemmDesc op;
     op.name = "attn_out";
@@ -679,7 +689,7 @@ extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, in
     op.B = w.WoC, op.ldb = E;
     op.epilogue = EPI_STORE;
     op.C = Y, op.ldc = d;
-    return run(op, s);
+    return run(dtype, op, s);
 }
 
 extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
@@ -700,7 +710,7 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
     const bool gathered = mode == SDP_MASK_FORWARD;
     const int hr = heads_run(mode, H, ph);
     const int T = Bt * S, E = hr * hd, Eh = ph * hd; // width the core runs on, width of the held heads
-    const BwdWs w = bwd_ws((char*)ws, T, d, E, Eh, (int64_t)Bt * hr * S);
+    const BwdWs w = bwd_ws((char*)ws, esize(dtype), T, d, E, Eh, (int64_t)Bt * hr * S);
 
     rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
     if (rc != SDP_OK) return rc;
@@ -713,28 +723,37 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
     if (gathered) go.b_gather = w.rows_o, go.b_rows = (int64_t)H * hd;
     go.epilogue = EPI_STORE;
     go.C = w.dO, go.ldc = E;
-    rc = run(go, s);
+    rc = run(dtype, go, s);
     if (rc != SDP_OK) return rc;
 
-    CoreArgs a{};
-    a.qkv = (const uint16_t*)QKV_save, a.ldq = 3 * E;
-    a.o = (const uint16_t*)O_save, a.dO = (const uint16_t*)w.dO, a.ldo = E;
-    a.lse = const_cast<float*>(LSE_save), a.delta = w.delta;
-    a.dqkv = (uint16_t*)w.dQKV;
-    a.S = S, a.ph = hr;
-    a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
-    const int nblocks = (S + BQ - 1) / BQ;
-    const dim3 grid((nblocks + 1) / 2, hr, Bt);
-    {
-        ProfileScope ps("attn_core_bwd_dq", s);
-        attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a, nblocks);
-        rc = launch_status();
-        if (rc != SDP_OK) return rc;
-    }
-    {
-        ProfileScope ps("attn_core_bwd_dkv", s); // reads the delta written by the dQ kernel
-        attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a, nblocks);
-        rc = launch_status();
+    if (mfma_core(dtype, hd)) {
+        CoreArgs a{};
+        a.qkv = (const uint16_t*)QKV_save, a.ldq = 3 * E;
+        a.o = (const uint16_t*)O_save, a.dO = (const uint16_t*)w.dO, a.ldo = E;
+        a.lse = const_cast<float*>(LSE_save), a.delta = w.delta;
+        a.dqkv = (uint16_t*)w.dQKV;
+        a.S = S, a.ph = hr;
+        a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
+        const int nblocks = (S + BQ - 1) / BQ;
+        const dim3 grid((nblocks + 1) / 2, hr, Bt);
+        {
+            ProfileScope ps("attn_core_bwd_dq", s);
+            attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a, nblocks);
+            rc = launch_status();
+            if (rc != SDP_OK) return rc;
+        }
+        {
+            ProfileScope ps("attn_core_bwd_dkv", s); // reads the delta written by the dQ kernel
+            attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a, nblocks);
+            rc = launch_status();
+            if (rc != SDP_OK) return rc;
+        }
+    } else {
+        AttnCoreDesc c;
+        c.qkv = QKV_save, c.ldq = 3 * E, c.o = O_save, c.dO = w.dO, c.ldo = E;
+        c.lse = const_cast<float*>(LSE_save), c.delta = w.delta, c.dqkv = w.dQKV;
+        c.Bt = Bt, c.S = S, c.n = hr, c.hd = hd;
+        rc = attn_plain_bwd(dtype, c, s);
         if (rc != SDP_OK) return rc;
     }
 
@@ -743,9 +762,9 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
                                 {O_save, w.Ot, E, ldt, nullptr, T, E},
                                 {X, w.Xt, d, ldt, nullptr, T, d},
                                 {dY, w.dYt, d, ldt, nullptr, T, d}};
-    rc = transpose_batch(2, tj, 4, "attn_tr_bwd", s);
+    rc = transpose_batch((int)esize(dtype), tj, 4, "attn_tr_bwd", s);
     if (rc != SDP_OK) return rc;
-    rc = transpose_rows(2, Wqkv, d, gathered ? w.rows_qkv : nullptr, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
+    rc = transpose_rows((int)esize(dtype), Wqkv, d, gathered ? w.rows_qkv : nullptr, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
     if (rc != SDP_OK) return rc;
 
     // the four weight gradients share one shape (Eh x d, depth T): dWq, dWk, dWv from the three row blocks of
@@ -762,21 +781,22 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
     dw.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_o : nullptr; // rows of the held heads inside each matrix
     const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : Eh) * d;
     dw.nbatch = 4;
+    const size_t e = esize(dtype);
     for (int i = 0; i < 3; ++i) {
-        dw.Ab[i] = (const uint16_t*)w.dQKVt + (int64_t)i * E * ldt;
+        dw.Ab[i] = (const char*)w.dQKVt + (size_t)i * E * ldt * e;
         dw.Bb[i] = w.Xt;
-        dw.Cb[i] = (uint16_t*)dWqkv + i * part;
+        dw.Cb[i] = (char*)dWqkv + (size_t)i * part * e;
     }
     dw.Ab[3] = w.Ot, dw.Bb[3] = w.dYt, dw.Cb[3] = dWoT;
     dw.split_ws = w.split;
-    if (gemm_mfma_supported(dw)) {
+    if (dtype == SDP_BF16 && gemm_mfma_supported(dw)) {
         rc = gemm_mfma_bf16(dw, s);
         if (rc != SDP_OK) return rc;
     } else {
         dw.nbatch = 0;
         for (int i = 0; i < 4; ++i) {
             dw.A = dw.Ab[i], dw.B = dw.Bb[i], dw.C = dw.Cb[i];
-            rc = gemm_simple(SDP_BF16, dw, s);
+            rc = gemm_simple(dtype, dw, s);
             if (rc != SDP_OK) return rc;
         }
     }
@@ -788,5 +808,5 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
     dx.B = w.Wc, dx.ldb = 3 * E;
     dx.epilogue = EPI_STORE;
     dx.C = dX, dx.ldc = d;
-    return run(dx, s);
+    return run(dtype, dx, s);
 }

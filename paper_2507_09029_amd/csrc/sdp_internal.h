@@ -115,6 +115,26 @@ bool gemm_mfma_supported(const GemmDesc& g);
 int gemm_choose_ksplit(int M, int N, int K, int nbatch);
 size_t gemm_split_ws_bytes(int M, int N, int K, int nbatch);
 
+// ---- attention core -----------------------------------------------------------------------------
+// Causal attention of n heads of width hd over Bt sequences of S tokens, on the saved projections:
+// qkv [Bt S][ldq] = Q | K | V (head i at columns i hd of each part), o / dO [Bt S][ldo], lse / delta [Bt][n][S].
+struct AttnCoreDesc {
+    const void* qkv = nullptr;
+    int64_t ldq = 0;
+    const void* o = nullptr; // backward: the forward's output
+    void* o_out = nullptr;   // forward
+    const void* dO = nullptr;
+    int64_t ldo = 0;
+    float* lse = nullptr;
+    float* delta = nullptr;
+    void* dqkv = nullptr;
+    int Bt = 0, S = 0, n = 0, hd = 0;
+};
+// plain core: fp32 or bf16 storage, fp32 arithmetic, hd <= 128 (SDP_ERR_UNSUPPORTED beyond)
+bool attn_plain_supported(const AttnCoreDesc& c);
+int attn_plain_fwd(int dtype, const AttnCoreDesc& c, hipStream_t s);
+int attn_plain_bwd(int dtype, const AttnCoreDesc& c, hipStream_t s);
+
 // out[c][r] = in[rows ? rows[r] : r][c] for r < R, c < C: (gathered) transpose, element size 2 or 4.
 int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t* rows, int R, int C, void* out,
                    int64_t ld_out, const char* name, hipStream_t s);

@@ -159,16 +159,19 @@ def test_attention_arguments_are_checked_on_the_host():
     assert wb >= 8192 * 768 * 2 * (1 + 3 + 3 + 1) + 2 * 1536 * 8192 * 2
     # backward masking runs the core on all 24 heads: twice the activations of 12 held heads
     assert sdp.masked_attn_bwd_workspace_bytes("bm", torch.bfloat16, 4, 2048, 1536, 24, 64, 12) >= 8192 * 1536 * 2 * (1 + 3 + 3 + 1)
-    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.float32, 4, 2048, 1536, 24, 64, 12) == 0  # bf16 only
-    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 50, 12) == 0  # head width 64 only
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.float32, 4, 2048, 1536, 24, 64, 12) > ws   # fp32 elements
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.float32, 4, 1024, 1200, 24, 50, 12) > 0    # the paper's head width
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 50, 12) == 0  # bf16: 16-byte rows
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 136, 12) == 0  # wider than 128
     assert sdp.masked_attn_bwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1532, 24, 64, 12) == 0  # d % 8
     fwd = lambda *a: L.sdp_masked_attn_fwd(*a)
     # mode, dtype, Bt, S, d, H, hd, ph, then X, Wqkv, WoT, head_idx, Y, QKV, O, LSE, ws, ws_bytes, stream
     args = [FM, BF16, 2, 128, 128, 4, 64, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, big, None]
     unsupported, invalid, shape, workspace = -5, -1, -2, -3
     assert fwd(*([2] + args[1:])) == invalid                   # unknown regime
-    assert fwd(*(args[:1] + [F32] + args[2:])) == unsupported
-    assert fwd(*(args[:6] + [32] + args[7:])) == unsupported
+    assert fwd(*(args[:1] + [7] + args[2:])) == invalid        # unknown dtype
+    assert fwd(*(args[:6] + [136] + args[7:])) == unsupported  # head width beyond 128
+    assert fwd(*(args[:6] + [50] + args[7:])) == shape         # bf16 rows must be 16-byte multiples
     assert fwd(*(args[:7] + [5] + args[8:])) == shape          # more held heads than heads
     assert fwd(*(args[:2] + [0] + args[3:])) == invalid        # no sequence
     assert fwd(*(args[:8] + [None] + args[9:])) == invalid     # X missing
@@ -178,5 +181,5 @@ def test_attention_arguments_are_checked_on_the_host():
     bargs = [FM, BF16, 2, 128, 128, 4, 64, 2] + [FAKE] * 11 + [0, FAKE, big, None]
     assert L.sdp_masked_attn_bwd(*(bargs[:19] + [7] + bargs[20:])) == invalid   # unknown gradient layout
     assert L.sdp_masked_attn_bwd(*(bargs[:20] + [None, big, None])) == workspace
-    assert L.sdp_masked_attn_bwd(*(bargs[:1] + [F32] + bargs[2:])) == unsupported
+    assert L.sdp_masked_attn_bwd(*(bargs[:6] + [136] + bargs[7:])) == unsupported
     assert L.sdp_masked_attn_bwd(*([BM] + bargs[1:12] + [None] + bargs[13:])) == invalid  # the held heads are needed
