@@ -182,3 +182,26 @@ def test_attention_full_step_average(sdp, orc):
     assert_close(avg.cpu().numpy(), same_in, 1e-5, "average of the GPU's gradients")
     want, _ = orc.gated_average(refs, row_mask_host)
     assert err_report(avg.cpu().numpy(), want)[1] <= TOL, "averaged gradient, normwise"
+
+
+@pytest.mark.parametrize("mode", ["fm", "bm"])
+def test_plain_core_and_mfma_core_agree_on_the_same_inputs(sdp, mode):
+    """The same bf16-valued inputs through the fp32 path (plain contractions and plain attention core, no
+    intermediate rounding) and through the bf16 path (MFMA contractions and MFMA core): two implementations that
+    share no kernel must agree to the bf16 path's rounding, without the oracle in between."""
+    from helpers import err_report, err_report_rows
+
+    w = AttnWorkload("paths", 2, 320, 128, 4, 64, 2, 2, 44)
+    Wqkv, WoT = workloads.attn_weights(w)
+    X, dY = workloads.attn_batch(w, 0)
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    outs = {}
+    for name, conv in (("bf16", lambda t: t.cuda()), ("f32", lambda t: t.float().cuda())):
+        Y, QKV, O, LSE = sdp.masked_attn_fwd(mode, w.Bt, w.S, w.hd, conv(X), conv(Wqkv), conv(WoT), idx[0])
+        dX, gWqkv, gWoT = sdp.masked_attn_bwd(mode, w.Bt, w.S, w.hd, conv(X), conv(dY), conv(Wqkv), conv(WoT), idx[0], QKV, O, LSE)
+        torch.cuda.synchronize()
+        outs[name] = [workloads.to_f64(t) for t in (Y, O, dX)] + [workloads.to_f64(gWqkv).reshape(-1, w.d), workloads.to_f64(gWoT),
+                                                                 LSE.double().cpu().numpy().reshape(-1, w.S)]
+    for got, ref, what in zip(outs["bf16"], outs["f32"], ("Y", "O", "dX", "dWqkv", "dWoT", "LSE")):
+        elem, norm = (err_report if what.startswith("dW") else err_report_rows)(got, ref)
+        assert norm <= 1e-2 and elem <= 3e-2, f"{what}: elementwise {elem:.3e}, normwise {norm:.3e}"
