@@ -299,22 +299,31 @@ __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int
     }
 }
 
-// Causal rows differ in length: block i of a sequence meets i + 1 blocks of keys.  A workgroup therefore
-// takes blocks i and n - 1 - i of one (sequence, head), one after the other, so that all workgroups do
-// the same amount of work (they are all resident at once: nothing else would even them out).
-__device__ inline int paired_blocks(int nblocks, int x, int (&blk)[2]) {
-    blk[0] = nblocks - 1 - x, blk[1] = x;
-    return blk[0] == blk[1] ? 1 : 2;
+// Causal rows differ in length: block i of a sequence meets i + 1 blocks of keys, and at the sizes this
+// block runs at every workgroup of a launch is resident at once (about three per CU), so nothing evens the
+// work out afterwards.  One block per workgroup, and the blocks are dealt to the workgroup ids so that ids
+// congruent modulo the number of CUs -- which the dispatcher places on the same CU, one pass after the other
+// -- get a long, a short and a middling block: ranks in the order "longest first" run forwards in even passes
+// and backwards in odd ones.  Launches with more passes than fit at once start the long blocks first.
+__device__ inline void causal_item(int L, int nitems, int nbh, int nblocks, int ph, int& blk, int& head, int& b) {
+    constexpr int W = 256;
+    const int pass = L / W, base = pass * W;
+    const int width = nitems - base < W ? nitems - base : W;
+    const int w = L - base;
+    const int r = (pass & 1) ? base + (width - 1 - w) : base + w;
+    blk = nblocks - 1 - r / nbh;
+    const int bh = r % nbh;
+    head = bh % ph, b = bh / ph;
 }
 
 template <int QF, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SDP_ATTN_WPE_FWD, SDP_ATTN_WPE_FWD)))
-void attn_fwd_kernel(CoreArgs a, int nblocks) {
+void attn_fwd_kernel(CoreArgs a, int nblocks, int nbh) {
     __shared__ __attribute__((aligned(16))) unsigned char sK[2][TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sV[2][TILE_BYTES];
-    int blk[2];
-    const int n = paired_blocks(nblocks, blockIdx.x, blk);
-    for (int i = 0; i < n; ++i) attn_fwd_block<QF, NW>(a, blk[i] * 32 * QF * NW, blockIdx.y, blockIdx.z, sK, sV);
+    int blk, head, b;
+    causal_item(blockIdx.x, gridDim.x, nbh, nblocks, a.ph, blk, head, b);
+    attn_fwd_block<QF, NW>(a, blk * 32 * QF * NW, head, b, sK, sV);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -404,12 +413,12 @@ __device__ inline void attn_bwd_dq_block(const CoreArgs& a, const int q0, const 
     if (qrow < S) store_rows(a.dqkv + ((int64_t)b * S + qrow) * a.ldq + head * HD, acc, a.scale, lhi);
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SDP_ATTN_WPE_DQ, SDP_ATTN_WPE_DQ))) void attn_bwd_dq_kernel(CoreArgs a, int nblocks) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SDP_ATTN_WPE_DQ, SDP_ATTN_WPE_DQ))) void attn_bwd_dq_kernel(CoreArgs a, int nblocks, int nbh) {
     __shared__ __attribute__((aligned(16))) unsigned char sK[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sV[TILE_BYTES];
-    int blk[2];
-    const int n = paired_blocks(nblocks, blockIdx.x, blk);
-    for (int i = 0; i < n; ++i) attn_bwd_dq_block(a, blk[i] * BQ, blockIdx.y, blockIdx.z, sK, sV);
+    int blk, head, b;
+    causal_item(blockIdx.x, gridDim.x, nbh, nblocks, a.ph, blk, head, b);
+    attn_bwd_dq_block(a, blk * BQ, head, b, sK, sV);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -511,14 +520,15 @@ __device__ inline void attn_bwd_dkv_block(const CoreArgs& a, const int k0, const
     }
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_kernel(CoreArgs a, int nblocks) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_kernel(CoreArgs a, int nblocks, int nbh) {
     __shared__ __attribute__((aligned(16))) unsigned char sQ[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char sO[TILE_BYTES];
     __shared__ __attribute__((aligned(16))) float sL[64];
     __shared__ __attribute__((aligned(16))) float sD[64];
-    int blk[2];
-    const int n = paired_blocks(nblocks, blockIdx.x, blk); // the first key blocks meet the most queries: same pairing
-    for (int i = 0; i < n; ++i) attn_bwd_dkv_block(a, blk[i] * BQ, blockIdx.y, blockIdx.z, sQ, sO, sL, sD);
+    int blk, head, b;
+    causal_item(blockIdx.x, gridDim.x, nbh, nblocks, a.ph, blk, head, b);
+    // key block i meets the query blocks i .. n - 1: the first key blocks are the long ones
+    attn_bwd_dkv_block(a, (nblocks - 1 - blk) * BQ, head, b, sQ, sO, sL, sD);
 }
 
 // rows of [Wq; Wk; Wv] ([3 H hd][d]) and of WoT ([H hd][d]) that belong to the held heads
@@ -670,7 +680,8 @@ extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, in
         ProfileScope ps("attn_core_fwd", s);
         constexpr int QF = SDP_ATTN_FWD_QF, NW = SDP_ATTN_FWD_NW, ROWS = 32 * QF * NW;
         const int nblocks = (S + ROWS - 1) / ROWS;
-        attn_fwd_kernel<QF, NW><<<dim3((nblocks + 1) / 2, ph, Bt), 64 * NW, 0, s>>>(a, nblocks);
+        if ((int64_t)nblocks * ph * Bt > INT32_MAX) return SDP_ERR_UNSUPPORTED;
+        attn_fwd_kernel<QF, NW><<<dim3(nblocks * ph * Bt), 64 * NW, 0, s>>>(a, nblocks, ph * Bt);
         rc = launch_status();
     } else {
         AttnCoreDesc c;
@@ -735,16 +746,17 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
         a.S = S, a.ph = hr;
         a.scale = 1.f / sqrtf((float)hd), a.scale2 = a.scale * 1.44269504088896340736f;
         const int nblocks = (S + BQ - 1) / BQ;
-        const dim3 grid((nblocks + 1) / 2, hr, Bt);
+        if ((int64_t)nblocks * hr * Bt > INT32_MAX) return SDP_ERR_UNSUPPORTED;
+        const dim3 grid(nblocks * hr * Bt);
         {
             ProfileScope ps("attn_core_bwd_dq", s);
-            attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a, nblocks);
+            attn_bwd_dq_kernel<<<grid, 256, 0, s>>>(a, nblocks, hr * Bt);
             rc = launch_status();
             if (rc != SDP_OK) return rc;
         }
         {
             ProfileScope ps("attn_core_bwd_dkv", s); // reads the delta written by the dQ kernel
-            attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a, nblocks);
+            attn_bwd_dkv_kernel<<<grid, 256, 0, s>>>(a, nblocks, hr * Bt);
             rc = launch_status();
             if (rc != SDP_OK) return rc;
         }
