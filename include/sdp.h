@@ -103,6 +103,22 @@ int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t
                     int32_t* count, uint8_t* cov, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Distance to uniform masking (Thm. 3.1): rho^2 = || (1/K) 1 - m / c ||_Frob^2 over the K x F mask
+ * matrix, with the column's own load c_j as c (the gated average divides column j by c_j); it is 0
+ * iff every worker holds every neuron and enters the step-size bound and the variance term of the
+ * backward-masking rate.  A column of load c > 0 contributes 1/c - 1/K, an uncovered column 1/K, so
+ * the value follows from the histogram of loads, which is counted on the device in integers (the
+ * result does not depend on the order of the atomics) and finished on the host in fp64.
+ *   cov  [F] u8 device in: the loads c_j written by sdp_index_masks / sdp_make_masks
+ *   hist [SDP_MAX_WORKERS + 1] u64 device out: hist[c] = number of neurons of load c
+ *   rho2_host: host out
+ * The call synchronises `stream`.  Multiply by the row length to get the figure over all parameters
+ * of a neuron-major matrix.
+ * Errors: INVALID_ARG (null, K out of range, F < 1, a load above K in cov), SHAPE (F >= 2^31), HIP.
+ * ------------------------------------------------------------------------------------------- */
+int sdp_mask_rho2(int K, int64_t F, const uint8_t* cov, uint64_t* hist, double* rho2_host, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * One worker's MLP forward under either regime of Sec. 3.1.
  *   SDP_MASK_FORWARD  (m_fwd = m): the block is evaluated at the gated parameters, i.e. as the
  *     smaller dense MLP made of the worker's p active neurons idx_k[0..p) (Sec. 3.2):

@@ -56,6 +56,8 @@ def lib():
     L.sdp_index_masks_workspace_bytes.argtypes = [i32, i64]
     L.sdp_index_masks.restype = i32
     L.sdp_index_masks.argtypes = [i32, i64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.sdp_mask_rho2.restype = i32
+    L.sdp_mask_rho2.argtypes = [i32, i64, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.sdp_masked_mlp_fwd_workspace_bytes.restype = sz
     L.sdp_masked_mlp_fwd_workspace_bytes.argtypes = [i32] * 6
     L.sdp_masked_mlp_bwd_workspace_bytes.restype = sz
@@ -160,6 +162,16 @@ def index_masks(mask, idx_ld=None, ws=None):
                                ws.data_ptr(), ws.numel(), _stream())
     _check(st, "sdp_index_masks")
     return idx, pos, count, cov
+
+
+def mask_rho2(K, cov):
+    """cov u8 [F] (GPU), K workers -> (rho^2 as a float, load histogram i64 [65] on the GPU)."""
+    cptr = _dev(cov, torch.uint8, "cov")
+    hist = torch.empty((65,), dtype=torch.int64, device=cov.device)
+    out = ctypes.c_double(0.0)
+    st = lib().sdp_mask_rho2(K, cov.numel(), cptr, hist.data_ptr(), ctypes.byref(out), _stream())
+    _check(st, "sdp_mask_rho2")
+    return out.value, hist
 
 
 def masked_mlp_fwd_workspace_bytes(mode, dtype, T, d, F, p):

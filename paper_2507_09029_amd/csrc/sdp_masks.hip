@@ -276,6 +276,28 @@ __global__ __launch_bounds__(256) void coverage_kernel(const uint8_t* __restrict
     cov[j] = (uint8_t)c;
 }
 
+// load histogram hist[c] = #{ j : c_j = c }, c = 0 .. SDP_MAX_WORKERS
+constexpr int kLoads = SDP_MAX_WORKERS + 1;
+
+__global__ void clear_histogram_kernel(unsigned long long* __restrict__ hist) {
+    if (threadIdx.x < kLoads) hist[threadIdx.x] = 0ull;
+}
+
+__global__ __launch_bounds__(256) void load_histogram_kernel(const uint8_t* __restrict__ cov, int64_t F,
+                                                             unsigned long long* __restrict__ hist) {
+    __shared__ unsigned int local[kLoads];
+    for (int i = threadIdx.x; i < kLoads; i += blockDim.x) local[i] = 0u;
+    __syncthreads();
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < F; j += stride) {
+        const int c = cov[j];
+        atomicAdd(&local[c < kLoads ? c : kLoads - 1], 1u); // a count above K cannot come from sdp_index_masks
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kLoads; i += blockDim.x)
+        if (local[i]) atomicAdd(&hist[i], (unsigned long long)local[i]);
+}
+
 int check_index_args(int K, int64_t F, const void* mask, const void* idx, int64_t idx_ld, const void* pos,
                      const void* cov, const void* ws, size_t ws_bytes) {
     if (!mask || !idx || !pos || !cov) return SDP_ERR_INVALID_ARG;
@@ -313,6 +335,33 @@ extern "C" int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* i
         coverage_kernel<<<dim3((unsigned)((F + 255) / 256)), 256, 0, s>>>(mask, K, F, cov);
     }
     return sdp::launch_status();
+}
+
+extern "C" int sdp_mask_rho2(int K, int64_t F, const uint8_t* cov, uint64_t* hist, double* rho2_host, void* stream) {
+    if (!cov || !hist || !rho2_host) return SDP_ERR_INVALID_ARG;
+    if (K < 1 || K > SDP_MAX_WORKERS || F < 1) return SDP_ERR_INVALID_ARG;
+    if (F >= ((int64_t)1 << 31)) return SDP_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned long long* h = reinterpret_cast<unsigned long long*>(hist);
+    {
+        sdp::ProfileScope ps("mask_load_histogram", s);
+        clear_histogram_kernel<<<1, 128, 0, s>>>(h);
+        const int64_t blocks = (F + 256 * 16 - 1) / (256 * 16); // each block's 65 global atomics pay for 4096 columns
+        load_histogram_kernel<<<dim3((unsigned)(blocks < 2048 ? blocks : 2048)), 256, 0, s>>>(cov, F, h);
+    }
+    int rc = sdp::launch_status();
+    if (rc != SDP_OK) return rc;
+    uint64_t host[kLoads];
+    if (hipMemcpyAsync(host, hist, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return SDP_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return SDP_ERR_HIP;
+    for (int c = K + 1; c < kLoads; ++c)
+        if (host[c]) return SDP_ERR_INVALID_ARG; // cov does not belong to K workers
+    // a column of load c > 0 holds c entries (1/K - 1/c) and K - c entries 1/K: together 1/c - 1/K;
+    // an uncovered column holds K entries 1/K
+    double acc = (double)host[0] / K;
+    for (int c = 1; c <= K; ++c) acc += (double)host[c] * (1.0 / c - 1.0 / K);
+    *rho2_host = acc;
+    return SDP_OK;
 }
 
 extern "C" int sdp_sample_masks_host(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask_host) {

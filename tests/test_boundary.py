@@ -64,6 +64,14 @@ def test_argument_errors_are_caught_on_the_host():
     assert L.sdp_index_masks(4, 16, FAKE, FAKE, 0, FAKE, None, FAKE, FAKE, big, None) == -2
     assert L.sdp_index_masks(4, 16, None, FAKE, 8, FAKE, None, FAKE, FAKE, big, None) == -1
     assert L.sdp_index_masks(4, 16, FAKE, FAKE, 8, FAKE, None, FAKE, FAKE, ctypes.c_size_t(8), None) == -3
+    # rho^2
+    out = ctypes.c_double(0.0)
+    assert L.sdp_mask_rho2(4, 16, None, FAKE, ctypes.byref(out), None) == -1
+    assert L.sdp_mask_rho2(4, 16, FAKE, None, ctypes.byref(out), None) == -1
+    assert L.sdp_mask_rho2(4, 16, FAKE, FAKE, None, None) == -1
+    assert L.sdp_mask_rho2(65, 16, FAKE, FAKE, ctypes.byref(out), None) == -1
+    assert L.sdp_mask_rho2(4, 0, FAKE, FAKE, ctypes.byref(out), None) == -1
+    assert L.sdp_mask_rho2(4, 1 << 31, FAKE, FAKE, ctypes.byref(out), None) == -2
     # forward
     def fwd(mode=0, dt=1, T=16, d=16, F=32, p=16, X=FAKE, idx=FAKE, ws=FAKE, wsb=big):
         return L.sdp_masked_mlp_fwd(mode, dt, T, d, F, p, X, FAKE, FAKE, FAKE, idx, FAKE, FAKE, FAKE, ws, wsb, None)

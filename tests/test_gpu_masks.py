@@ -76,3 +76,32 @@ def test_index_masks_general_masks(sdp, orc, K, F, density, idx_ld):
     assert (idx.cpu().numpy() == widx).all()
     assert (pos.cpu().numpy() == wpos).all()
     assert (cov.cpu().numpy() == wcov).all()
+
+
+@pytest.mark.parametrize("K,F,p,seed,cover", [
+    (workloads.CONFIG2.K, workloads.CONFIG2.F, workloads.CONFIG2.p, workloads.CONFIG2.mask_seed, True),
+    (workloads.CONFIG5.K, workloads.CONFIG5.R, workloads.CONFIG5.p, workloads.CONFIG5.mask_seed, False),
+    (4, 4096, 2048, 9, "balanced"), (1, 1, 1, 3, True), (64, 4097, 1000, 6, False), (3, 100001, 20000, 8, False),
+])
+def test_mask_rho2_matches_oracle(sdp, orc, K, F, p, seed, cover):
+    """Distance to uniform masking (Thm. 3.1): integer load histogram bit-exact, the value to fp64 rounding."""
+    print(f"mask_rho2 K={K} F={F} p={p} seed={seed} cover={cover}", flush=True)
+    mask, _, _, cov = sdp.make_masks(K, F, p, seed, cover)
+    rho2, hist = sdp.mask_rho2(K, cov)
+    want_mask = orc.make_masks_balanced(K, F, p, seed) if cover == "balanced" else orc.make_masks(K, F, p, seed, cover)
+    want = orc.rho2(want_mask)
+    loads = np.bincount(want_mask.sum(axis=0, dtype=np.int64), minlength=65)
+    assert (hist.cpu().numpy() == loads).all()
+    # the oracle adds K F non-negative terms one after the other (error at most K F ulps of the sum); the library
+    # adds at most K + 1 products of exact counts
+    assert abs(rho2 - want) <= (K * F + 64) * 2.0 ** -52 * max(1.0, abs(want))
+    if cover == "balanced":  # K p a multiple of F: every load is K p / F
+        assert abs(rho2 - F * (F / (K * p) - 1 / K)) < 1e-9
+
+
+def test_mask_rho2_rejects_loads_above_K(sdp):
+    cov = torch.full((1000,), 5, dtype=torch.uint8, device="cuda")
+    with pytest.raises(RuntimeError):
+        sdp.mask_rho2(4, cov)
+    rho2, hist = sdp.mask_rho2(5, cov)  # all five workers hold everything
+    assert rho2 == 0.0 and int(hist[5]) == 1000

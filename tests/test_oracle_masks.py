@@ -181,3 +181,19 @@ def test_rho2_closed_form_for_constant_load(orc):
         mask[(j + 1) % K, j] = 1
     assert abs(orc.rho2(mask) - F * (1 / 2 - 1 / K)) < 1e-12
     assert orc.rho2(np.ones((K, F), dtype=np.uint8)) == 0.0  # C = 1 is DDP
+
+
+def test_rho2_by_hand_and_against_a_library_norm(orc):
+    # two workers, three columns of load 2, 1, 0: the entries of (1/n) 1 - m / c are
+    #   column 0: 0, 0;  column 1: -1/2, 1/2;  column 2 (nobody holds it): 1/2, 1/2  ->  rho^2 = 0 + 1/2 + 1/2
+    assert orc.rho2(np.array([[1, 1, 0], [1, 0, 0]], dtype=np.uint8)) == 1.0
+    # uneven loads: the matrix written out and handed to numpy's Frobenius norm
+    rng = np.random.default_rng(12)
+    K, F = 7, 301
+    mask = (rng.random((K, F)) < 0.4).astype(np.uint8)
+    mask[:, :5] = 0
+    c = mask.sum(axis=0)
+    A = np.full((K, F), 1.0 / K) - np.divide(mask, c, out=np.zeros((K, F)), where=c > 0)
+    assert abs(orc.rho2(mask) - np.linalg.norm(A, "fro") ** 2) < 1e-10
+    # transposing the roles of the two terms' signs or dropping the uncovered columns would show here
+    assert abs(orc.rho2(mask) - np.linalg.norm(A[:, 5:], "fro") ** 2 - 5 / K) < 1e-10
