@@ -485,17 +485,20 @@ __device__ inline void attn_bwd_dkv_block(const CoreArgs& a, const int k0, const
                 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sQ, 32 * tb + l32, s, lhi), kf[s], sc, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sO, 32 * tb + l32, s, lhi), vf[s], dp, 0, 0, 0);
             }
+            if (edge) { // a branch of its own: only the tiles on the diagonal and the ragged last one pay for it
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int query = qt0 + 32 * tb + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                    if (krow > query || query >= S) sc[e] = -INFINITY;
+                }
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const f32x4 l4 = *(const f32x4*)(sL + 32 * tb + 8 * q + 4 * lhi);
                 const f32x4 d4 = *(const f32x4*)(sD + 32 * tb + 8 * q + 4 * lhi);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float z = sc[4 * q + r];
-                    if (edge) {
-                        const int query = qt0 + 32 * tb + 8 * q + 4 * lhi + r;
-                        if (krow > query || query >= S) z = -INFINITY;
-                    }
+                    const float z = sc[4 * q + r];
                     const float p = exp2_neg(__builtin_fmaf(z, a.scale2, -l4[r]));
                     sc[4 * q + r] = p;
                     dp[4 * q + r] = p * (dp[4 * q + r] - d4[r]);
