@@ -55,6 +55,7 @@ typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 constexpr int HD = 64;              // head width of the MFMA core
 constexpr int RSB = 144;            // bytes per LDS tile row: 64 bf16 + 16 bytes (bank spread), 16-byte aligned
 constexpr int TILE_BYTES = 64 * RSB; // one 64 x 64 tile
+constexpr float kSlack = 8.f;      // forward: how far a query's maximum may run ahead of its reference exponent
 constexpr int BQ = 128;             // rows (queries, or keys in the dK/dV kernel) per workgroup: 4 waves x 32
 
 struct CoreArgs {
@@ -75,6 +76,13 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     const bf16x2 v = {(__bf16)lo, (__bf16)hi};
     return __builtin_bit_cast(uint32_t, v);
+}
+
+// acc + the two bf16 halves of w (v_dot2c_f32_bf16 against a pair of ones)
+__device__ inline float pair_sum(uint32_t w, float acc) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, acc, false);
 }
 
 // elements 8 s .. 8 s + 7 of an accumulator tile as a bf16 operand
@@ -241,6 +249,7 @@ __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int
                         }
                 }
             }
+            bf16x8 pf[QF][2][2]; // probabilities as operands: [query block][key block][depth half]
 #pragma unroll
             for (int f = 0; f < QF; ++f) {
                 float mx = -INFINITY;
@@ -249,42 +258,52 @@ __device__ inline void attn_fwd_block(const CoreArgs& a, const int q0, const int
 #pragma unroll
                     for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[f][tb][e]);
                 mx = fmaxf(mx, other_half(mx));
-                // the first tile holds key 0, which no query masks: the running maximum is finite from then
-                // on.  m is kept in units of the scaled base-2 logits; the scale rides in the multiply-add.
-                const float m_new = fmaxf(m[f], mx * a.scale2);
-                const float alpha = exp2_neg(m[f] - m_new);
-                m[f] = m_new;
+                // m is the reference the exponents are taken against, in units of the scaled base-2 logits (the
+                // scale rides in the multiply-add).  It follows the running maximum lazily: only when a query's
+                // maximum has grown by more than kSlack is the reference moved and the accumulators rescaled, so
+                // probabilities stay below 2^kSlack and the 32 multiplies of the rescale run on few tiles (the
+                // first one always: it holds key 0, which no query masks, so m is finite from then on).
+                const float m_cand = mx * a.scale2;
+                if (__builtin_amdgcn_ballot_w64(m_cand > m[f] + kSlack) != 0) { // wave-uniform
+                    const float m_new = m_cand > m[f] + kSlack ? m_cand : m[f];
+                    const float alpha = exp2_neg(m[f] - m_new);
+                    m[f] = m_new;
+                    lsum[f] *= alpha;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc_o[f][j][e] *= alpha;
+                }
+                // the sum runs over the rounded probabilities, the ones the second product sees, two per instruction
                 float ps = 0.f;
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const float p = exp2_neg(__builtin_fmaf(sc[f][tb][e], a.scale2, -m_new));
-                        sc[f][tb][e] = p;
-                        ps += p;
+                    for (int h = 0; h < 2; ++h) {
+                        u32x4 w;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float p0 = exp2_neg(__builtin_fmaf(sc[f][tb][8 * h + 2 * i], a.scale2, -m[f]));
+                            const float p1 = exp2_neg(__builtin_fmaf(sc[f][tb][8 * h + 2 * i + 1], a.scale2, -m[f]));
+                            w[i] = pack_bf16(p0, p1);
+                            ps = pair_sum(w[i], ps);
+                        }
+                        pf[f][tb][h] = __builtin_bit_cast(bf16x8, w);
                     }
-                lsum[f] = lsum[f] * alpha + ps;
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc_o[f][j][e] *= alpha;
+                lsum[f] += ps;
             }
             // O^T[h][query] += sum_key V[key][h] P[query][key]
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    bf16x8 pf[QF];
-#pragma unroll
-                    for (int f = 0; f < QF; ++f) pf[f] = pack_operand(sc[f][tb], s);
+                for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         const bf16x8 vfr = frag_cols(tV, 32 * tb + 16 * s, 32 * j, lane);
 #pragma unroll
                         for (int f = 0; f < QF; ++f)
-                            acc_o[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, pf[f], acc_o[f][j], 0, 0, 0);
+                            acc_o[f][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, pf[f][tb][s], acc_o[f][j], 0, 0, 0);
                     }
-                }
         }
         __syncthreads(); // tile t is released, tile t + 1 is in place
     }

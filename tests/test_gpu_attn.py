@@ -205,3 +205,38 @@ def test_plain_core_and_mfma_core_agree_on_the_same_inputs(sdp, mode):
     for got, ref, what in zip(outs["bf16"], outs["f32"], ("Y", "O", "dX", "dWqkv", "dWoT", "LSE")):
         elem, norm = (err_report if what.startswith("dW") else err_report_rows)(got, ref)
         assert norm <= 1e-2 and elem <= 3e-2, f"{what}: elementwise {elem:.3e}, normwise {norm:.3e}"
+
+
+def test_forward_core_with_logits_that_keep_growing(sdp, orc):
+    """Keys later in a sequence carry larger logits, so a query's running maximum climbs far beyond what it was
+    after the first tile: the forward kernel has to move its reference exponent (and rescale what it has
+    accumulated) several times on the way.  The core is isolated from the projections: the oracle evaluates
+    the attention of the Q, K, V the library stored (bf16 values, widened exactly), through selector matrices."""
+    w = AttnWorkload("growing_logits", 2, 520, 128, 2, 64, 2, 2, 45)
+    Wqkv, WoT = workloads.attn_weights(w)
+    Wqkv = Wqkv.clone()
+    Wqkv[:2] *= 10.0  # W_Q, W_K
+    X, _ = workloads.attn_batch(w, 0)
+    ramp = 0.25 + 1.75 * torch.arange(w.S, dtype=torch.float32) / (w.S - 1)  # token norm grows 8-fold along a sequence
+    X = (X.float().view(w.Bt, w.S, w.d) * ramp[None, :, None]).view(w.T, w.d).to(X.dtype)
+    heads = torch.arange(w.H, dtype=torch.int32, device="cuda")
+    Y, QKV, O, LSE = sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X.cuda(), Wqkv.cuda(), WoT.cuda(), heads)
+    torch.cuda.synchronize()
+    E = w.H * w.hd
+    qkv = workloads.to_f64(QKV)
+    sel = [np.zeros((E, 3 * E)) for _ in range(3)]
+    for i in range(3):
+        sel[i][np.arange(E), i * E + np.arange(E)] = 1.0
+    ref = orc.attn_fwd(w.Bt, w.S, w.hd, qkv, sel[0], sel[1], sel[2], np.zeros((E, 3 * E)))  # the output projection is not used
+    assert (ref["Q"] == qkv[:, :E]).all() and (ref["V"] == qkv[:, 2 * E:]).all()
+    q = ref["Q"].reshape(w.Bt, w.S, w.H, w.hd)
+    k = ref["K"].reshape(w.Bt, w.S, w.H, w.hd)
+    z = np.einsum("bshr,buhr->bhsu", q, k) / np.sqrt(w.hd) / np.log(2.0)
+    z = np.where(np.tril(np.ones((w.S, w.S), bool)), z, -np.inf)
+    # the case does what it is meant to: maxima over the first 64 keys against maxima over all keys
+    growth = z.max(axis=-1)[..., 64:] - z[..., :64].max(axis=-1)[..., 64:]
+    assert np.median(growth) > 16.0, f"median growth of the running maximum {np.median(growth):.1f}"
+    zmax = z.max(axis=-1, keepdims=True)
+    lse2 = zmax[..., 0] + np.log2(np.exp2(z - zmax).sum(axis=-1))
+    assert np.abs(LSE.cpu().numpy() - lse2).max() <= 1e-4 * np.abs(lse2).max()
+    assert_close_rows(workloads.to_f64(O), ref["O"], TOL, "O")
