@@ -122,6 +122,29 @@ def bench_grad_avg_1b(sdp, torch, steps):
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((c.name, "coverage_grad_avg"))},
     }
+    # the squared norm of the average alone (what gradient clipping needs before the fused update): reads the
+    # covered gradient rows, writes nothing
+    sq = torch.empty((1,), dtype=torch.float64, device="cuda")
+    for _ in range(2):
+        sdp.coverage_grad_sqnorm(grads, mask, out=sq)
+    torch.cuda.synchronize()
+    sdp.profile_reset()
+    sdp.profile_enable(True)
+    nsq = max(3, steps // 2)
+    for _ in range(nsq):
+        sdp.coverage_grad_sqnorm(grads, mask, out=sq)
+    torch.cuda.synchronize()
+    prof = sdp.profile_read()
+    sdp.profile_enable(False)
+    calls, ms = prof["coverage_grad_sqnorm"]
+    kern_sq = ms / calls * 1e-3
+    rbytes = c.K * c.p * c.D * 2 + c.K * c.R
+    res["sqnorm"] = {
+        "algorithmic_bytes": rbytes, "ms_per_call": kern_sq * 1e3,
+        "roofline": {"bound": "hbm", "achieved": rbytes / kern_sq / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": rbytes / kern_sq / 1e9 / PEAK_HBM_GBS, "traffic": None},
+        "note": "covered gradient rows (bf16) + masks read, one fp64 number written",
+    }
     # the same pass with AdamW fused in: besides the covered gradient rows it reads and writes the fp32
     # parameters and both moments of every covered row once
     del out

@@ -249,6 +249,23 @@ int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const void* cons
                            const sdp_adamw_params* hp, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Squared l2 norm of the coverage-normalised average, sum over all rows and parameters of
+ * ((1 / c_r) sum_{k covers r} g_k[r][e])^2, without storing the average: the quantity that global
+ * gradient clipping (App. "Hyperparameters for LLM Architecture": clipping at 1.0) measures before the
+ * update; min(1, clip / sqrt(norm^2)) is the grad_scale of sdp_coverage_avg_adamw.  Same streaming
+ * pass as the average (only covered rows are read); each element is averaged in fp32 exactly as
+ * sdp_coverage_grad_avg would store it, squares are summed in fp64 in a fixed order (no atomics: the
+ * result is a pure function of the inputs).  Rows nobody covers contribute 0.
+ *   g, mask   as for sdp_coverage_grad_avg
+ *   sqnorm    device, one fp64 value out (8-byte aligned)
+ *   ws        sdp_coverage_grad_sqnorm_workspace_bytes(R, D) bytes, 16-byte aligned
+ * R = 0 writes 0.  Errors: INVALID_ARG, SHAPE (R D > 2^40), WORKSPACE.
+ * ------------------------------------------------------------------------------------------- */
+size_t sdp_coverage_grad_sqnorm_workspace_bytes(int64_t R, int D);
+int sdp_coverage_grad_sqnorm(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
+                             double* sqnorm, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Per-kernel timing.  With profiling on, every kernel launch is bracketed by HIP events on its
  * stream.  sdp_profile_read synchronises those events and returns, for up to `cap` distinct
  * kernel names, the launch count and total milliseconds since the last reset.

@@ -65,6 +65,10 @@ def lib():
             ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
             ctypes.POINTER(ctypes.c_void_p), _u8p, _f64p, _u8p,
         ]
+        L.orc_gated_average_sqnorm.restype = ctypes.c_double
+        L.orc_gated_average_sqnorm.argtypes = [
+            ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), _u8p,
+        ]
         L.orc_attn_fwd.restype = None
         L.orc_attn_fwd.argtypes = [ctypes.c_int64] * 5 + [_f64p] * 10
         L.orc_attn_bwd.restype = None
@@ -197,6 +201,21 @@ def gated_average(g_list, mask):
     cov = np.empty((R,), dtype=np.uint8)
     lib().orc_gated_average(K, R, D, gtype, ptrs, _p(mask, _u8p), _p(out, _f64p), _p(cov, _u8p))
     return out, cov
+
+
+def gated_average_sqnorm(g_list, mask):
+    """Squared l2 norm of the coverage-normalised average (fp64); see orc_gated_average_sqnorm."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    K, R = mask.shape
+    assert len(g_list) == K
+    g_list = [np.ascontiguousarray(g) for g in g_list]
+    D = g_list[0].shape[1]
+    dt = g_list[0].dtype
+    gtype = {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float64): 2}[dt]
+    for g in g_list:
+        assert g.shape == (R, D) and g.dtype == dt
+    ptrs = (ctypes.c_void_p * K)(*[g.ctypes.data for g in g_list])
+    return float(lib().orc_gated_average_sqnorm(K, R, D, gtype, ptrs, _p(mask, _u8p)))
 
 
 def avg_adamw(g_list, mask, theta, m, v, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0):

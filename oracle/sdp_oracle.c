@@ -386,6 +386,28 @@ void orc_gated_average(int K, int64_t R, int64_t D, int gtype, const void* const
     }
 }
 
+/* Squared l2 norm of the gated average: what the global gradient clipping of */
+/* the LLM runs (App. "Hyperparameters for LLM Architecture": clipping at 1.0) */
+/* measures before the update.  Rows nobody covers have a zero average.        */
+/* Plain sequential sum in fp64, rows in order.                                */
+double orc_gated_average_sqnorm(int K, int64_t R, int64_t D, int gtype, const void* const* g,
+                                const uint8_t* mask) {
+    double total = 0.0;
+    for (int64_t r = 0; r < R; ++r) {
+        int c = 0;
+        for (int k = 0; k < K; ++k) c += mask[(int64_t)k * R + r] ? 1 : 0;
+        if (!c) continue;
+        for (int64_t e = 0; e < D; ++e) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k)
+                if (mask[(int64_t)k * R + r]) s += widen(g[k], gtype, r * D + e);
+            const double a = s / (double)c;
+            total += a * a;
+        }
+    }
+    return total;
+}
+
 /* ------------------------------------------------------------------------- */
 /* The gated average followed by the optimizer the paper trains with (AdamW,   */
 /* App. "Hyperparameters for LLM Architecture"), on covered rows only         */

@@ -76,6 +76,10 @@ def lib():
     L.sdp_masked_attn_bwd.argtypes = [i32] * 8 + [vp] * 11 + [i32, vp, sz, vp]
     L.sdp_coverage_grad_avg.restype = i32
     L.sdp_coverage_grad_avg.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp]
+    L.sdp_coverage_grad_sqnorm_workspace_bytes.restype = sz
+    L.sdp_coverage_grad_sqnorm_workspace_bytes.argtypes = [i64, i32]
+    L.sdp_coverage_grad_sqnorm.restype = i32
+    L.sdp_coverage_grad_sqnorm.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, sz, vp]
     L.sdp_coverage_avg_adamw.restype = i32
     L.sdp_coverage_avg_adamw.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp, vp, vp, vp, vp]
     L.sdp_profile_enable.restype = i32
@@ -321,6 +325,29 @@ def coverage_grad_avg(grads, mask, out=None, cov=None):
                                      _dev(out, torch.float32, "out"), _dev(cov, torch.uint8, "cov"), _stream())
     _check(st, "sdp_coverage_grad_avg")
     return out, cov
+
+
+def coverage_grad_sqnorm(grads, mask, out=None, ws=None):
+    """Squared l2 norm of the coverage-normalised average of `grads` -> fp64 tensor with one element, on the GPU."""
+    K = len(grads)
+    if K < 1 or K > MAX_WORKERS:
+        raise SdpError(-1, "sdp_coverage_grad_sqnorm")
+    dt = grads[0].dtype
+    R, D = grads[0].shape
+    ptrs = (ctypes.c_void_p * K)(*[_dev(g, dt, f"grads[{i}]") for i, g in enumerate(grads)])
+    for g in grads:
+        if tuple(g.shape) != (R, D):
+            raise ValueError("all gradient buffers must share one shape")
+    if tuple(mask.shape) != (K, R):
+        raise ValueError("mask must be [K][R]")
+    if out is None:
+        out = torch.empty((1,), dtype=torch.float64, device=grads[0].device)
+    if ws is None:
+        ws = _ws(int(lib().sdp_coverage_grad_sqnorm_workspace_bytes(R, D)), grads[0].device)
+    st = lib().sdp_coverage_grad_sqnorm(K, R, D, _DTYPES[dt], ptrs, _dev(mask, torch.uint8, "mask"),
+                                        _dev(out, torch.float64, "sqnorm"), ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_coverage_grad_sqnorm")
+    return out
 
 
 class AdamWParams(ctypes.Structure):

@@ -9,7 +9,8 @@
 // The same pass can apply the optimizer instead of storing the average (sdp_coverage_avg_adamw):
 // the averaged gradient of a covered row goes straight into a decoupled-weight-decay Adam update of
 // that row's fp32 parameters and moments, which are read and written once; rows nobody covers are
-// left untouched.
+// left untouched.  A third form (sdp_coverage_grad_sqnorm) stores nothing and returns the squared norm of
+// the average, which global gradient clipping needs before that fused update.
 #include "sdp_internal.h"
 
 #include <cmath>
@@ -32,7 +33,29 @@ struct AdamArgs {
     float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^t)
     float eps;
     float grad_scale;
+    double* partial;      // OPT = 2: one partial sum of squares per workgroup
 };
+
+constexpr int OPT_STORE = 0, OPT_ADAMW = 1, OPT_SQNORM = 2;
+
+// Sum of one double per thread over a workgroup of 256 threads, in a fixed order: butterfly inside each wave,
+// then the four waves' sums one after the other.  The result is valid in thread 0.
+__device__ inline double block_sum(double x) {
+    __shared__ double wave_sums[4];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
+    if ((threadIdx.x & 63) == 0) wave_sums[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return ((wave_sums[0] + wave_sums[1]) + wave_sums[2]) + wave_sums[3];
+}
+
+// partial sums of the workgroups -> one number, again in a fixed order
+__global__ __launch_bounds__(256) void sqnorm_finish_kernel(const double* __restrict__ partial, int n, double* __restrict__ out) {
+    double x = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) x += partial[i];
+    x = block_sum(x);
+    if (threadIdx.x == 0) *out = x;
+}
 
 __device__ inline uint32_t pack2_bf16(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -78,6 +101,7 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
     const int lane = threadIdx.x & 63;
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    double sq = 0.0; // OPT_SQNORM: this lane's share of the sum of squares
     for (int64_t item = wave0; item < nitems; item += nwaves) {
         const int64_t r = item / segs;
         const int seg = (int)(item - r * segs);
@@ -89,7 +113,7 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
         // optimizer state of the segment: requested first, so that it travels while the gradients are summed
         // (rows nobody covers are read too, which is harmless and rare, and never written back)
         f32x4 th[2], mm[2], vv[2];
-        if (OPT && live) {
+        if (OPT == OPT_ADAMW && live) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 th[h] = *((const f32x4*)(ad.theta + off) + h);
@@ -131,7 +155,16 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
                 }
             }
         }
-        if (live && !OPT) {
+        if (live && OPT == OPT_SQNORM && c > 0) {
+            // squares of the very fp32 values the storing form would write, added up in double
+            const float denom = (float)c;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const double a = (double)(acc[i] / denom);
+                sq += a * a;
+            }
+        }
+        if (live && OPT == OPT_STORE) {
             // c == 0: nobody covers the row, the average is defined as 0 (acc is still 0)
             const float denom = c > 0 ? (float)c : 1.0f;
             f32x4 a, b;
@@ -144,7 +177,7 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
             __builtin_nontemporal_store(a, dst);
             __builtin_nontemporal_store(b, dst + 1);
         }
-        if (live && OPT && c > 0) {
+        if (live && OPT == OPT_ADAMW && c > 0) {
             // rows nobody covers keep their parameters and moments
             const float denom = (float)c;
 #pragma unroll
@@ -169,6 +202,10 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
         }
         if (cov && seg == 0 && lane == 0) cov[r] = (uint8_t)c;
     }
+    if (OPT == OPT_SQNORM) {
+        sq = block_sum(sq);
+        if (threadIdx.x == 0) ad.partial[blockIdx.x] = sq;
+    }
 }
 
 // Any D: one thread per parameter.
@@ -177,6 +214,7 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
                                                         int D, float* __restrict__ out, uint8_t* __restrict__ cov,
                                                         AdamArgs ad) {
     const int64_t n = R * D;
+    double sq = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = i / D;
         float acc = 0.f;
@@ -189,8 +227,13 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
             else
                 acc += ((const float*)g.p[k])[i];
         }
-        if (!OPT) {
+        if (OPT == OPT_STORE) {
             out[i] = acc / (c > 0 ? (float)c : 1.0f);
+        } else if (OPT == OPT_SQNORM) {
+            if (c > 0) {
+                const double a = (double)(acc / (float)c);
+                sq += a * a;
+            }
         } else if (c > 0) {
             float t = ad.theta[i], m1 = ad.m[i], v1 = ad.v[i];
             adamw_one(ad, acc / (float)c, t, m1, v1);
@@ -199,11 +242,22 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
         }
         if (cov && i == r * D) cov[r] = (uint8_t)c;
     }
+    if (OPT == OPT_SQNORM) {
+        sq = block_sum(sq);
+        if (threadIdx.x == 0) ad.partial[blockIdx.x] = sq;
+    }
+}
+
+// workgroups of the norm pass: enough to keep every CU's queue full, few enough for a small table of partial sums
+constexpr int64_t kNormBlocks = 1 << 15;
+int64_t norm_blocks(int64_t R, int D) {
+    const int64_t want = D % 8 == 0 ? (R * ((D + 511) / 512) + 3) / 4 : (R * D + 255) / 256;
+    return want < 1 ? 1 : (want < kNormBlocks ? want : kNormBlocks);
 }
 
 // argument checks and launch shared by the two entry points; ad == nullptr: store the average into out
 int launch_average(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask, float* out,
-                   uint8_t* cov, const AdamArgs* ad, const char* name, hipStream_t s) {
+                   uint8_t* cov, const AdamArgs* ad, const char* name, hipStream_t s, bool norm = false) {
     GradPtrs ptrs;
     for (int k = 0; k < K; ++k) {
         if (!g[k] || !sdp::aligned16(g[k])) return SDP_ERR_INVALID_ARG;
@@ -216,8 +270,11 @@ int launch_average(int K, int64_t R, int D, int gdtype, const void* const* g, co
         const int segs = (D + 511) / 512;
         const int64_t items = R * segs;
         const int64_t blocks64 = (items + 3) / 4; // 4 waves per workgroup
-        const unsigned blocks = (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
-        if (gdtype == SDP_BF16) {
+        const unsigned blocks = norm ? (unsigned)norm_blocks(R, D) : (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
+        if (norm) {
+            if (gdtype == SDP_BF16) avg_rows_kernel<1, OPT_SQNORM><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+            else avg_rows_kernel<0, OPT_SQNORM><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+        } else if (gdtype == SDP_BF16) {
             if (ad) avg_rows_kernel<1, 1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
             else avg_rows_kernel<1, 0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
         } else {
@@ -227,8 +284,11 @@ int launch_average(int K, int64_t R, int D, int gdtype, const void* const* g, co
     } else {
         const int64_t n = R * D;
         const int64_t blocks64 = (n + 255) / 256;
-        const unsigned blocks = (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
-        if (gdtype == SDP_BF16) {
+        const unsigned blocks = norm ? (unsigned)norm_blocks(R, D) : (unsigned)(blocks64 < (1 << 20) ? blocks64 : (1 << 20));
+        if (norm) {
+            if (gdtype == SDP_BF16) avg_elems_kernel<1, OPT_SQNORM><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+            else avg_elems_kernel<0, OPT_SQNORM><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
+        } else if (gdtype == SDP_BF16) {
             if (ad) avg_elems_kernel<1, 1><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
             else avg_elems_kernel<1, 0><<<blocks, 256, 0, s>>>(ptrs, mask, K, R, D, out, cov, a);
         } else {
@@ -275,4 +335,30 @@ extern "C" int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const
     a.step_size = (float)((double)hp->lr / (1.0 - std::pow((double)hp->beta1, (double)hp->step)));
     a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)hp->beta2, (double)hp->step)));
     return launch_average(K, R, D, gdtype, g, mask, nullptr, cov, &a, "coverage_avg_adamw", (hipStream_t)stream);
+}
+
+extern "C" size_t sdp_coverage_grad_sqnorm_workspace_bytes(int64_t R, int D) {
+    if (R < 0 || D < 1) return 0;
+    return sdp::round_up((size_t)norm_blocks(R, D) * sizeof(double), 256);
+}
+
+extern "C" int sdp_coverage_grad_sqnorm(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
+                                        double* sqnorm, void* ws, size_t ws_bytes, void* stream) {
+    if (K < 1 || K > SDP_MAX_WORKERS || R < 0 || D < 1) return SDP_ERR_INVALID_ARG;
+    if (gdtype != SDP_F32 && gdtype != SDP_BF16) return SDP_ERR_INVALID_ARG;
+    if (!g || !sqnorm || ((uintptr_t)sqnorm & 7)) return SDP_ERR_INVALID_ARG;
+    if (R > 0 && !mask) return SDP_ERR_INVALID_ARG;
+    if (R > 0 && R > ((int64_t)1 << 40) / D) return SDP_ERR_SHAPE;
+    if (!ws || !sdp::aligned16(ws) || ws_bytes < sdp_coverage_grad_sqnorm_workspace_bytes(R, D)) return SDP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    AdamArgs a{};
+    a.partial = (double*)ws;
+    if (R == 0) { // nothing to add (empty buffers may legitimately be null): the norm is 0
+        sqnorm_finish_kernel<<<1, 256, 0, s>>>((const double*)ws, 0, sqnorm);
+        return sdp::launch_status();
+    }
+    int rc = launch_average(K, R, D, gdtype, g, mask, nullptr, nullptr, &a, "coverage_grad_sqnorm", s, true);
+    if (rc != SDP_OK) return rc;
+    sqnorm_finish_kernel<<<1, 256, 0, s>>>((const double*)ws, (int)norm_blocks(R, D), sqnorm);
+    return sdp::launch_status();
 }

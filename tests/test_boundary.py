@@ -72,6 +72,17 @@ def test_argument_errors_are_caught_on_the_host():
     assert L.sdp_mask_rho2(65, 16, FAKE, FAKE, ctypes.byref(out), None) == -1
     assert L.sdp_mask_rho2(4, 0, FAKE, FAKE, ctypes.byref(out), None) == -1
     assert L.sdp_mask_rho2(4, 1 << 31, FAKE, FAKE, ctypes.byref(out), None) == -2
+    # squared norm of the average
+    ptrs2 = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    assert sdp.lib().sdp_coverage_grad_sqnorm_workspace_bytes(488282, 2048) >= 8
+    assert sdp.lib().sdp_coverage_grad_sqnorm_workspace_bytes(-1, 8) == 0
+    assert L.sdp_coverage_grad_sqnorm(0, 4, 16, 1, ptrs2, FAKE, FAKE, FAKE, big, None) == -1
+    assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 3, ptrs2, FAKE, FAKE, FAKE, big, None) == -1
+    assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 1, ptrs2, None, FAKE, FAKE, big, None) == -1
+    assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 1, ptrs2, FAKE, None, FAKE, big, None) == -1
+    assert L.sdp_coverage_grad_sqnorm(2, 1 << 38, 16, 1, ptrs2, FAKE, FAKE, FAKE, big, None) == -2
+    assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 1, ptrs2, FAKE, FAKE, None, big, None) == -3
+    assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 1, ptrs2, FAKE, FAKE, FAKE, ctypes.c_size_t(8), None) == -3
     # forward
     def fwd(mode=0, dt=1, T=16, d=16, F=32, p=16, X=FAKE, idx=FAKE, ws=FAKE, wsb=big):
         return L.sdp_masked_mlp_fwd(mode, dt, T, d, F, p, X, FAKE, FAKE, FAKE, idx, FAKE, FAKE, FAKE, ws, wsb, None)

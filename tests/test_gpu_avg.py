@@ -85,3 +85,43 @@ def test_avg_empty_input_and_binding_errors(sdp):
     assert out.shape == (0, 64) and cov.shape == (0,)
     with pytest.raises(sdp.SdpError):
         sdp.coverage_grad_avg([], torch.empty((0, 0), dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("K,R,D,p,dtype", [
+    (4, 300, 256, 150, "bf16"), (8, 1000, 2048, 690, "bf16"), (8, 257, 1536, 100, "f32"), (5, 40, 13, 20, "f32"),
+    (5, 40, 7, 20, "bf16"), (1, 10, 512, 4, "bf16"), (8, 40000, 512, 27600, "bf16"),
+])
+def test_squared_norm_of_the_average_matches_oracle(sdp, orc, K, R, D, p, dtype):
+    """sdp_coverage_grad_sqnorm against the oracle's fp64 sum; NaN in rows nobody covers is never read; the value
+    equals the norm of what sdp_coverage_grad_avg stores (same fp32 averages), and repeats bit for bit."""
+    print(f"sqnorm K={K} R={R} D={D} p={p} {dtype}", flush=True)
+    mask = orc.make_masks(K, R, p, 78, False)
+    tmask = torch.from_numpy(mask)
+    grads = workloads.grad_buffers(K, R, D, 1e-3, dtype, poison_mask=tmask)
+    dev = [g.cuda() for g in grads]
+    got = sdp.coverage_grad_sqnorm(dev, tmask.cuda())
+    again = sdp.coverage_grad_sqnorm(dev, tmask.cuda())
+    avg, _ = sdp.coverage_grad_avg(dev, tmask.cuda())
+    torch.cuda.synchronize()
+    want = orc.gated_average_sqnorm(_np_inputs(grads), mask)
+    got = float(got.cpu()[0])
+    assert np.isfinite(got) and got == float(again.cpu()[0])
+    assert abs(got - want) <= 1e-5 * want  # fp32 averages (relative error 1e-7 each), fp64 sum
+    stored = float((avg.double() ** 2).sum().cpu())
+    assert abs(got - stored) <= 1e-12 * stored
+
+
+def test_squared_norm_empty_and_errors(sdp):
+    import ctypes
+
+    L = sdp.lib()
+    out = torch.full((1,), 7.0, dtype=torch.float64, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    ptrs = (ctypes.c_void_p * 2)(None, None)
+    assert L.sdp_coverage_grad_sqnorm(2, 0, 16, 1, ptrs, None, out.data_ptr(), ws.data_ptr(), ws.numel(), None) == 0
+    torch.cuda.synchronize()
+    assert float(out.cpu()[0]) == 0.0
+    g = torch.zeros((4, 16), dtype=torch.bfloat16, device="cuda")
+    m = torch.ones((2, 4), dtype=torch.uint8, device="cuda")
+    with pytest.raises(RuntimeError):
+        sdp.coverage_grad_sqnorm([g, g], m, ws=torch.empty(16, dtype=torch.uint8, device="cuda")[:0])

@@ -115,6 +115,32 @@ def test_fullsize_config5_average_sampled(sdp, orc):
     assert_close(out[trows].cpu().numpy(), want, 1e-5, "config5 average (sampled rows)")
 
 
+def test_fullsize_config5_squared_norm(sdp, orc):
+    """The norm pass at config 5 in bench.py's launch configuration: it must equal the norm of the stored average
+    (whose elements the test above samples against the oracle) to fp64 summation error, repeat bit for bit, and
+    match the oracle's own norm on a slice of rows that the oracle finishes in seconds."""
+    c = workloads.CONFIG5
+    mask_host = sdp.sample_masks_host(c.K, c.R, c.p, c.mask_seed, False)
+    mask = mask_host.cuda()
+    grads = workloads.grad_buffers(c.K, c.R, c.D, c.sigma, "bf16", device="cuda")
+    print(f"fullsize sqnorm K={c.K} R={c.R} D={c.D}", flush=True)
+    a = sdp.coverage_grad_sqnorm(grads, mask)
+    b = sdp.coverage_grad_sqnorm(grads, mask)
+    out, cov = sdp.coverage_grad_avg(grads, mask)
+    torch.cuda.synchronize()
+    got = float(a.cpu()[0])
+    assert got == float(b.cpu()[0]) and got > 0.0
+    stored = 0.0
+    for r0 in range(0, c.R, 1 << 16):  # in pieces: an fp64 copy of the whole average would not be a small tensor
+        stored += float((out[r0:r0 + (1 << 16)].double() ** 2).sum().cpu())
+    assert abs(got - stored) <= 1e-11 * stored
+    rows = slice(1000, 3000)
+    part = sdp.coverage_grad_sqnorm([g[rows] for g in grads], mask[:, rows].contiguous())
+    torch.cuda.synchronize()
+    want = orc.gated_average_sqnorm([workloads.bf16_bits(g[rows]) for g in grads], mask_host[:, rows].numpy())
+    assert abs(float(part.cpu()[0]) - want) <= 1e-5 * want
+
+
 def test_fullsize_config5_adamw_sampled(sdp, orc):
     """The fused average + AdamW pass at the 1B-parameter size, sampled rows against the oracle."""
     c = workloads.CONFIG5

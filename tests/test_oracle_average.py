@@ -104,3 +104,36 @@ def test_sdp_step_at_coverage_one_equals_ddp(orc):
     for mode in grads:
         out, cov = orc.gated_average(grads[mode], ones)
         np.testing.assert_allclose(out, sum(dense) / K, rtol=1e-15, atol=1e-15)
+
+
+def test_squared_norm_of_the_average(orc):
+    """The quantity global gradient clipping measures (App. "Hyperparameters for LLM Architecture")."""
+    rng = np.random.default_rng(21)
+    K, R, D = 6, 40, 11
+    mask = (rng.random((K, R)) < 0.5).astype(np.uint8)
+    mask[:, :3] = 0  # rows nobody covers
+    g = [rng.standard_normal((R, D)) for _ in range(K)]
+    out, cov = orc.gated_average(g, mask)
+    got = orc.gated_average_sqnorm(g, mask)
+    # a library norm of the average that is pinned on its own above
+    assert abs(got - np.linalg.norm(out) ** 2) <= 1e-12 * got
+    # uncovered rows count for nothing, even when their buffers hold garbage
+    g2 = [a.copy() for a in g]
+    for a in g2:
+        a[:3] = np.nan
+    assert orc.gated_average_sqnorm(g2, mask) == got
+    # one worker that holds everything: the plain sum of squares; scaling the gradients by a scales it by a^2
+    assert abs(orc.gated_average_sqnorm(g[:1], np.ones((1, R), np.uint8)) - (g[0] ** 2).sum()) <= 1e-12 * (g[0] ** 2).sum()
+    assert abs(orc.gated_average_sqnorm([3.0 * a for a in g], mask) - 9.0 * got) <= 1e-12 * got
+    # constant gradients v on every covered row: v^2 D (number of covered rows), whatever the loads
+    const = [np.full((R, D), -1.5) for _ in range(K)]
+    assert abs(orc.gated_average_sqnorm(const, mask) - 2.25 * D * int((mask.sum(axis=0) > 0).sum())) < 1e-9
+    # hand-computed: two workers, rows of load 2, 1, 0
+    m = np.array([[1, 1, 0], [1, 0, 0]], dtype=np.uint8)
+    a = [np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]]), np.array([[3.0, 0.0], [7.0, 7.0], [7.0, 7.0]])]
+    # averages: row 0 -> (2, 1), row 1 -> (3, 4), row 2 -> 0
+    assert orc.gated_average_sqnorm(a, m) == 4.0 + 1.0 + 9.0 + 16.0
+    # bf16 bit patterns widen exactly
+    gb = [np.asarray(_bf16_bits(x)) for x in g]
+    gw = [torch.from_numpy(np.asarray(x, dtype=np.float32)).to(torch.bfloat16).double().numpy() for x in g]
+    assert orc.gated_average_sqnorm(gb, mask) == orc.gated_average_sqnorm(gw, mask)
