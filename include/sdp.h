@@ -231,8 +231,8 @@ int sdp_coverage_grad_avg(int K, int64_t R, int D, int gdtype, const void* const
  *     theta <- theta - lr / (1 - beta1^t) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps)
  * (decoupled weight decay, bias-corrected moments, t = step >= 1), all in fp32.  Rows with c_r = 0 are
  * left untouched: no gradient reached them, and neither decay nor moment update is applied.
- * grad_scale carries a clipping coefficient computed elsewhere (1 = none).  The averaged gradient
- * itself is not stored.
+ * grad_scale (host value) times *grad_scale_dev (device value, if given) scales the gradient: a loss scale
+ * and / or the clipping coefficient (1 = none).  The averaged gradient itself is not stored.
  *   g, mask, cov   as for sdp_coverage_grad_avg
  *   theta, m, v    [R][D] fp32, updated in place (each row read and written once)
  *   theta_bf16     [R][D] bf16 out, may be NULL: the updated parameters rounded to nearest even, i.e.
@@ -243,6 +243,9 @@ int sdp_coverage_grad_avg(int K, int64_t R, int D, int gdtype, const void* const
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay, grad_scale;
     int step; /* t, counted from 1 */
+    const float* grad_scale_dev; /* device, may be NULL: a second factor of the gradient's scale, read by the
+                                    kernel (e.g. the coefficient sdp_clip_scale wrote), so that clipping needs
+                                    no round trip to the host; 4-byte aligned */
 } sdp_adamw_params;
 int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
                            float* theta, float* m, float* v, void* theta_bf16, uint8_t* cov,
@@ -264,6 +267,12 @@ int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const void* cons
 size_t sdp_coverage_grad_sqnorm_workspace_bytes(int64_t R, int D);
 int sdp_coverage_grad_sqnorm(int K, int64_t R, int D, int gdtype, const void* const* g, const uint8_t* mask,
                              double* sqnorm, void* ws, size_t ws_bytes, void* stream);
+
+/* Clipping coefficient of global-norm clipping from the squared norms of n parameter groups (each from
+ * sdp_coverage_grad_sqnorm): *scale = min(1, max_norm / (sqrt(sum_i sqnorm[i]) + 1e-6)), the usual form
+ * (the paper states only the threshold, 1.0).  sqnorm: device [n] fp64; scale: device fp32 out, to be passed
+ * as grad_scale_dev.  Errors: INVALID_ARG (null, misaligned, n < 1, max_norm not positive and finite). */
+int sdp_clip_scale(int n, const double* sqnorm, float max_norm, float* scale, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Per-kernel timing.  With profiling on, every kernel launch is bracketed by HIP events on its

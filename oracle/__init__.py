@@ -69,6 +69,8 @@ def lib():
         L.orc_gated_average_sqnorm.argtypes = [
             ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), _u8p,
         ]
+        L.orc_clip_scale.restype = ctypes.c_double
+        L.orc_clip_scale.argtypes = [ctypes.c_int, _f64p, ctypes.c_double]
         L.orc_attn_fwd.restype = None
         L.orc_attn_fwd.argtypes = [ctypes.c_int64] * 5 + [_f64p] * 10
         L.orc_attn_bwd.restype = None
@@ -216,6 +218,12 @@ def gated_average_sqnorm(g_list, mask):
         assert g.shape == (R, D) and g.dtype == dt
     ptrs = (ctypes.c_void_p * K)(*[g.ctypes.data for g in g_list])
     return float(lib().orc_gated_average_sqnorm(K, R, D, gtype, ptrs, _p(mask, _u8p)))
+
+
+def clip_scale(sqnorms, max_norm):
+    """Coefficient of global-norm clipping from the groups' squared norms; see orc_clip_scale."""
+    sq = np.ascontiguousarray(sqnorms, dtype=np.float64).reshape(-1)
+    return float(lib().orc_clip_scale(sq.size, _p(sq, _f64p), float(max_norm)))
 
 
 def avg_adamw(g_list, mask, theta, m, v, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0):

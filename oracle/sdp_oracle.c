@@ -408,6 +408,16 @@ double orc_gated_average_sqnorm(int K, int64_t R, int64_t D, int gtype, const vo
     return total;
 }
 
+/* Coefficient of global-norm clipping at max_norm (the paper states the       */
+/* threshold only; this is the usual form): min(1, max_norm / (norm + 1e-6)),  */
+/* norm^2 = the sum of the parameter groups' squared norms.                     */
+double orc_clip_scale(int n, const double* sqnorm, double max_norm) {
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) total += sqnorm[i];
+    const double coef = max_norm / (sqrt(total) + 1e-6);
+    return coef < 1.0 ? coef : 1.0;
+}
+
 /* ------------------------------------------------------------------------- */
 /* The gated average followed by the optimizer the paper trains with (AdamW,   */
 /* App. "Hyperparameters for LLM Architecture"), on covered rows only         */

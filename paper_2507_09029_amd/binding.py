@@ -80,6 +80,8 @@ def lib():
     L.sdp_coverage_grad_sqnorm_workspace_bytes.argtypes = [i64, i32]
     L.sdp_coverage_grad_sqnorm.restype = i32
     L.sdp_coverage_grad_sqnorm.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, sz, vp]
+    L.sdp_clip_scale.restype = i32
+    L.sdp_clip_scale.argtypes = [i32, vp, ctypes.c_float, vp, vp]
     L.sdp_coverage_avg_adamw.restype = i32
     L.sdp_coverage_avg_adamw.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp, vp, vp, vp, vp]
     L.sdp_profile_enable.restype = i32
@@ -352,11 +354,22 @@ def coverage_grad_sqnorm(grads, mask, out=None, ws=None):
 
 class AdamWParams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
-                ("weight_decay", ctypes.c_float), ("grad_scale", ctypes.c_float), ("step", ctypes.c_int)]
+                ("weight_decay", ctypes.c_float), ("grad_scale", ctypes.c_float), ("step", ctypes.c_int),
+                ("grad_scale_dev", ctypes.c_void_p)]
+
+
+def clip_scale(sqnorms, max_norm, out=None):
+    """sqnorms: fp64 GPU tensor [n] of squared norms -> fp32 GPU tensor [1]: min(1, max_norm / (sqrt(sum) + 1e-6))."""
+    if out is None:
+        out = torch.empty((1,), dtype=torch.float32, device=sqnorms.device)
+    st = lib().sdp_clip_scale(sqnorms.numel(), _dev(sqnorms, torch.float64, "sqnorms"), max_norm,
+                              _dev(out, torch.float32, "scale"), _stream())
+    _check(st, "sdp_clip_scale")
+    return out
 
 
 def coverage_avg_adamw(grads, mask, theta, m, v, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0,
-                       theta_bf16=None, cov=None):
+                       theta_bf16=None, cov=None, grad_scale_dev=None):
     """Coverage average fused with AdamW on covered rows: theta, m, v (fp32 [R][D]) are updated in place.
 
     theta_bf16 (optional bf16 [R][D]) receives the updated parameters of covered rows.  Returns cov u8 [R].
@@ -374,7 +387,8 @@ def coverage_avg_adamw(grads, mask, theta, m, v, lr, beta1, beta2, eps, weight_d
         raise ValueError("mask must be [K][R]")
     if cov is None:
         cov = torch.empty((R,), dtype=torch.uint8, device=grads[0].device)
-    hp = AdamWParams(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+    hp = AdamWParams(lr, beta1, beta2, eps, weight_decay, grad_scale, step,
+                     _dev(grad_scale_dev, torch.float32, "grad_scale_dev") if grad_scale_dev is not None else None)
     lowp = _dev(theta_bf16, torch.bfloat16, "theta_bf16") if theta_bf16 is not None else None
     st = lib().sdp_coverage_avg_adamw(K, R, D, _DTYPES[dt], ptrs, _dev(mask, torch.uint8, "mask"),
                                       _dev(theta, torch.float32, "theta"), _dev(m, torch.float32, "m"),

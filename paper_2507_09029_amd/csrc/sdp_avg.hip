@@ -33,6 +33,7 @@ struct AdamArgs {
     float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^t)
     float eps;
     float grad_scale;
+    const float* grad_scale_dev; // optional second factor, read from device memory by every workgroup
     double* partial;      // OPT = 2: one partial sum of squares per workgroup
 };
 
@@ -49,6 +50,15 @@ __device__ inline double block_sum(double x) {
     return ((wave_sums[0] + wave_sums[1]) + wave_sums[2]) + wave_sums[3];
 }
 
+// clipping coefficient from n squared norms: min(1, max_norm / (sqrt(sum) + 1e-6)); one thread, n is small
+__global__ void clip_scale_kernel(const double* __restrict__ sqnorm, int n, double max_norm, float* __restrict__ scale) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) total += sqnorm[i];
+    const double coef = max_norm / (sqrt(total) + 1e-6);
+    *scale = (float)(coef < 1.0 ? coef : 1.0);
+}
+
 // partial sums of the workgroups -> one number, again in a fixed order
 __global__ __launch_bounds__(256) void sqnorm_finish_kernel(const double* __restrict__ partial, int n, double* __restrict__ out) {
     double x = 0.0;
@@ -63,9 +73,9 @@ __device__ inline uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, p);
 }
 
-// one parameter: (theta, m, v) <- AdamW(theta, m, v, g)
-__device__ inline void adamw_one(const AdamArgs& a, float g, float& th, float& m, float& v) {
-    g *= a.grad_scale;
+// one parameter: (theta, m, v) <- AdamW(theta, m, v, g); gs = the gradient's scale
+__device__ inline void adamw_one(const AdamArgs& a, float gs, float g, float& th, float& m, float& v) {
+    g *= gs;
     th *= a.decay;
     m = a.beta1 * m + (1.0f - a.beta1) * g;
     v = a.beta2 * v + (1.0f - a.beta2) * g * g;
@@ -102,6 +112,8 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     double sq = 0.0; // OPT_SQNORM: this lane's share of the sum of squares
+    float gs = ad.grad_scale;
+    if (OPT == OPT_ADAMW && ad.grad_scale_dev) gs *= *ad.grad_scale_dev;
     for (int64_t item = wave0; item < nitems; item += nwaves) {
         const int64_t r = item / segs;
         const int seg = (int)(item - r * segs);
@@ -185,7 +197,7 @@ __global__ __launch_bounds__(256) void avg_rows_kernel(GradPtrs g, const uint8_t
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float t = th[h][i], m1 = mm[h][i], v1 = vv[h][i];
-                    adamw_one(ad, acc[4 * h + i] / denom, t, m1, v1);
+                    adamw_one(ad, gs, acc[4 * h + i] / denom, t, m1, v1);
                     th[h][i] = t, mm[h][i] = m1, vv[h][i] = v1;
                 }
 #pragma unroll
@@ -215,6 +227,8 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
                                                         AdamArgs ad) {
     const int64_t n = R * D;
     double sq = 0.0;
+    float gs = ad.grad_scale;
+    if (OPT == OPT_ADAMW && ad.grad_scale_dev) gs *= *ad.grad_scale_dev;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = i / D;
         float acc = 0.f;
@@ -236,7 +250,7 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
             }
         } else if (c > 0) {
             float t = ad.theta[i], m1 = ad.m[i], v1 = ad.v[i];
-            adamw_one(ad, acc / (float)c, t, m1, v1);
+            adamw_one(ad, gs, acc / (float)c, t, m1, v1);
             ad.theta[i] = t, ad.m[i] = m1, ad.v[i] = v1;
             if (ad.theta_bf16) ad.theta_bf16[i] = (uint16_t)(pack2_bf16(t, 0.f) & 0xFFFFu);
         }
@@ -327,10 +341,12 @@ extern "C" int sdp_coverage_avg_adamw(int K, int64_t R, int D, int gdtype, const
     if (R > ((int64_t)1 << 40) / D) return SDP_ERR_SHAPE;
     for (const void* q : {(const void*)theta, (const void*)m, (const void*)v, (const void*)theta_bf16})
         if (q && !sdp::aligned16(q)) return SDP_ERR_INVALID_ARG;
+    if ((uintptr_t)hp->grad_scale_dev & 3) return SDP_ERR_INVALID_ARG;
     AdamArgs a;
     a.theta = theta, a.m = m, a.v = v, a.theta_bf16 = (uint16_t*)theta_bf16;
     a.decay = 1.0f - hp->lr * hp->weight_decay;
     a.beta1 = hp->beta1, a.beta2 = hp->beta2, a.eps = hp->eps, a.grad_scale = hp->grad_scale;
+    a.grad_scale_dev = hp->grad_scale_dev, a.partial = nullptr;
     // bias corrections in double on the host (beta^t loses digits in fp32 for large t)
     a.step_size = (float)((double)hp->lr / (1.0 - std::pow((double)hp->beta1, (double)hp->step)));
     a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)hp->beta2, (double)hp->step)));
@@ -360,5 +376,12 @@ extern "C" int sdp_coverage_grad_sqnorm(int K, int64_t R, int D, int gdtype, con
     int rc = launch_average(K, R, D, gdtype, g, mask, nullptr, nullptr, &a, "coverage_grad_sqnorm", s, true);
     if (rc != SDP_OK) return rc;
     sqnorm_finish_kernel<<<1, 256, 0, s>>>((const double*)ws, (int)norm_blocks(R, D), sqnorm);
+    return sdp::launch_status();
+}
+
+extern "C" int sdp_clip_scale(int n, const double* sqnorm, float max_norm, float* scale, void* stream) {
+    if (n < 1 || n > (1 << 20) || !sqnorm || !scale || !(max_norm > 0.f) || !std::isfinite(max_norm)) return SDP_ERR_INVALID_ARG;
+    if (((uintptr_t)sqnorm & 7) || ((uintptr_t)scale & 3)) return SDP_ERR_INVALID_ARG;
+    clip_scale_kernel<<<1, 64, 0, (hipStream_t)stream>>>(sqnorm, n, (double)max_norm, scale);
     return sdp::launch_status();
 }

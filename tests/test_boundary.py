@@ -83,6 +83,12 @@ def test_argument_errors_are_caught_on_the_host():
     assert L.sdp_coverage_grad_sqnorm(2, 1 << 38, 16, 1, ptrs2, FAKE, FAKE, FAKE, big, None) == -2
     assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 1, ptrs2, FAKE, FAKE, None, big, None) == -3
     assert L.sdp_coverage_grad_sqnorm(2, 4, 16, 1, ptrs2, FAKE, FAKE, FAKE, ctypes.c_size_t(8), None) == -3
+    # clip coefficient
+    assert L.sdp_clip_scale(0, FAKE, ctypes.c_float(1.0), FAKE, None) == -1
+    assert L.sdp_clip_scale(2, None, ctypes.c_float(1.0), FAKE, None) == -1
+    assert L.sdp_clip_scale(2, FAKE, ctypes.c_float(1.0), None, None) == -1
+    assert L.sdp_clip_scale(2, FAKE, ctypes.c_float(0.0), FAKE, None) == -1
+    assert L.sdp_clip_scale(2, ctypes.c_void_p(0x1004), ctypes.c_float(1.0), FAKE, None) == -1
     # forward
     def fwd(mode=0, dt=1, T=16, d=16, F=32, p=16, X=FAKE, idx=FAKE, ws=FAKE, wsb=big):
         return L.sdp_masked_mlp_fwd(mode, dt, T, d, F, p, X, FAKE, FAKE, FAKE, idx, FAKE, FAKE, FAKE, ws, wsb, None)

@@ -72,3 +72,45 @@ def test_adamw_argument_errors(sdp):
             sdp.coverage_avg_adamw(g, mask, th, m, v, step=1, **bad)
     with pytest.raises(sdp.SdpError):
         sdp.coverage_avg_adamw(g, mask, th, m, v, step=0, **HP)
+
+
+@pytest.mark.parametrize("max_norm,gscale", [(1.0, 30.0), (1.0, 1e-3)])
+def test_clipped_update_on_the_device_matches_oracle(sdp, orc, max_norm, gscale):
+    """Global-norm clipping without a round trip to the host: squared norms of two parameter groups ->
+    sdp_clip_scale -> the fused update reads the coefficient from device memory.  Gradient scale 30 puts the
+    norm far above the threshold (coefficient < 1), 1e-3 far below (coefficient 1)."""
+    K, D = 4, 256
+    groups = []
+    for gi, (R, p) in enumerate(((300, 150), (77, 40))):
+        mask = orc.make_masks(K, R, p, 90 + gi, False)
+        grads = workloads.grad_buffers(K, R, D, gscale, "bf16", poison_mask=torch.from_numpy(mask))
+        groups.append((R, mask, grads))
+    sq = torch.zeros((2,), dtype=torch.float64, device="cuda")
+    for gi, (R, mask, grads) in enumerate(groups):
+        sdp.coverage_grad_sqnorm([g.cuda() for g in grads], torch.from_numpy(mask).cuda(), out=sq[gi:gi + 1])
+    scale = sdp.clip_scale(sq, max_norm)
+    want_sq = [orc.gated_average_sqnorm([workloads.bf16_bits(g) for g in grads], mask) for R, mask, grads in groups]
+    want_scale = orc.clip_scale(want_sq, max_norm)
+    torch.cuda.synchronize()
+    assert (want_scale < 0.5) == (gscale > 1.0) and (want_scale == 1.0) == (gscale < 1.0)
+    assert abs(float(scale.cpu()[0]) - want_scale) <= 1e-5 * want_scale
+    for gi, (R, mask, grads) in enumerate(groups):
+        theta, m, v = _state(R, D, 11 + gi)
+        dth, dm, dv = theta.cuda(), m.cuda(), v.cuda()
+        sdp.coverage_avg_adamw([g.cuda() for g in grads], torch.from_numpy(mask).cuda(), dth, dm, dv, step=3,
+                               grad_scale_dev=scale, **HP)
+        torch.cuda.synchronize()
+        wth, wm, wv, wcov = orc.avg_adamw([workloads.bf16_bits(g) for g in grads], mask, theta.numpy(), m.numpy(), v.numpy(),
+                                          step=3, grad_scale=want_scale, **HP)
+        assert_close(dm.cpu().numpy(), wm, TOL, "m")
+        assert_close(dv.cpu().numpy(), wv, 2 * TOL, "v")  # the coefficient's own 1e-5 enters squared
+        assert_close(dth.cpu().numpy(), wth, TOL, "theta")
+
+
+def test_clip_scale_argument_errors(sdp):
+    sq = torch.ones((2,), dtype=torch.float64, device="cuda")
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        with pytest.raises(sdp.SdpError):
+            sdp.clip_scale(sq, bad)
+    with pytest.raises(sdp.SdpError):
+        sdp.clip_scale(sq[:0], 1.0)

@@ -89,3 +89,21 @@ def test_bf16_inputs_are_widened_exactly(orc):
     b = orc.avg_adamw([g32.to(torch.float64).numpy()], one, theta0, z, z, step=1, **HP)
     for x, y in zip(a[:3], b[:3]):
         assert (x == y).all()
+
+
+def test_clip_coefficient_matches_the_library_routine(orc):
+    """orc_clip_scale against torch.nn.utils.clip_grad_norm_ on two parameter groups, above and below the
+    threshold (the paper states the threshold, 1.0; the form of the coefficient is the usual one)."""
+    rng = np.random.default_rng(31)
+    for scale in (5.0, 1e-3):
+        ga, gb = rng.standard_normal((7, 5)) * scale, rng.standard_normal((3, 11)) * scale
+        pa, pb = torch.zeros((7, 5), dtype=torch.float64, requires_grad=True), torch.zeros((3, 11), dtype=torch.float64, requires_grad=True)
+        pa.grad, pb.grad = torch.from_numpy(ga.copy()), torch.from_numpy(gb.copy())
+        total = torch.nn.utils.clip_grad_norm_([pa, pb], max_norm=1.0)
+        coef = orc.clip_scale([(ga ** 2).sum(), (gb ** 2).sum()], 1.0)
+        assert abs(float(total) ** 2 - ((ga ** 2).sum() + (gb ** 2).sum())) <= 1e-12 * float(total) ** 2
+        np.testing.assert_allclose(pa.grad.numpy(), coef * ga, rtol=1e-12, atol=0)
+        np.testing.assert_allclose(pb.grad.numpy(), coef * gb, rtol=1e-12, atol=0)
+        assert (coef == 1.0) == (scale < 1.0)
+    assert orc.clip_scale([0.0], 1.0) == 1.0  # a zero gradient is left alone
+    assert abs(orc.clip_scale([4.0, 12.0], 2.0) - 2.0 / (4.0 + 1e-6)) < 1e-15
