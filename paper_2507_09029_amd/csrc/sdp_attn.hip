@@ -1,6 +1,8 @@
 // One worker's attention block under head-level masks (the paper's Sec. 4.1: the neuron-level variant of
 // Sec. 3.2 masks attention heads on W_Q, W_K, W_V and W_O), forward masking (Sec. 3.1): the block is
-// evaluated at the gated parameters, i.e. as the smaller dense block made of the worker's ph heads.
+// evaluated at the gated parameters, i.e. as the smaller dense block made of the worker's ph heads.  Under
+// backward masking the block runs on all H heads without gather lists, and only the weight-gradient
+// contraction is restricted to the held heads' rows (row gather on its left operand).
 //
 // With E = ph * hd, rows_qkv = the 3 E rows of [Wq; Wk; Wv] that belong to the held heads and rows_o the E
 // rows of WoT (columns of W_O):
