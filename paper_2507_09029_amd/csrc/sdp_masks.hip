@@ -298,6 +298,55 @@ __global__ __launch_bounds__(256) void load_histogram_kernel(const uint8_t* __re
         if (local[i]) atomicAdd(&hist[i], (unsigned long long)local[i]);
 }
 
+// Short rows (at most kFusedChunks chunks): everything in one launch.  Workgroup k < K walks worker k's row
+// chunk by chunk, carrying the running count (no second kernel, no table of chunk counts); the workgroups
+// after those compute the coverage counts of 256 neurons each.
+constexpr int kFusedChunks = 16;
+__global__ __launch_bounds__(kScanThreads) void index_short_rows_kernel(const uint8_t* __restrict__ mask, int K, int64_t F,
+                                                                        int nchunks, int32_t* __restrict__ idx, int64_t idx_ld,
+                                                                        int32_t* __restrict__ pos, int32_t* __restrict__ count,
+                                                                        uint8_t* __restrict__ cov) {
+    __shared__ int lds[kScanThreads / 64 + 1];
+    if ((int)blockIdx.x >= K) {
+        const int64_t j = (int64_t)(blockIdx.x - K) * kScanThreads + threadIdx.x;
+        if (j >= F) return;
+        int c = 0;
+        for (int k = 0; k < K; ++k) c += mask[(int64_t)k * F + j] != 0;
+        cov[j] = (uint8_t)c;
+        return;
+    }
+    const int k = blockIdx.x;
+    const uint8_t* row = mask + (int64_t)k * F;
+    int base = 0;
+    for (int c = 0; c < nchunks; ++c) {
+        const int64_t j0 = (int64_t)c * kChunk + (int64_t)threadIdx.x * kPerThread;
+        uint8_t bits[kPerThread];
+        int n = 0;
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            bits[i] = (j0 + i < F) ? (row[j0 + i] != 0) : 0;
+            n += bits[i];
+        }
+        int total;
+        int rank = base + block_exclusive_scan(n, &total, lds);
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            if (j0 + i >= F) break;
+            if (bits[i]) {
+                pos[(int64_t)k * F + j0 + i] = rank;
+                if (rank < idx_ld) idx[(int64_t)k * idx_ld + rank] = (int32_t)(j0 + i);
+                ++rank;
+            } else {
+                pos[(int64_t)k * F + j0 + i] = -1;
+            }
+        }
+        base += total;
+    }
+    // the tail of the idx row (entries count .. idx_ld) is -1
+    for (int64_t t = (int64_t)base + threadIdx.x; t < idx_ld; t += kScanThreads) idx[(int64_t)k * idx_ld + t] = -1;
+    if (threadIdx.x == 0 && count) count[k] = base;
+}
+
 int check_index_args(int K, int64_t F, const void* mask, const void* idx, int64_t idx_ld, const void* pos,
                      const void* cov, const void* ws, size_t ws_bytes) {
     if (!mask || !idx || !pos || !cov) return SDP_ERR_INVALID_ARG;
@@ -321,6 +370,12 @@ extern "C" int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* i
     if (rc != SDP_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     const int nchunks = (int)((F + kChunk - 1) / kChunk);
+    if (nchunks <= kFusedChunks) {
+        sdp::ProfileScope ps("mask_index", s);
+        const unsigned blocks = (unsigned)(K + (F + kScanThreads - 1) / kScanThreads);
+        index_short_rows_kernel<<<blocks, kScanThreads, 0, s>>>(mask, K, F, nchunks, idx, idx_ld, pos, count, cov);
+        return sdp::launch_status();
+    }
     int32_t* chunk_cnt = (int32_t*)ws;
     {
         sdp::ProfileScope ps("mask_chunk_count", s);
