@@ -61,9 +61,12 @@ __global__ void clip_scale_kernel(const double* __restrict__ sqnorm, int n, doub
 
 // partial sums of the workgroups -> one number, again in a fixed order
 __global__ __launch_bounds__(256) void sqnorm_finish_kernel(const double* __restrict__ partial, int n, double* __restrict__ out) {
-    double x = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256) x += partial[i];
-    x = block_sum(x);
+    // four independent running sums per thread keep four loads in flight; the order of the additions is fixed
+    double x0 = 0.0, x1 = 0.0, x2 = 0.0, x3 = 0.0;
+    int i = threadIdx.x;
+    for (; i + 768 < n; i += 1024) x0 += partial[i], x1 += partial[i + 256], x2 += partial[i + 512], x3 += partial[i + 768];
+    for (; i < n; i += 256) x0 += partial[i];
+    double x = block_sum((x0 + x1) + (x2 + x3));
     if (threadIdx.x == 0) *out = x;
 }
 
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(256) void avg_elems_kernel(GradPtrs g, const uint8_
 }
 
 // workgroups of the norm pass: enough to keep every CU's queue full, few enough for a small table of partial sums
-constexpr int64_t kNormBlocks = 1 << 15;
+constexpr int64_t kNormBlocks = 1 << 13;
 int64_t norm_blocks(int64_t R, int D) {
     const int64_t want = D % 8 == 0 ? (R * ((D + 511) / 512) + 3) / 4 : (R * D + 255) / 256;
     return want < 1 ? 1 : (want < kNormBlocks ? want : kNormBlocks);
@@ -373,7 +376,8 @@ extern "C" int sdp_coverage_grad_sqnorm(int K, int64_t R, int D, int gdtype, con
         sqnorm_finish_kernel<<<1, 256, 0, s>>>((const double*)ws, 0, sqnorm);
         return sdp::launch_status();
     }
-    int rc = launch_average(K, R, D, gdtype, g, mask, nullptr, nullptr, &a, "coverage_grad_sqnorm", s, true);
+    sdp::ProfileScope ps("coverage_grad_sqnorm", s); // both kernels
+    int rc = launch_average(K, R, D, gdtype, g, mask, nullptr, nullptr, &a, nullptr, s, true);
     if (rc != SDP_OK) return rc;
     sqnorm_finish_kernel<<<1, 256, 0, s>>>((const double*)ws, (int)norm_blocks(R, D), sqnorm);
     return sdp::launch_status();

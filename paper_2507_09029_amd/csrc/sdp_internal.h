@@ -18,7 +18,7 @@ void profile_end(hipStream_t s);
 struct ProfileScope {
     hipStream_t s;
     bool on;
-    ProfileScope(const char* name, hipStream_t stream) : s(stream), on(profiling_on() && profiling_wants(name)) {
+    ProfileScope(const char* name, hipStream_t stream) : s(stream), on(name && profiling_on() && profiling_wants(name)) {
         if (on) profile_begin(name, s);
     }
     ~ProfileScope() {
