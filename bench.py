@@ -35,7 +35,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("config2_bf16_fm_500M", "mlp_down"): 84.0e6 + 25.2e6,
     ("config2_bf16_fm_500M", "mlp_dact"): 143.2e6 + 167.9e6,
     ("config2_bf16_fm_500M", "mlp_dx"): 167.9e6 + 25.2e6,
-    ("config2_bf16_fm_500M", "mlp_dw"): 402.8e6 + 18.9e6,
+    ("config2_bf16_fm_500M", "mlp_dw"): 328.1e6 + 18.9e6,
     ("config5_avg_1B", "coverage_grad_avg"): 11.071e9 + 4.293e9,
 }
 
