@@ -78,7 +78,7 @@ struct Dev {
     int pc;
     int tiles_m, tiles_n, ntot; // ntot = tiles of all problems of the launch
     int group_m, nbatch;
-    int np0; // OP_DW: > 0 = the first np0 problems share one B operand and the others another (see tile_of_shared)
+    int np0; // batched launches: > 0 = the first np0 problems share one B operand and the others another (see tile_of_shared)
     // batched launch (weight gradients): problem z uses Ab[z], Bb[z], Cb[z]
     const uint16_t *Ab[kMaxBatch], *Bb[kMaxBatch];
     uint16_t* Cb[kMaxBatch];
@@ -105,11 +105,14 @@ __device__ __attribute__((aligned(256))) const uint32_t kZeroChunk[64] = {0};
 // X^T, Act^T against dY^T).  Problems that share B are stacked into one matrix of (problems x tiles_m)
 // tile-rows, and each such stack is walked like a single problem: group_m tile-rows at a time, down the rows
 // first, then along the tile-columns.  The tiles that run together on one XCD then touch fewer distinct operand
-// rows than with the problems interleaved tile by tile.  Stack 0 = problems [0, np0), stack 1 = the rest.
-__host__ __device__ inline void tile_of_shared(int lin, int tiles_m, int tiles_n, int np0, int nbatch, int group_m,
-                                               int& batch, int& tile_m, int& tile_n) {
+// rows than with the problems interleaved tile by tile.  Per depth range (ksplit > 1: OP_DW_SPLIT) there are two
+// stacks, problems [0, np0) and the rest; the ranges follow one another.  `batch` returns range * nbatch + problem.
+__host__ __device__ inline void tile_of_shared(int lin, int tiles_m, int tiles_n, int np0, int nbatch, int ksplit,
+                                               int group_m, int& batch, int& tile_m, int& tile_n) {
+    const int n0 = np0 * tiles_m * tiles_n, n1 = (nbatch - np0) * tiles_m * tiles_n;
+    const int range = lin / (n0 + n1);
+    lin -= range * (n0 + n1);
     int first_problem = 0, stack = np0;
-    const int n0 = np0 * tiles_m * tiles_n;
     if (lin >= n0) lin -= n0, first_problem = np0, stack = nbatch - np0;
     const int rows = stack * tiles_m;
     const int per_group = group_m * tiles_n;
@@ -119,8 +122,9 @@ __host__ __device__ inline void tile_of_shared(int lin, int tiles_m, int tiles_n
     const int in = lin - grp * per_group;
     const int v = first + in % gm;
     tile_n = in / gm;
-    batch = first_problem + v / tiles_m;
+    batch = range * nbatch + first_problem + v / tiles_m;
     tile_m = v % tiles_m;
+    (void)ksplit;
 }
 
 // s_waitcnt vmcnt(n) alone (expcnt / lgkmcnt left at their maxima), gfx9 encoding
@@ -178,8 +182,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     constexpr bool kSplit = OP == OP_DW_SPLIT;
     const int nb = kBatched ? g.nbatch * (kSplit ? g.ksplit : 1) : 1;
     int tile_m, tile_n, batch;
-    if (OP == OP_DW && g.np0 > 0) {
-        tile_of_shared(bid, g.tiles_m, g.tiles_n, g.np0, g.nbatch, g.group_m, batch, tile_m, tile_n);
+    if (kBatched && g.np0 > 0) {
+        tile_of_shared(bid, g.tiles_m, g.tiles_n, g.np0, g.nbatch, g.ksplit, g.group_m, batch, tile_m, tile_n);
     } else {
         const int per_group = g.group_m * g.tiles_n * nb;
         const int grp = bid / per_group;
@@ -636,13 +640,13 @@ int choose_group_m(int tiles_m, int tiles_n, int nbatch, int na, int nb, int bm,
 
 // group_m of the stacked order (tile_of_shared): the one whose first round of resident tiles (each XCD's range,
 // at most one tile per CU) touches the fewest operand bytes, counted by walking that very order.
-int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int bm, int bn) {
-    const int ntot = tiles_m * tiles_n * nbatch;
+int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int ksplit, int bm, int bn) {
+    const int ntot = tiles_m * tiles_n * nbatch * ksplit;
     const int per_xcd = kNumCU / NUM_XCD;
     const int max_rows = (np0 > nbatch - np0 ? np0 : nbatch - np0) * tiles_m;
     int best = 1;
     int64_t best_cost = -1;
-    std::vector<char> seen_a((size_t)nbatch * tiles_m), seen_b((size_t)2 * tiles_n);
+    std::vector<char> seen_a((size_t)ksplit * nbatch * tiles_m), seen_b((size_t)ksplit * 2 * tiles_n);
     for (int gm = 1; gm <= max_rows && gm <= 2 * per_xcd; ++gm) {
         int64_t cost = 0;
         for (int x = 0; x < NUM_XCD; ++x) {
@@ -654,9 +658,10 @@ int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int bm, i
             std::fill(seen_b.begin(), seen_b.end(), 0);
             for (int lin = start; lin < start + count; ++lin) {
                 int b, tm, tn;
-                tile_of_shared(lin, tiles_m, tiles_n, np0, nbatch, gm, b, tm, tn);
+                tile_of_shared(lin, tiles_m, tiles_n, np0, nbatch, ksplit, gm, b, tm, tn);
+                const int range = b / nbatch, z = b % nbatch; // a depth range reads its own part of every row
                 char& a = seen_a[(size_t)b * tiles_m + tm];
-                char& bb = seen_b[(size_t)(b < np0 ? 0 : 1) * tiles_n + tn];
+                char& bb = seen_b[((size_t)range * 2 + (z < np0 ? 0 : 1)) * tiles_n + tn];
                 if (!a) a = 1, cost += bm;
                 if (!bb) bb = 1, cost += bn;
             }
@@ -706,7 +711,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     }
     g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na * ksplit, nbo * ksplit, BM, BN);
     g.np0 = 0;
-    if (OP == OP_DW && d.nbatch > 1 && nbo <= 2 && !getenv("SDP_PLAIN_ORDER")) {
+    if (kBatched && d.nbatch > 1 && nbo <= 2 && !getenv("SDP_PLAIN_ORDER")) {
         // problems that share B must be neighbours: [0, np0) on Bb[0], the rest on one other operand (or none)
         int np0 = 1;
         while (np0 < d.nbatch && d.Bb[np0] == d.Bb[0]) ++np0;
@@ -714,7 +719,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
         for (int z = np0; z < d.nbatch; ++z) ok = ok && d.Bb[z] == d.Bb[np0] && d.Bb[z] != d.Bb[0];
         if (ok) {
             g.np0 = np0;
-            g.group_m = choose_group_shared(g.tiles_m, g.tiles_n, np0, d.nbatch, BM, BN);
+            g.group_m = choose_group_shared(g.tiles_m, g.tiles_n, np0, d.nbatch, ksplit, BM, BN);
         }
     }
     if (const char* e = getenv("SDP_GROUP_M")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
