@@ -711,6 +711,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     }
     g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na * ksplit, nbo * ksplit, BM, BN);
     g.np0 = 0;
+    // SDP_PLAIN_ORDER in the environment keeps the problems interleaved tile by tile (comparison runs)
     if (kBatched && d.nbatch > 1 && nbo <= 2 && !getenv("SDP_PLAIN_ORDER")) {
         // problems that share B must be neighbours: [0, np0) on Bb[0], the rest on one other operand (or none)
         int np0 = 1;
