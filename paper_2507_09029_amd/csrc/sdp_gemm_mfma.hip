@@ -42,7 +42,10 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <array>
 #include <cstdlib>
+#include <map>
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -641,6 +644,15 @@ int choose_group_m(int tiles_m, int tiles_n, int nbatch, int na, int nb, int bm,
 // group_m of the stacked order (tile_of_shared): the one whose first round of resident tiles (each XCD's range,
 // at most one tile per CU) touches the fewest operand bytes, counted by walking that very order.
 int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int ksplit, int bm, int bn) {
+    // the walk costs a fraction of a millisecond of host time: remembered per shape
+    static std::mutex mu;
+    static std::map<std::array<int, 7>, int> known;
+    const std::array<int, 7> key = {tiles_m, tiles_n, np0, nbatch, ksplit, bm, bn};
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        auto it = known.find(key);
+        if (it != known.end()) return it->second;
+    }
     const int ntot = tiles_m * tiles_n * nbatch * ksplit;
     const int per_xcd = kNumCU / NUM_XCD;
     const int max_rows = (np0 > nbatch - np0 ? np0 : nbatch - np0) * tiles_m;
@@ -668,6 +680,8 @@ int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int kspli
         }
         if (best_cost < 0 || cost < best_cost) best_cost = cost, best = gm;
     }
+    std::lock_guard<std::mutex> lk(mu);
+    known[key] = best;
     return best;
 }
 
