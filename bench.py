@@ -6,11 +6,15 @@ in HBM: mask -> index compaction, then for each of the K simulated workers (run 
 stream) the masked SwiGLU MLP forward and backward writing its weight gradients into that worker's
 full-size bf16 gradient buffer, then the coverage-normalised average of the K buffers.
 
-Prints ONE JSON line.  `value` is active TFLOP/s (18 T d p per worker and step under forward
-masking; the dense work the method avoids is not counted).  `roofline` is for the kernel that takes
-most of the step; `grad_avg` reports the HBM-bound average alone at 1B-parameter scale;
-`attention` reports one worker's head-masked attention block (not part of `value`);
-`cpu_baseline` is the fp64 oracle timed on this host on a bounded sample.
+Prints ONE JSON line.  The headline workload is the largest one-GPU configuration, the 1B-LLaMA-like
+MLP under backward masking (dense forward and dX, weight gradients on each worker's mask); `value` is
+its active TFLOP/s (12 T d F + 6 T d p per worker and step there, 18 T d p under forward masking; the
+dense work the method avoids is not counted).  `roofline` is for the kernel that takes most of the
+step; `other_configs` holds the same measurement for the 500M-like and the 1B-like forward-masking
+workloads; `grad_avg` reports the HBM-bound average alone at 1B-parameter scale; `attention` reports
+one worker's head-masked attention block (not part of `value`); `cpu_baseline` is the fp64 oracle
+timed on this host on a bounded sample of the headline workload, `cpu_baselines_other` the same for
+the average and for the small fp32 configuration (one thread and all threads).
 """
 import argparse
 import json
@@ -25,19 +29,28 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak (published: 8 TB/s)
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # 256 CUs x 128 fp32 FMA lanes x 2 flop x 2.4 GHz
 
-# HBM-side bytes per launch, from rocprofv3 counter runs (FETCH_SIZE, then WRITE_SIZE, each scaled by
-# what the same counter reads for a 1 GiB copy); the summaries with their commands are
-# profiles/mlp_config2_hbm_traffic.md and profiles/coverage_grad_avg_config5_hbm_traffic.md.
-# Counters cannot be read from inside this process, so these are recorded values for the named
-# workload and launch configuration; any other workload reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("config2_bf16_fm_500M", "mlp_gate_up"): 151.3e6 + 100.9e6,
-    ("config2_bf16_fm_500M", "mlp_down"): 84.0e6 + 25.2e6,
-    ("config2_bf16_fm_500M", "mlp_dact"): 143.2e6 + 167.9e6,
-    ("config2_bf16_fm_500M", "mlp_dx"): 167.9e6 + 25.2e6,
-    ("config2_bf16_fm_500M", "mlp_dw"): 328.1e6 + 18.9e6,
-    ("config5_avg_1B", "coverage_grad_avg"): 11.071e9 + 4.293e9,
-}
+# HBM-side bytes per launch come from rocprofv3 counter runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what
+# the same counter reads for a 1 GiB copy).  Counters cannot be read from inside this process: the file below is
+# written by `python -m paper_2507_09029_amd.traffic_probe summarize ...` from those runs and records, next to each
+# figure, the tile shape and tile order the kernel was launched with.  A figure is reported only while the
+# kernel still launches that way; otherwise `traffic` is null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_recorded.json")
+DEFAULT_WORKLOAD = "config4_bf16_bm_1B"
+
+
+def recorded_traffic(workload, kernel, shape):
+    """Recorded L2 <-> fabric bytes per launch of `kernel` at `workload`, or None when there is no record or
+    the launch configuration (`shape`, from sdp_profile_launch_shape; None for kernels that have none) differs."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+    if not rec:
+        return None
+    if rec.get("launch") != shape:
+        return None
+    return rec["fetch_bytes"] + rec["write_bytes"]
 
 
 def parse():
@@ -45,7 +58,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config2_bf16_fm_500M")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the sub-objects for the other bf16 MLP workloads (default line only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-grad-avg-1b", action="store_true", help="skip the 1B-parameter average measurement")
     ap.add_argument("--avg-steps", type=int, default=20)
@@ -70,25 +85,80 @@ def flops_per_launch(name, w):
     }.get(name)
 
 
-def cpu_baseline(w):
-    """The oracle as it stands, timed on this host on a bounded token slice of worker 0's batch."""
+def _omp_threads(n=None):
+    """Thread count the oracle's OpenMP loops use; n sets it (the oracle library links the same libgomp)."""
+    import ctypes
+
+    gomp = ctypes.CDLL("libgomp.so.1")
+    if n is not None:
+        gomp.omp_set_num_threads(int(n))
+    return int(gomp.omp_get_max_threads())
+
+
+def cpu_baseline(w, target_flop=6e11):
+    """The oracle as it stands, timed on this host on a bounded token slice of worker 0's batch (cost is linear in
+    the number of token rows): about target_flop of work, 10-30 s on 16 threads."""
     import oracle
     import workloads
 
-    rows = min(w.T, 8192)
+    rows = int(min(w.T, max(256, target_flop / (w.active_flop_per_worker / w.T))))
+    rows -= rows % 256 if rows > 256 else 0
     W = [workloads.to_f64(t) for t in workloads.mlp_weights(w)]
     X, dY = workloads.mlp_batch(w, 0, rows=rows)
     mask = oracle.make_masks(w.K, w.F, w.p, w.mask_seed, True)[0]
     X, dY = workloads.to_f64(X), workloads.to_f64(dY)
+    cores = _omp_threads()
     t0 = time.perf_counter()
     oracle.worker_step(w.mode, mask, X, dY, *W)
     dt = time.perf_counter() - t0
     flop = w.active_flop_per_worker * rows / w.T
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {
         "value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-        "sample": f"worker 0, first {rows} of {w.T} token rows, full d and F, fp64, {dt:.2f} s; active flops counted as for the GPU",
+        "sample": f"{w.name}: worker 0, first {rows} of {w.T} token rows, full d and F, fp64, {dt:.2f} s; "
+                  f"active flops counted as for the GPU",
     }
+
+
+def cpu_baselines_other():
+    """The oracle beside the other workloads: the coverage average of the 1B-parameter workload on a row slice
+    (cost is linear in the rows), and the whole small fp32 configuration on one thread and on all threads."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    out = {}
+    cores = _omp_threads()
+    c = workloads.CONFIG5
+    rows = 16384
+    mask = np.ascontiguousarray(oracle.make_masks(c.K, c.R, c.p, c.mask_seed, False)[:, :rows])
+    g = [workloads.bf16_bits(t) for t in workloads.grad_buffers(c.K, rows, c.D, c.sigma, "bf16")]
+    t0 = time.perf_counter()
+    oracle.gated_average(g, mask)
+    dt = time.perf_counter() - t0
+    nbytes = int(mask.sum()) * c.D * 2 + rows * c.D * 4 + c.K * rows + rows
+    out["config5_avg_1B"] = {
+        "value": nbytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": f"first {rows} of {c.R} rows of the {c.K} buffers (row length {c.D}), bf16 in, fp64 out, {dt:.2f} s; "
+                  f"bytes counted as for the GPU (covered rows read, fp32-sized output written)",
+    }
+    del g
+    w = workloads.CONFIG1
+    W = [workloads.to_f64(t) for t in workloads.mlp_weights(w)]
+    masks = oracle.make_masks(w.K, w.F, w.p, w.mask_seed, True)
+    batches = [tuple(workloads.to_f64(t) for t in workloads.mlp_batch(w, k)) for k in range(w.K)]
+    for label, n in (("one_thread", 1), ("all_threads", cores)):
+        _omp_threads(n)
+        t0 = time.perf_counter()
+        for k in range(w.K):
+            oracle.worker_step(w.mode, masks[k], *batches[k], *W)
+        dt = time.perf_counter() - t0
+        out[f"config1_f32_fm_{label}"] = {
+            "value": w.K * w.active_flop_per_worker / dt / 1e12, "unit": "TFLOP/s", "cores": n, "kind": "oracle",
+            "sample": f"all {w.K} workers' forward + backward at full size, fp64, {dt:.3f} s",
+        }
+    _omp_threads(cores)
+    return out
 
 
 def bench_grad_avg_1b(sdp, torch, steps):
@@ -120,7 +190,7 @@ def bench_grad_avg_1b(sdp, torch, steps):
         "algorithmic_bytes": c.algorithmic_bytes, "ms_per_call": kern * 1e3, "ms_per_call_wall": wall * 1e3,
         "value": gbs, "unit": "GB/s",
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((c.name, "coverage_grad_avg"))},
+                     "traffic": recorded_traffic(c.name, "coverage_grad_avg", None)},
     }
     # the squared norm of the average alone (what gradient clipping needs before the fused update): reads the
     # covered gradient rows, writes nothing
@@ -229,26 +299,10 @@ def bench_attention(sdp, torch, steps):
     }
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build measures one GPU only (K workers are simulated back to back on it); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import torch
-
-    import paper_2507_09029_amd as sdp
+def bench_mlp(sdp, torch, w, a, steps, warmup):
+    """One MLP workload: W warm-up steps, an untimed per-kernel survey, then exactly `steps` timed steps."""
     import workloads
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
-        sys.exit(3)
-    sdp.lib()
-    torch.cuda.set_device(0)
-    if a.attention_only:
-        print(json.dumps({"attention": bench_attention(sdp, torch, max(2, a.steps // 4))}))
-        return
-    w = workloads.MLP_CONFIGS[a.workload]
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = "cuda"
 
@@ -304,6 +358,7 @@ def main():
         sdp.coverage_grad_avg(bufs, row_mask, out=avg, cov=avg_cov)
 
     run_step = step
+    events = a.events
     if a.graph:
         # one eager step first (first-launch set-up is not capturable), then capture and replay
         step()
@@ -318,8 +373,8 @@ def main():
                 step()
             main, streams[0] = saved_main, saved_streams0
         run_step = graph.replay
-        a.events = 0
-    for _ in range(a.warmup):
+        events = 0
+    for _ in range(warmup):
         run_step()
     torch.cuda.synchronize()
 
@@ -334,11 +389,12 @@ def main():
             out[name] = {"launches_per_step": calls / nsteps, "avg_ms": avg_ms, "share_of_step": ms / nsteps / step_ms}
             if f:
                 out[name]["tflops"] = f / (avg_ms * 1e-3) / 1e12
+                out[name]["launch"] = sdp.profile_launch_shape(name)
         return out
 
     kernels, dominant = {}, None
-    if a.events and not a.graph:
-        nsurvey = max(1, min(3, a.steps))
+    if events and not a.graph:
+        nsurvey = max(1, min(3, steps))
         sdp.profile_filter(None)
         sdp.profile_reset()
         sdp.profile_enable(True)
@@ -353,14 +409,14 @@ def main():
         if gemm:
             dominant = max(gemm, key=lambda k: gemm[k]["share_of_step"])
 
-    # ---- timed region: exactly K steps; HIP events (on the launch stream) around the dominant kernel only
+    # ---- timed region: exactly `steps` steps; HIP events (on the launch stream) around the dominant kernel only
     sdp.profile_reset()
     if dominant:
         sdp.profile_filter(dominant)
         sdp.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    for _ in range(steps):
         run_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -368,7 +424,7 @@ def main():
     sdp.profile_enable(False)
     sdp.profile_filter(None)
 
-    ms_per_step = elapsed / a.steps * 1e3
+    ms_per_step = elapsed / steps * 1e3
     flop_step = w.K * w.active_flop_per_worker
     value = flop_step / (ms_per_step * 1e-3) / 1e12
 
@@ -379,13 +435,15 @@ def main():
         ach = flops_per_launch(dominant, w) / (avg_ms * 1e-3) / 1e12
         # the fp32 path (config 1, a correctness configuration) runs on the vector ALUs, not on the matrix cores
         bound, peak = ("mfma", PEAK_BF16_TFLOPS) if w.dtype == "bf16" else ("alu", PEAK_FP32_VECTOR_TFLOPS)
+        shape = kernels[dominant].get("launch")
         roofline = {"bound": bound, "kernel": dominant, "achieved": ach, "peak": peak, "unit": "TFLOP/s",
                     "frac": ach / peak,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)) if S == 1 else None,
-                    "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, recorded)",
-                    "avg_launch_ms": avg_ms,
+                    "traffic": recorded_traffic(w.name, dominant, shape) if S == 1 else None,
+                    "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, recorded for this "
+                                    "launch configuration in profiles/hbm_traffic_recorded.json; null if none matches)",
+                    "launch": shape, "avg_launch_ms": avg_ms,
                     "launches_timed": calls, "flop_per_launch": flops_per_launch(dominant, w),
-                    "share_of_step": ms / a.steps / ms_per_step}
+                    "share_of_step": ms / steps / ms_per_step}
 
     # forward and backward separately (sums of the survey's per-kernel means, per worker)
     fwd_names = ("mlp_wt_fwd", "mlp_gate_up", "mlp_down")
@@ -395,17 +453,50 @@ def main():
         b = sum(v["avg_ms"] * v["launches_per_step"] / w.K for k, v in kernels.items() if k.startswith("mlp_") and k not in fwd_names)
         fwd_bwd = {"forward": f, "backward": b}
 
-    rec = {
-        "metric": "masked-MLP fwd+bwd active TFLOP/s (% bf16 MFMA peak) + grad-avg GB/s (% HBM)",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+    res = {
+        "value": value, "unit": "TFLOP/s", "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "dtype": w.dtype,
         "config": {"workload": w.name, "mode": w.mode, "tokens": w.T, "d_model": w.d, "d_ff": w.F, "active_neurons": w.p,
                    "workers_simulated": w.K, "active_flop_per_step": flop_step, "streams": S},
         "frac_of_bf16_peak": value / PEAK_BF16_TFLOPS if w.dtype == "bf16" else None,
         "roofline": roofline,
         "kernels": kernels,
         "fwd_bwd_ms_per_worker": fwd_bwd,
+    }
+    return res, Xs[0]
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU only (K workers are simulated back to back on it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2507_09029_amd as sdp
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    L = sdp.lib()
+    torch.cuda.set_device(0)
+    if a.attention_only:
+        print(json.dumps({"attention": bench_attention(sdp, torch, max(2, a.steps // 4))}))
+        return
+    w = workloads.MLP_CONFIGS[a.workload]
+    res, x0 = bench_mlp(sdp, torch, w, a, a.steps, a.warmup)
+    rec = {
+        "metric": "masked-MLP fwd+bwd active TFLOP/s (% bf16 MFMA peak) + grad-avg GB/s (% HBM)",
+        "value": res["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": res["config"],
+        "frac_of_bf16_peak": res["frac_of_bf16_peak"],
+        "roofline": res["roofline"],
+        "kernels": res["kernels"],
+        "fwd_bwd_ms_per_worker": res["fwd_bwd_ms_per_worker"],
         "kernels_note": "per-kernel table from an untimed survey of up to 3 steps with HIP events around every kernel "
                         "(that instrumentation slows a step by about a tenth); roofline is timed live in the K timed steps",
     }
@@ -414,21 +505,30 @@ def main():
     # under MFMA load depends on the operand bits)
     if w.dtype == "bf16":
         nop = L.sdp_probe_mfma_operand_bytes() // 2
-        rnd = Xs[0].reshape(-1)[:nop].contiguous()
+        rnd = x0.reshape(-1)[:nop].contiguous()
         rec["mfma_ceiling"] = {
             "random_operands_tflops": sdp.probe_mfma_tflops(rnd),
             "zero_operands_tflops": sdp.probe_mfma_tflops(torch.zeros_like(rnd)),
             "published_peak_tflops": PEAK_BF16_TFLOPS,
             "note": "v_mfma_f32_32x32x16_bf16 loop, 8 waves per CU, no memory traffic; measured live",
         }
+    del res, x0
+    torch.cuda.empty_cache()
+    # the other bf16 MLP workloads, measured the same way (their own steps; not part of `value`)
+    if a.workload == DEFAULT_WORKLOAD and not a.no_other_configs:
+        rec["other_configs"] = {}
+        for name, st in (("config3_bf16_fm_1B", max(3, a.steps // 2)), ("config2_bf16_fm_500M", a.steps)):
+            r, _ = bench_mlp(sdp, torch, workloads.MLP_CONFIGS[name], a, st, max(1, min(a.warmup, 3)))
+            rec["other_configs"][name] = r
+            del r, _
+            torch.cuda.empty_cache()
     if not a.no_grad_avg_1b:
-        del Xs, dYs, bufs, avg, per
-        torch.cuda.empty_cache()
         rec["grad_avg"] = bench_grad_avg_1b(sdp, torch, a.avg_steps)
     if not a.no_attention:
         rec["attention"] = bench_attention(sdp, torch, max(2, a.steps // 4))
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
+        rec["cpu_baselines_other"] = cpu_baselines_other()
     print(json.dumps(rec))
 
 

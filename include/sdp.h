@@ -88,7 +88,9 @@ int sdp_make_masks(int K, int F, int p, uint64_t seed, int require_cover, uint8_
 int sdp_sample_masks_host(int K, int F, int p, uint64_t seed, int require_cover, uint8_t* mask_host);
 
 /* ---------------------------------------------------------------------------------------------
- * Mask -> index compaction (prefix sum over each worker's mask row) and coverage counts.
+ * Mask -> index compaction (prefix sum over each worker's mask row) and coverage counts: the index
+ * form of the mask matrix of Sec. 3.1, with the row sums and the column loads c_j = sum_k m_{k,j} of
+ * App. A (the load of a column is the divisor of the gated average of every parameter it owns).
  *   mask  [K][F] u8 in, any non-zero byte counts as 1
  *   idx   [K][idx_ld] i32 out: idx[k][i] = i-th active neuron of worker k, ascending; entries
  *         from count[k] on are -1; active neurons of rank >= idx_ld are dropped
@@ -110,7 +112,8 @@ int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t
  * the value follows from the histogram of loads, which is counted on the device in integers (the
  * result does not depend on the order of the atomics) and finished on the host in fp64.
  *   cov  [F] u8 device in: the loads c_j written by sdp_index_masks / sdp_make_masks
- *   hist [SDP_MAX_WORKERS + 1] u64 device out: hist[c] = number of neurons of load c
+ *   hist [SDP_MAX_WORKERS + 2] u64 device out: hist[c] = number of neurons of load c for c <= SDP_MAX_WORKERS;
+ *        the last entry counts bytes of cov above SDP_MAX_WORKERS (always an error)
  *   rho2_host: host out
  * The call synchronises `stream`.  Multiply by the row length to get the figure over all parameters
  * of a neuron-major matrix.
@@ -273,36 +276,6 @@ int sdp_coverage_grad_sqnorm(int K, int64_t R, int D, int gdtype, const void* co
  * (the paper states only the threshold, 1.0).  sqnorm: device [n] fp64; scale: device fp32 out, to be passed
  * as grad_scale_dev.  Errors: INVALID_ARG (null, misaligned, n < 1, max_norm not positive and finite). */
 int sdp_clip_scale(int n, const double* sqnorm, float max_norm, float* scale, void* stream);
-
-/* ---------------------------------------------------------------------------------------------
- * Per-kernel timing.  With profiling on, every kernel launch is bracketed by HIP events on its
- * stream.  sdp_profile_read synchronises those events and returns, for up to `cap` distinct
- * kernel names, the launch count and total milliseconds since the last reset.
- *   names  host array of cap pointers, set to static strings owned by the library
- *   calls, ms host arrays of cap entries.   Returns the number of entries filled, or < 0.
- * sdp_profile_filter(name) restricts the bracketing to launches of that one kernel name (NULL or ""
- * = all): events between back-to-back kernels keep them from overlapping their launch and drain
- * phases, so timing every kernel slows a step by about a tenth; timing one kernel does not.
- * ------------------------------------------------------------------------------------------- */
-int sdp_profile_enable(int on);
-int sdp_profile_filter(const char* name);
-int sdp_profile_reset(void);
-int sdp_profile_read(int cap, const char** names, int64_t* calls, double* ms);
-
-/* ---------------------------------------------------------------------------------------------
- * Measurement aid (not a step of the method): the rate at which this GPU's matrix cores sustain the
- * bf16 MFMA instruction the contractions use, on operand values supplied by the caller and with no
- * memory traffic inside the loop.  The clock the chip holds under MFMA load depends on the operand
- * values (power), so this is the practical ceiling that the contractions' rates can be read against.
- *   operands  device, sdp_probe_mfma_operand_bytes() bytes of bf16 values, 16-byte aligned
- *   blocks    workgroups of 512 lanes to launch (a few per CU), iters: 32 MFMAs per wave each
- *   sink      device scratch, sdp_probe_mfma_sink_bytes(blocks) bytes (written, never read)
- *   tflops    host out.  The call launches the loop twice, times the second launch with HIP events
- *             and synchronises `stream`.
- * ------------------------------------------------------------------------------------------- */
-size_t sdp_probe_mfma_operand_bytes(void);
-size_t sdp_probe_mfma_sink_bytes(int blocks);
-int sdp_probe_mfma_tflops(const void* operands, int blocks, int iters, void* sink, double* tflops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -56,6 +56,8 @@ def lib():
     L.sdp_index_masks_workspace_bytes.argtypes = [i32, i64]
     L.sdp_index_masks.restype = i32
     L.sdp_index_masks.argtypes = [i32, i64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.sdp_profile_launch_shape.restype = i32
+    L.sdp_profile_launch_shape.argtypes = [ctypes.c_char_p] + [ctypes.POINTER(ctypes.c_int)] * 4
     L.sdp_mask_rho2.restype = i32
     L.sdp_mask_rho2.argtypes = [i32, i64, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.sdp_masked_mlp_fwd_workspace_bytes.restype = sz
@@ -171,13 +173,13 @@ def index_masks(mask, idx_ld=None, ws=None):
 
 
 def mask_rho2(K, cov):
-    """cov u8 [F] (GPU), K workers -> (rho^2 as a float, load histogram i64 [65] on the GPU)."""
+    """cov u8 [F] (GPU), K workers -> (rho^2 as a float, load histogram i64 [65] on the GPU: loads 0 .. 64)."""
     cptr = _dev(cov, torch.uint8, "cov")
-    hist = torch.empty((65,), dtype=torch.int64, device=cov.device)
+    hist = torch.empty((MAX_WORKERS + 2,), dtype=torch.int64, device=cov.device)  # last bin: bytes above 64
     out = ctypes.c_double(0.0)
     st = lib().sdp_mask_rho2(K, cov.numel(), cptr, hist.data_ptr(), ctypes.byref(out), _stream())
     _check(st, "sdp_mask_rho2")
-    return out.value, hist
+    return out.value, hist[: MAX_WORKERS + 1]
 
 
 def masked_mlp_fwd_workspace_bytes(mode, dtype, T, d, F, p):
@@ -418,6 +420,16 @@ def profile_read(cap=64):
     n = lib().sdp_profile_read(cap, names, calls, ms)
     _check(n, "sdp_profile_read")
     return {names[i].decode(): (int(calls[i]), float(ms[i])) for i in range(n)}
+
+
+def profile_launch_shape(name):
+    """-> {"tile": "BMxBN", "group_m": g, "stacked": bool} of the last MFMA contraction launched under `name` while
+    timing was on, or None if there was none."""
+    v = [ctypes.c_int(0) for _ in range(4)]
+    st = lib().sdp_profile_launch_shape(name.encode(), *[ctypes.byref(x) for x in v])
+    if st != 0:
+        return None
+    return {"tile": f"{v[0].value}x{v[1].value}", "group_m": v[2].value, "stacked": bool(v[3].value)}
 
 
 def probe_mfma_tflops(operands, blocks=1024, iters=500):

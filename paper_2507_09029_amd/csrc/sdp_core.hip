@@ -1,4 +1,5 @@
 // Status strings and per-kernel event timing of libsdp_hip.so.
+#include <atomic>
 #include <map>
 #include <mutex>
 #include <string>
@@ -15,7 +16,7 @@ struct Pending {
 };
 
 std::mutex g_mu;
-bool g_on = false;
+std::atomic<bool> g_on{false}; // read on every launch without the lock
 std::vector<Pending> g_pending;
 std::vector<hipEvent_t> g_free;
 std::map<std::string, std::pair<int64_t, double>> g_totals; // name -> (calls, ms)
@@ -55,10 +56,10 @@ void drain_locked() {
 
 } // namespace
 
-bool profiling_on() { return g_on; }
+bool profiling_on() { return g_on.load(std::memory_order_relaxed); }
 
 bool profiling_wants(const char* name) {
-    if (!g_on) return false;
+    if (!profiling_on()) return false;
     std::lock_guard<std::mutex> lk(g_mu);
     return g_filter.empty() || g_filter == name;
 }
@@ -110,7 +111,7 @@ extern "C" const char* sdp_status_string(int status) {
 
 extern "C" int sdp_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(sdp::g_mu);
-    sdp::g_on = on != 0;
+    sdp::g_on.store(on != 0, std::memory_order_relaxed);
     return SDP_OK;
 }
 

@@ -46,6 +46,7 @@
 #include <cstdlib>
 #include <map>
 #include <mutex>
+#include <string>
 #include <type_traits>
 #include <vector>
 
@@ -620,6 +621,30 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
 
 constexpr int kNumCU = 256;
 
+// Overrides of the tile shape and order for tuning runs.  The library's behaviour is a pure function of its
+// arguments: the environment is consulted only in a build with -DSDP_TUNING_SWITCHES (never the shipped one),
+// once per process, and values outside the accepted sets are ignored.
+struct Tuning {
+    int force_tile = 0; // 0 = choose; 128 / 192 / 256
+    int group_m = 0;    // 0 = choose
+    bool plain_order = false;
+};
+const Tuning& tuning() {
+    static const Tuning t = [] {
+        Tuning v;
+#ifdef SDP_TUNING_SWITCHES
+        if (const char* e = getenv("SDP_FORCE_TILE")) {
+            const int f = atoi(e);
+            if (f == 128 || f == 192 || f == 256) v.force_tile = f;
+        }
+        if (const char* e = getenv("SDP_GROUP_M")) v.group_m = atoi(e) > 0 ? atoi(e) : 0;
+        v.plain_order = getenv("SDP_PLAIN_ORDER") != nullptr;
+#endif
+        return v;
+    }();
+    return t;
+}
+
 // Tile-rows per group of the workgroup -> tile order: the tiles resident on one XCD at a time (its
 // share of the launch, at most one per CU) form a block of nbatch x group_m x columns; pick the
 // group_m for which that block touches the fewest distinct operand rows (A rows weigh na operands,
@@ -685,6 +710,10 @@ int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int kspli
     return best;
 }
 
+// last launch configuration per call-site name, kept only while per-kernel timing is on (sdp_profile_launch_shape)
+std::mutex g_shape_mu;
+std::map<std::string, std::array<int, 4>> g_last_shape;
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OP>
 int launch_cfg(const GemmDesc& d, hipStream_t s) {
     using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
@@ -725,8 +754,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     }
     g.group_m = choose_group_m(g.tiles_m, g.tiles_n, nbatch, na * ksplit, nbo * ksplit, BM, BN);
     g.np0 = 0;
-    // SDP_PLAIN_ORDER in the environment keeps the problems interleaved tile by tile (comparison runs)
-    if (kBatched && d.nbatch > 1 && nbo <= 2 && !getenv("SDP_PLAIN_ORDER")) {
+    if (kBatched && d.nbatch > 1 && nbo <= 2 && !tuning().plain_order) {
         // problems that share B must be neighbours: [0, np0) on Bb[0], the rest on one other operand (or none)
         int np0 = 1;
         while (np0 < d.nbatch && d.Bb[np0] == d.Bb[0]) ++np0;
@@ -737,7 +765,11 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
             g.group_m = choose_group_shared(g.tiles_m, g.tiles_n, np0, d.nbatch, ksplit, BM, BN);
         }
     }
-    if (const char* e = getenv("SDP_GROUP_M")) g.group_m = atoi(e) > 0 ? atoi(e) : g.group_m;
+    if (tuning().group_m > 0) g.group_m = tuning().group_m;
+    if (profiling_on() && d.name) {
+        std::lock_guard<std::mutex> lk(g_shape_mu);
+        g_last_shape[d.name] = {BM, BN, g.group_m, g.np0 > 0 ? 1 : 0};
+    }
     auto kern = sdp_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, OP>;
     // once per instantiation (initialisation of a function-local static is thread-safe)
     static const hipError_t attr =
@@ -771,9 +803,7 @@ int launch(const GemmDesc& d, hipStream_t s) {
     // the SwiGLU-forward epilogue pairs gate and up columns inside a tile and has no 192-wide variant
     const double c192 = EPI == EPI_SWIGLU_FWD ? 1e300 : shape_cost(d.M, ncols, nbatch, 256, 192, 1.08);
     const double c128 = shape_cost(d.M, ncols, nbatch, 128, 128, 1.6);
-    // SDP_FORCE_TILE=256|192|128 in the environment overrides the choice (tuning runs and tests)
-    int force = d.force_tile;
-    if (const char* e = getenv("SDP_FORCE_TILE")) force = atoi(e);
+    const int force = tuning().force_tile ? tuning().force_tile : d.force_tile;
     if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) {
         return launch_cfg<256, 256, 2, 4, EPI, OP>(d, s);
     }
@@ -836,6 +866,7 @@ size_t gemm_split_ws_bytes(int M, int N, int K, int nbatch) {
 
 bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return false;
+    if (d.force_tile != 0 && d.force_tile != 128 && d.force_tile != 192 && d.force_tile != 256) return false;
     // 16-byte global chunks, 16-deep MFMA steps, 32-bit byte offsets inside each operand
     if (d.K % 16 || d.lda % 8 || d.ldb % 8 || d.N % 8 || d.ldc % 8) return false;
     if (d.a_km) return false; // depth-major A goes through the transposing pre-pass or the plain kernel
@@ -898,3 +929,12 @@ int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
 }
 
 } // namespace sdp
+
+extern "C" int sdp_profile_launch_shape(const char* name, int* tile_m, int* tile_n, int* group_m, int* stacked) {
+    if (!name || !tile_m || !tile_n || !group_m || !stacked) return SDP_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(sdp::g_shape_mu);
+    auto it = sdp::g_last_shape.find(name);
+    if (it == sdp::g_last_shape.end()) return SDP_ERR_INVALID_ARG;
+    *tile_m = it->second[0], *tile_n = it->second[1], *group_m = it->second[2], *stacked = it->second[3];
+    return SDP_OK;
+}

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "sdp.h"
+#include "sdp_measure.h"
 
 namespace sdp {
 

@@ -276,8 +276,9 @@ __global__ __launch_bounds__(256) void coverage_kernel(const uint8_t* __restrict
     cov[j] = (uint8_t)c;
 }
 
-// load histogram hist[c] = #{ j : c_j = c }, c = 0 .. SDP_MAX_WORKERS
-constexpr int kLoads = SDP_MAX_WORKERS + 1;
+// load histogram hist[c] = #{ j : c_j = c }, c = 0 .. SDP_MAX_WORKERS; one more bin, hist[SDP_MAX_WORKERS + 1],
+// counts the bytes above SDP_MAX_WORKERS (no set of workers produces them: the call then fails)
+constexpr int kLoads = SDP_MAX_WORKERS + 2;
 
 __global__ void clear_histogram_kernel(unsigned long long* __restrict__ hist) {
     if (threadIdx.x < kLoads) hist[threadIdx.x] = 0ull;
@@ -291,7 +292,7 @@ __global__ __launch_bounds__(256) void load_histogram_kernel(const uint8_t* __re
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < F; j += stride) {
         const int c = cov[j];
-        atomicAdd(&local[c < kLoads ? c : kLoads - 1], 1u); // a count above K cannot come from sdp_index_masks
+        atomicAdd(&local[c < kLoads - 1 ? c : kLoads - 1], 1u);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kLoads; i += blockDim.x)
@@ -401,7 +402,7 @@ extern "C" int sdp_mask_rho2(int K, int64_t F, const uint8_t* cov, uint64_t* his
     {
         sdp::ProfileScope ps("mask_load_histogram", s);
         clear_histogram_kernel<<<1, 128, 0, s>>>(h);
-        const int64_t blocks = (F + 256 * 16 - 1) / (256 * 16); // each block's 65 global atomics pay for 4096 columns
+        const int64_t blocks = (F + 256 * 16 - 1) / (256 * 16); // each block's 66 global atomics pay for 4096 columns
         load_histogram_kernel<<<dim3((unsigned)(blocks < 2048 ? blocks : 2048)), 256, 0, s>>>(cov, F, h);
     }
     int rc = sdp::launch_status();

@@ -1,4 +1,4 @@
-"""Host-only checks of the C-ABI library: it loads, exports everything include/sdp.h declares,
+"""Host-only checks of the C-ABI library: it loads, exports everything include/*.h declares,
 rejects bad arguments before launching anything, and its host mask sampler matches the oracle's
 independent implementation of the same sampler bit for bit."""
 import ctypes
@@ -16,7 +16,9 @@ FAKE = ctypes.c_void_p(0x1000)  # non-null, 16-byte aligned, never dereferenced:
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "sdp.h")).read()
+    import glob
+
+    text = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(sdp_[a-z0-9_]+)\s*\(", text)))
 

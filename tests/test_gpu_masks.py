@@ -105,3 +105,13 @@ def test_mask_rho2_rejects_loads_above_K(sdp):
         sdp.mask_rho2(4, cov)
     rho2, hist = sdp.mask_rho2(5, cov)  # all five workers hold everything
     assert rho2 == 0.0 and int(hist[5]) == 1000
+
+
+def test_mask_rho2_rejects_loads_above_the_largest_K(sdp):
+    """With K = 64 (the largest accepted) a count byte above 64 must still be an error, not load 64."""
+    cov = torch.full((4096,), 64, dtype=torch.uint8, device="cuda")
+    rho2, hist = sdp.mask_rho2(64, cov)
+    assert rho2 == 0.0 and int(hist[64]) == 4096
+    cov[1234] = 200
+    with pytest.raises(RuntimeError):
+        sdp.mask_rho2(64, cov)
