@@ -46,7 +46,8 @@ def _fullsize_worker(sdp, orc, w, k, Wd, W64, idx, want_mask, dw_layout):
     S = np.flatnonzero(want_mask[k])
 
     # token-row sample: tile edges (tiles of 128 / 256 rows), the very last rows, random rows
-    rows = _sample(w.T, 160, rng, [0, 1, 127, 128, 255, 256, w.T - 257, w.T - 256, w.T - 129, w.T - 128, w.T - 2, w.T - 1])
+    rows = _sample(w.T, 256, rng, [0, 1, 127, 128, 255, 256, w.T - 257, w.T - 256, w.T - 129, w.T - 128, w.T - 2, w.T - 1])
+    assert len(rows) >= 256
     X64, dY64 = workloads.to_f64(X), workloads.to_f64(dY)
     ref = orc.worker_step(w.mode, want_mask[k], X64[rows], dY64[rows], *W64)
     cols = S if w.mode == "fm" else np.arange(w.F)
@@ -58,7 +59,8 @@ def _fullsize_worker(sdp, orc, w, k, Wd, W64, idx, want_mask, dw_layout):
 
     # neuron sample among the worker's active neurons, by rank: tile edges and the ragged tail
     p = len(S)
-    ranks = _sample(p, 48, rng, [0, 1, 31, 32, 127, 128, 255, 256, p - 130, p - 129, p - 33, p - 32, p - 2, p - 1])
+    ranks = _sample(p, 64, rng, [0, 1, 31, 32, 127, 128, 255, 256, p - 130, p - 129, p - 33, p - 32, p - 2, p - 1])
+    assert len(ranks) >= 64
     neurons = S[ranks]
     f = orc.mlp_fwd(X64, W64[0][neurons], W64[1][neurons], W64[2][neurons])
     b = orc.mlp_bwd(X64, dY64, W64[0][neurons], W64[1][neurons], W64[2][neurons], f["G"], f["U"], f["A"])
@@ -69,12 +71,10 @@ def _fullsize_worker(sdp, orc, w, k, Wd, W64, idx, want_mask, dw_layout):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("w,workers,layout", [
-    (workloads.CONFIG2, [0, 3], "compact"),
-    (workloads.CONFIG3, [0, 7], "scatter"),
-    (workloads.CONFIG4, [1], "compact"),
-], ids=["config2", "config3", "config4"])
-def test_fullsize_mlp_sampled(sdp, orc, w, workers, layout):
+@pytest.mark.parametrize("w", [workloads.CONFIG2, workloads.CONFIG3, workloads.CONFIG4], ids=["config2", "config3", "config4"])
+def test_fullsize_mlp_sampled(sdp, orc, w):
+    """Every worker of the configuration (each has its own index list and its own batch): at least 256 token rows
+    and at least 64 of its neurons; the two gradient layouts alternate from worker to worker."""
     W = workloads.mlp_weights(w)
     Wd = [t.cuda() for t in W]
     W64 = [workloads.to_f64(t) for t in W]
@@ -83,7 +83,8 @@ def test_fullsize_mlp_sampled(sdp, orc, w, workers, layout):
     assert (mask.cpu().numpy() == want_mask).all()
     widx, wpos, wcount, wcov = orc.index_masks(want_mask, idx_ld=w.p)
     assert (idx.cpu().numpy() == widx).all() and (cov.cpu().numpy() == wcov).all()
-    for k in workers:
+    for k in range(w.K):
+        layout = ("compact", "scatter")[k % 2]
         print(f"  {w.name}: worker {k}, layout {layout}", flush=True)
         _fullsize_worker(sdp, orc, w, k, Wd, W64, idx, want_mask, layout)
 
