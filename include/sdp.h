@@ -105,6 +105,23 @@ int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t
                     int32_t* count, uint8_t* cov, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * sdp_index_masks for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * results as sdp_index_masks without `ws`: the table of per-chunk counts that long rows need lives in a
+ * fixed array of the library, SDP_INDEX_STATIC_MAX_COUNTS int32 (256 KiB), which every GPU the library
+ * runs on holds until the process ends.  The call allocates nothing and frees nothing.
+ * Limit: rows of more than 32768 columns need K * ceil(F / 2048) <= SDP_INDEX_STATIC_MAX_COUNTS
+ * (K = 8 workers: F up to 16.7 million columns), else SDP_ERR_SHAPE and nothing is enqueued; shorter rows
+ * use no table and have no such limit.  Other errors as for sdp_index_masks (no WORKSPACE).
+ * All calls on one GPU share that array: two calls that may run at the same time on one GPU (different
+ * streams, or different host threads) race and must be ordered by the caller.  The array keeps the
+ * previous call's contents; every entry a call reads it has written itself, so nothing needs clearing.
+ * ------------------------------------------------------------------------------------------- */
+#define SDP_INDEX_STATIC_MAX_COUNTS 65536
+int sdp_index_masks_static(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t idx_ld, int32_t* pos,
+                           int32_t* count, uint8_t* cov, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Distance to uniform masking (Thm. 3.1): rho^2 = || (1/K) 1 - m / c ||_Frob^2 over the K x F mask
  * matrix, with the column's own load c_j as c (the gated average divides column j by c_j); it is 0
  * iff every worker holds every neuron and enters the step-size bound and the variance term of the

@@ -58,6 +58,8 @@ def lib():
     L.sdp_index_masks.argtypes = [i32, i64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     L.sdp_profile_launch_shape.restype = i32
     L.sdp_profile_launch_shape.argtypes = [ctypes.c_char_p] + [ctypes.POINTER(ctypes.c_int)] * 4
+    L.sdp_index_masks_static.restype = i32
+    L.sdp_index_masks_static.argtypes = [i32, i64, vp, vp, i64, vp, vp, vp, vp]
     L.sdp_mask_rho2.restype = i32
     L.sdp_mask_rho2.argtypes = [i32, i64, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.sdp_masked_mlp_fwd_workspace_bytes.restype = sz
@@ -169,6 +171,26 @@ def index_masks(mask, idx_ld=None, ws=None):
     st = lib().sdp_index_masks(K, F, mptr, idx.data_ptr(), idx_ld, pos.data_ptr(), count.data_ptr(), cov.data_ptr(),
                                ws.data_ptr(), ws.numel(), _stream())
     _check(st, "sdp_index_masks")
+    return idx, pos, count, cov
+
+
+def index_masks_static(mask, idx_ld=None, out=None):
+    """index_masks without a workspace: the library's fixed table holds the chunk counts (no allocation inside the call).
+
+    `out` = (idx, pos, count, cov) preallocated tensors makes the whole call allocation-free."""
+    mptr = _dev(mask, torch.uint8, "mask")
+    K, F = mask.shape
+    if idx_ld is None:
+        idx_ld = F
+    if out is None:
+        out = (torch.empty((K, idx_ld), dtype=torch.int32, device=mask.device),
+               torch.empty((K, F), dtype=torch.int32, device=mask.device),
+               torch.empty((K,), dtype=torch.int32, device=mask.device),
+               torch.empty((F,), dtype=torch.uint8, device=mask.device))
+    idx, pos, count, cov = out
+    st = lib().sdp_index_masks_static(K, F, mptr, _dev(idx, torch.int32, "idx"), idx_ld, _dev(pos, torch.int32, "pos"),
+                                      _dev(count, torch.int32, "count"), _dev(cov, torch.uint8, "cov"), _stream())
+    _check(st, "sdp_index_masks_static")
     return idx, pos, count, cov
 
 

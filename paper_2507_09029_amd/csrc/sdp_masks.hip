@@ -3,6 +3,7 @@
 // Mask matrix m in {0,1}^{K x F}: Sec. 3.1 of the paper; exact row budget p and column loads c_j:
 // App. A.  The index form (ascending gather indices, ranks, per-neuron coverage) is what lets a
 // forward-masked worker run as the physically smaller dense network of Sec. 3.2.
+#include <mutex>
 #include <vector>
 
 #include "sdp_internal.h"
@@ -385,6 +386,65 @@ extern "C" int sdp_index_masks(int K, int64_t F, const uint8_t* mask, int32_t* i
     {
         sdp::ProfileScope ps("mask_compact", s);
         compact_kernel<<<dim3(nchunks, K), kScanThreads, 0, s>>>(mask, F, nchunks, chunk_cnt, idx, idx_ld, pos, count);
+    }
+    {
+        sdp::ProfileScope ps("mask_coverage", s);
+        coverage_kernel<<<dim3((unsigned)((F + 255) / 256)), 256, 0, s>>>(mask, K, F, cov);
+    }
+    return sdp::launch_status();
+}
+
+namespace {
+
+// ---- the compaction for callers that cannot allocate ------------------------------------------------
+// The table of chunk counts, which sdp_index_masks takes from the caller's workspace, lives in a fixed array of
+// this library instead.  In host code the array's name is only a stand-in: the address a kernel can use is asked
+// for once per device (each GPU holds its own copy at its own address) and kept.
+__device__ __align__(256) int32_t g_chunk_counts[SDP_INDEX_STATIC_MAX_COUNTS];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_counts_mu;
+int32_t* g_counts_ptr[kMaxDevices] = {};
+
+// device address of g_chunk_counts on the current device (looked up on first use); null on failure
+int32_t* chunk_counts_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lk(g_counts_mu);
+    if (!g_counts_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_chunk_counts)) != hipSuccess || !p) return nullptr;
+        g_counts_ptr[dev] = (int32_t*)p;
+    }
+    return g_counts_ptr[dev];
+}
+
+} // namespace
+
+extern "C" int sdp_index_masks_static(int K, int64_t F, const uint8_t* mask, int32_t* idx, int64_t idx_ld, int32_t* pos,
+                                      int32_t* count, uint8_t* cov, void* stream) {
+    if (!mask || !idx || !pos || !cov) return SDP_ERR_INVALID_ARG;
+    if (K < 1 || K > SDP_MAX_WORKERS || F < 1) return SDP_ERR_INVALID_ARG;
+    if (F >= ((int64_t)1 << 31) || idx_ld < 1 || idx_ld > F) return SDP_ERR_SHAPE;
+    const int64_t nchunks = (F + kChunk - 1) / kChunk;
+    if (nchunks > kFusedChunks && (int64_t)K * nchunks > SDP_INDEX_STATIC_MAX_COUNTS) return SDP_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    if (nchunks <= kFusedChunks) { // short rows need no table at all
+        sdp::ProfileScope ps("mask_index", s);
+        const unsigned blocks = (unsigned)(K + (F + kScanThreads - 1) / kScanThreads);
+        index_short_rows_kernel<<<blocks, kScanThreads, 0, s>>>(mask, K, F, (int)nchunks, idx, idx_ld, pos, count, cov);
+        return sdp::launch_status();
+    }
+    int32_t* chunk_cnt = chunk_counts_on_current_device();
+    if (!chunk_cnt) return SDP_ERR_HIP;
+    // every entry the second kernel reads is written by the first one of the same call: nothing to clear
+    {
+        sdp::ProfileScope ps("mask_chunk_count", s);
+        chunk_count_kernel<<<dim3((unsigned)nchunks, K), kScanThreads, 0, s>>>(mask, F, (int)nchunks, chunk_cnt);
+    }
+    {
+        sdp::ProfileScope ps("mask_compact", s);
+        compact_kernel<<<dim3((unsigned)nchunks, K), kScanThreads, 0, s>>>(mask, F, (int)nchunks, chunk_cnt, idx, idx_ld, pos, count);
     }
     {
         sdp::ProfileScope ps("mask_coverage", s);
