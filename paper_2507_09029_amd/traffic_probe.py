@@ -47,14 +47,21 @@ def kernel_site(kernel_name):
 
 
 def read_counters(paths):
-    """{site: {counter: [values per dispatch]}} from counter_collection.csv files."""
+    """{site: {counter: [values per dispatch]}} from counter_collection.csv files; the pseudo-counter
+    "duration_ns" holds End_Timestamp - Start_Timestamp of each dispatch (once per dispatch)."""
     out = {}
     for path in paths:
+        seen = set()
         with open(path, newline="") as f:
             for r in csv.DictReader(f):
                 site = kernel_site(r["Kernel_Name"])
-                if site:
-                    out.setdefault(site, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+                if not site:
+                    continue
+                out.setdefault(site, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+                key = (path, r["Dispatch_Id"])
+                if key not in seen:
+                    seen.add(key)
+                    out[site].setdefault("duration_ns", []).append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
     return out
 
 
