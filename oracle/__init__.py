@@ -301,3 +301,52 @@ def attn_worker_step(Bt, S, hd, head_mask, X, dY, Wq, Wk, Wv, WoT, mode="fm"):
                                     *[_p(out[n], _f64p) for n in names])
     out["nonzero_off_mask"] = int(nz)
     return out
+
+
+def block_fwd(Bt, S, hd, X, Wq, Wk, Wv, WoT, W1, W3, W2T):
+    """Dense residual transformer block (attention + MLP, each behind its own skip connection, no normalisation):
+    Hm = X + Attn(X), Y = Hm + MLP(Hm); with B(X) = Y - X this is the paper's block "B(x) + x" (Sec. 3.2,
+    block-level variant).  Returns the attention and MLP intermediates too."""
+    a = attn_fwd(Bt, S, hd, X, Wq, Wk, Wv, WoT)
+    Hm = _f64(X) + a["Y"]
+    f = mlp_fwd(Hm, W1, W3, W2T)
+    return dict(Hm=Hm, Y=Hm + f["Y"], attn=a, mlp=f)
+
+
+def block_bwd(Bt, S, hd, X, dY, Wq, Wk, Wv, WoT, W1, W3, W2T, fwd):
+    """Backward of block_fwd for upstream dY: the skip connections add the incoming gradient to what comes back
+    through each half.  Returns dX and the seven weight gradients."""
+    dY = _f64(dY)
+    f, a = fwd["mlp"], fwd["attn"]
+    bm = mlp_bwd(fwd["Hm"], dY, W1, W3, W2T, f["G"], f["U"], f["A"])
+    dHm = dY + bm["dX"]
+    ba = attn_bwd(Bt, S, hd, X, dHm, Wq, Wk, Wv, WoT, a["Q"], a["K"], a["V"], a["O"])
+    return dict(dX=dHm + ba["dX"], dHm=dHm, dWq=ba["dWq"], dWk=ba["dWk"], dWv=ba["dWv"], dWoT=ba["dWoT"],
+                dW1=bm["dW1"], dW3=bm["dW3"], dW2T=bm["dW2T"])
+
+
+BLOCK_WEIGHTS = ("Wq", "Wk", "Wv", "WoT", "W1", "W3", "W2T")
+
+
+def block_step(mode, m, Bt, S, hd, X, dY, Wq, Wk, Wv, WoT, W1, W3, W2T, dx_rule="through"):
+    """One worker's forward + backward through one residual block under a block-level mask bit m (Sec. 3.2):
+
+    mode 'fm' (block-level forward masking): the masked computation is m B(x) + x.  m = 0 skips the block: Y = X,
+      the gradient passes the skip connection unchanged (dX = dY) and the block's weights get no gradient.
+    mode 'bm' (block-level backward masking): the forward pass always runs the block (m_fwd is all ones); with
+      m = 0 the block is left out of the backward pass: its weight gradients are not computed.  What then reaches
+      the layers below is a reading: 'through' sends the gradient through the block as well as the skip
+      connection (the gradient at the full parameters that Sec. 3.1's backward masking aggregates), 'skip' sends
+      it through the skip connection alone (the whole backward pass of the block omitted, the cost model behind
+      the 1.5 x iteration multiplier of Sec. 4).
+    Weight gradients that are not computed are returned as exact zeros, `computed` says which case ran."""
+    W = (Wq, Wk, Wv, WoT, W1, W3, W2T)
+    zero = {"d" + n: np.zeros_like(_f64(w)) for n, w in zip(BLOCK_WEIGHTS, W)}
+    if mode == "fm" and not m:
+        return dict(Y=_f64(X).copy(), dX=_f64(dY).copy(), computed="skipped", **zero)
+    f = block_fwd(Bt, S, hd, X, *W)
+    b = block_bwd(Bt, S, hd, X, dY, *W, f)
+    if m:
+        return dict(Y=f["Y"], dX=b["dX"], computed="full", **{k: b[k] for k in zero})
+    assert mode == "bm" and dx_rule in ("through", "skip")
+    return dict(Y=f["Y"], dX=b["dX"] if dx_rule == "through" else _f64(dY).copy(), computed="forward only", **zero)
