@@ -228,6 +228,47 @@ int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, int H, int hd
                         void* dWoT, int dw_layout, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Block-level masking (Sec. 3.2, block-level variant: the masked block computes m B(x) + x; the
+ * backward-masked variant runs the block in the forward pass and leaves it out of the backward pass).
+ * One worker's pass through one residual transformer block under its mask bit m for that block.  The block
+ * is attention followed by the SwiGLU MLP, each behind its own skip connection, without normalisation layers
+ * (the paper's block is "Attention + MLP"; it states no more):
+ *     Hm = X + Attn(X),   Y = Hm + MLP(Hm),   i.e.  B(X) = Y - X
+ * with the dense forms of sdp_masked_attn_fwd (all H heads) and sdp_masked_mlp_fwd (all F neurons); the skip
+ * connections are added in the epilogues of the contractions that produce the sums.
+ *   mode SDP_MASK_FORWARD  (m_fwd = m_bwd = m):  m = 1 the dense block;  m = 0 the block is skipped, Y = X
+ *     (only X and Y are looked at; every other pointer may be null), and in the backward call dX = dY and no
+ *     weight gradient is written: the block's parameters get none (Sec. 3.1).
+ *   mode SDP_MASK_BACKWARD (m_fwd = all ones, m_bwd = m):  the forward call runs the dense block whatever m is.
+ *     Backward with m = 1: the dense backward pass.  Backward with m = 0: no weight gradient of the block is
+ *     computed or written; dX follows dx_rule:
+ *       SDP_BLOCK_DX_THROUGH  dX = dY carried through the block and its skip connections: the gradient at the full
+ *                             parameters, which is what Sec. 3.1's backward masking aggregates for the blocks below
+ *       SDP_BLOCK_DX_SKIP     dX = dY: the whole backward pass of the block is omitted, the gradient takes the
+ *                             skip connection alone (the cost model of the 1.5 x iteration multiplier in Sec. 4)
+ *   X, dY [T][d] in, T = Bt S;  Wqkv [3][H hd][d], WoT [H hd][d], W1, W3, W2T [F][d] in
+ *   Y [T][d] out;  saved for the backward call: Hm_save [T][d], QKV_save [T][3 H hd], O_save [T][H hd],
+ *   LSE_save [Bt][H][S] fp32, G_save, U_save [T][F]
+ *   dX [T][d] out;  dWqkv [3][H hd][d], dWoT [H hd][d], dW1, dW3, dW2T [F][d] out (m = 1 only; may be null otherwise)
+ *   ws: sdp_block_fwd_workspace_bytes / sdp_block_bwd_workspace_bytes.
+ * Limits as for the attention and MLP calls (bf16: d, hd, F multiples of 8, T a multiple of 8 in the backward call;
+ * hd <= 128).  Y, Hm_save and X must be three different buffers, dX and dY two.
+ * Errors: INVALID_ARG (null, misaligned, aliasing, m not 0 / 1, unknown mode / dx_rule), SHAPE, WORKSPACE, UNSUPPORTED, HIP.
+ * ------------------------------------------------------------------------------------------- */
+typedef enum { SDP_BLOCK_DX_THROUGH = 0, SDP_BLOCK_DX_SKIP = 1 } sdp_block_dx_rule;
+size_t sdp_block_fwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int F);
+size_t sdp_block_bwd_workspace_bytes(int dtype, int Bt, int S, int d, int H, int hd, int F);
+int sdp_block_fwd(int mode, int m, int dtype, int Bt, int S, int d, int H, int hd, int F, const void* X,
+                  const void* Wqkv, const void* WoT, const void* W1, const void* W3, const void* W2T, void* Y,
+                  void* Hm_save, void* QKV_save, void* O_save, float* LSE_save, void* G_save, void* U_save, void* ws,
+                  size_t ws_bytes, void* stream);
+int sdp_block_bwd(int mode, int m, int dx_rule, int dtype, int Bt, int S, int d, int H, int hd, int F, const void* X,
+                  const void* dY, const void* Wqkv, const void* WoT, const void* W1, const void* W3, const void* W2T,
+                  const void* Hm_save, const void* QKV_save, const void* O_save, const float* LSE_save,
+                  const void* G_save, const void* U_save, void* dX, void* dWqkv, void* dWoT, void* dW1, void* dW3,
+                  void* dW2T, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Gated average of K workers' gradients (Sec. 3.1, eq. "average"), normalised per coordinate by
  * the number of workers that cover it:
  *     out[r][e] = (1 / c_r) * sum_{k : mask[k][r] != 0} g_k[r][e],   c_r = sum_k mask[k][r],

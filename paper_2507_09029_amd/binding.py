@@ -78,6 +78,14 @@ def lib():
     L.sdp_masked_attn_fwd.argtypes = [i32] * 8 + [vp] * 9 + [sz, vp]
     L.sdp_masked_attn_bwd.restype = i32
     L.sdp_masked_attn_bwd.argtypes = [i32] * 8 + [vp] * 11 + [i32, vp, sz, vp]
+    L.sdp_block_fwd_workspace_bytes.restype = sz
+    L.sdp_block_fwd_workspace_bytes.argtypes = [i32] * 7
+    L.sdp_block_bwd_workspace_bytes.restype = sz
+    L.sdp_block_bwd_workspace_bytes.argtypes = [i32] * 7
+    L.sdp_block_fwd.restype = i32
+    L.sdp_block_fwd.argtypes = [i32] * 9 + [vp] * 14 + [sz, vp]
+    L.sdp_block_bwd.restype = i32
+    L.sdp_block_bwd.argtypes = [i32] * 10 + [vp] * 20 + [sz, vp]
     L.sdp_coverage_grad_avg.restype = i32
     L.sdp_coverage_grad_avg.argtypes = [i32, i64, i32, i32, ctypes.POINTER(vp), vp, vp, vp, vp]
     L.sdp_coverage_grad_sqnorm_workspace_bytes.restype = sz
@@ -328,6 +336,94 @@ def masked_attn_bwd(mode, Bt, S, hd, X, dY, Wqkv, WoT, head_idx_k, QKV_save, O_s
         lay, ws.data_ptr(), ws.numel(), _stream())
     _check(st, "sdp_masked_attn_bwd")
     return dX, dWqkv, dWoT
+
+
+BLOCK_DX_THROUGH, BLOCK_DX_SKIP = 0, 1
+_DX_RULES = {"through": BLOCK_DX_THROUGH, "skip": BLOCK_DX_SKIP, BLOCK_DX_THROUGH: BLOCK_DX_THROUGH, BLOCK_DX_SKIP: BLOCK_DX_SKIP}
+
+
+def block_fwd_workspace_bytes(dtype, Bt, S, d, H, hd, F):
+    return int(lib().sdp_block_fwd_workspace_bytes(_DTYPES[dtype], Bt, S, d, H, hd, F))
+
+
+def block_bwd_workspace_bytes(dtype, Bt, S, d, H, hd, F):
+    return int(lib().sdp_block_bwd_workspace_bytes(_DTYPES[dtype], Bt, S, d, H, hd, F))
+
+
+def _opt(t, dtype, name):
+    return _dev(t, dtype, name) if t is not None else None
+
+
+def block_fwd(mode, m, Bt, S, hd, X, Wqkv, WoT, W1, W3, W2T, out=None, ws=None):
+    """One worker's forward through one residual block (attention + MLP) under its block mask bit m.
+
+    'fm' with m = 0 skips the block: returns (Y = X, None): nothing is saved.  Otherwise returns
+    (Y [T][d], saved) with saved = (Hm, QKV, O, LSE, G, U) for block_bwd."""
+    md = _MODES[mode]
+    dt = X.dtype
+    T, d = X.shape
+    E = WoT.shape[0]
+    H = E // hd
+    F = W1.shape[0]
+    dev = X.device
+    if md == MASK_FORWARD and not m:
+        Y = torch.empty_like(X) if out is None else out
+        st = lib().sdp_block_fwd(md, 0, _DTYPES[dt], Bt, S, d, H, hd, F, _dev(X, dt, "X"), None, None, None, None, None,
+                                 _dev(Y, dt, "Y"), None, None, None, None, None, None, None, 0, _stream())
+        _check(st, "sdp_block_fwd")
+        return Y, None
+    if out is None:
+        out = (torch.empty((T, d), dtype=dt, device=dev), torch.empty((T, d), dtype=dt, device=dev),
+               torch.empty((T, 3 * E), dtype=dt, device=dev), torch.empty((T, E), dtype=dt, device=dev),
+               torch.empty((Bt, H, S), dtype=torch.float32, device=dev), torch.empty((T, F), dtype=dt, device=dev),
+               torch.empty((T, F), dtype=dt, device=dev))
+    Y, Hm, QKV, O, LSE, G, U = out
+    if ws is None:
+        ws = _ws(block_fwd_workspace_bytes(dt, Bt, S, d, H, hd, F), dev)
+    st = lib().sdp_block_fwd(md, int(bool(m)), _DTYPES[dt], Bt, S, d, H, hd, F, _dev(X, dt, "X"), _dev(Wqkv, dt, "Wqkv"),
+                             _dev(WoT, dt, "WoT"), _dev(W1, dt, "W1"), _dev(W3, dt, "W3"), _dev(W2T, dt, "W2T"), _dev(Y, dt, "Y"),
+                             _dev(Hm, dt, "Hm_save"), _dev(QKV, dt, "QKV_save"), _dev(O, dt, "O_save"),
+                             _dev(LSE, torch.float32, "LSE_save"), _dev(G, dt, "G_save"), _dev(U, dt, "U_save"),
+                             ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_block_fwd")
+    return Y, (Hm, QKV, O, LSE, G, U)
+
+
+def block_bwd(mode, m, Bt, S, hd, X, dY, Wqkv, WoT, W1, W3, W2T, saved, dx_rule="through", out=None, ws=None):
+    """Backward of block_fwd.  Returns (dX, grads) with grads = (dWqkv, dWoT, dW1, dW3, dW2T) when m = 1 and None
+    otherwise (a masked block gets no weight gradient; under 'bm' dX then follows dx_rule)."""
+    md = _MODES[mode]
+    dt = X.dtype
+    T, d = X.shape
+    E = WoT.shape[0]
+    H = E // hd
+    F = W1.shape[0]
+    dev = X.device
+    rule = _DX_RULES[dx_rule]
+    if not m and (md == MASK_FORWARD or rule == BLOCK_DX_SKIP):
+        dX = torch.empty_like(dY) if out is None else out[0]
+        st = lib().sdp_block_bwd(md, 0, rule, _DTYPES[dt], Bt, S, d, H, hd, F, None, _dev(dY, dt, "dY"), *([None] * 11),
+                                 _dev(dX, dt, "dX"), *([None] * 5), None, 0, _stream())
+        _check(st, "sdp_block_bwd")
+        return dX, None
+    Hm, QKV, O, LSE, G, U = saved
+    if out is None:
+        out = (torch.empty((T, d), dtype=dt, device=dev),)
+        if m:
+            out += (torch.empty((3, E, d), dtype=dt, device=dev), torch.empty((E, d), dtype=dt, device=dev),
+                    torch.empty((F, d), dtype=dt, device=dev), torch.empty((F, d), dtype=dt, device=dev),
+                    torch.empty((F, d), dtype=dt, device=dev))
+    dX = out[0]
+    g = tuple(out[1:6]) if m else (None,) * 5
+    if ws is None:
+        ws = _ws(block_bwd_workspace_bytes(dt, Bt, S, d, H, hd, F), dev)
+    st = lib().sdp_block_bwd(md, int(bool(m)), rule, _DTYPES[dt], Bt, S, d, H, hd, F, _dev(X, dt, "X"), _dev(dY, dt, "dY"),
+                             _dev(Wqkv, dt, "Wqkv"), _dev(WoT, dt, "WoT"), _dev(W1, dt, "W1"), _dev(W3, dt, "W3"),
+                             _dev(W2T, dt, "W2T"), _dev(Hm, dt, "Hm_save"), _dev(QKV, dt, "QKV_save"), _dev(O, dt, "O_save"),
+                             _dev(LSE, torch.float32, "LSE_save"), _dev(G, dt, "G_save"), _dev(U, dt, "U_save"),
+                             _dev(dX, dt, "dX"), *[_opt(t, dt, "dW") for t in g], ws.data_ptr(), ws.numel(), _stream())
+    _check(st, "sdp_block_bwd")
+    return dX, (g if m else None)
 
 
 def coverage_grad_avg(grads, mask, out=None, cov=None):

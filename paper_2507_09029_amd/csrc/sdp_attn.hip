@@ -673,7 +673,15 @@ extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, in
         if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_fwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph))
         return SDP_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+    return attn_fwd_impl(mode, dtype, Bt, S, d, H, hd, ph, X, Wqkv, WoT, head_idx_k, Y, QKV_save, O_save, LSE_save, nullptr,
+                         ws, (hipStream_t)stream);
+}
+
+int sdp::attn_fwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* Wqkv,
+                       const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save, void* O_save, float* LSE_save,
+                       const void* residual, void* ws, hipStream_t s) {
+    if (mode == SDP_MASK_BACKWARD) ph = H;
+    int rc;
     const bool gathered = mode == SDP_MASK_FORWARD;
     const int T = Bt * S, E = ph * hd;
     const FwdWs w = fwd_ws((char*)ws, esize(dtype), d, E);
@@ -724,6 +732,7 @@ extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, in
     op.B = w.WoC, op.ldb = E;
     op.epilogue = EPI_STORE;
     op.C = Y, op.ldc = d;
+    op.R = residual, op.ldr = d;
     return run(dtype, op, s);
 }
 
@@ -741,14 +750,26 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
         if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_attn_bwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph))
         return SDP_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+    return attn_bwd_impl(mode, dtype, Bt, S, d, H, hd, ph, X, dY, Wqkv, WoT, head_idx_k, QKV_save, O_save, LSE_save, dX,
+                         dWqkv, dWoT, dw_layout, nullptr, true, ws, (hipStream_t)stream);
+}
+
+int sdp::attn_bwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* dY,
+                       const void* Wqkv, const void* WoT, const int32_t* head_idx_k, const void* QKV_save,
+                       const void* O_save, const float* LSE_save, void* dX, void* dWqkv, void* dWoT, int dw_layout,
+                       const void* dx_residual, bool want_dw, void* ws, hipStream_t s) {
+    int rc;
     const bool gathered = mode == SDP_MASK_FORWARD;
     const int hr = heads_run(mode, H, ph);
     const int T = Bt * S, E = hr * hd, Eh = ph * hd; // width the core runs on, width of the held heads
     const BwdWs w = bwd_ws((char*)ws, esize(dtype), T, d, E, Eh, (int64_t)Bt * hr * S);
+    // no list under backward masking: every head is held (ph = H), no row gather and no scatter are needed
+    const bool all_heads = !gathered && head_idx_k == nullptr;
 
-    rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
-    if (rc != SDP_OK) return rc;
+    if (!all_heads) {
+        rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
+        if (rc != SDP_OK) return rc;
+    }
 
     GemmDesc go;
     go.name = "attn_dout";
@@ -793,14 +814,24 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
         if (rc != SDP_OK) return rc;
     }
 
+    rc = transpose_rows((int)esize(dtype), Wqkv, d, gathered ? w.rows_qkv : nullptr, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
+    if (rc != SDP_OK) return rc;
+    GemmDesc dx;
+    dx.name = "attn_dx";
+    dx.M = T, dx.N = d, dx.K = 3 * E;
+    dx.A = w.dQKV, dx.lda = 3 * E;
+    dx.B = w.Wc, dx.ldb = 3 * E;
+    dx.epilogue = EPI_STORE;
+    dx.C = dX, dx.ldc = d;
+    dx.R = dx_residual, dx.ldr = d;
+    if (!want_dw) return run(dtype, dx, s);
+
     const int64_t ldt = ld_tokens(T);
     const TransposeJob tj[4] = {{w.dQKV, w.dQKVt, 3 * E, ldt, nullptr, T, 3 * E},
                                 {O_save, w.Ot, E, ldt, nullptr, T, E},
                                 {X, w.Xt, d, ldt, nullptr, T, d},
                                 {dY, w.dYt, d, ldt, nullptr, T, d}};
     rc = transpose_batch((int)esize(dtype), tj, 4, "attn_tr_bwd", s);
-    if (rc != SDP_OK) return rc;
-    rc = transpose_rows((int)esize(dtype), Wqkv, d, gathered ? w.rows_qkv : nullptr, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
     if (rc != SDP_OK) return rc;
 
     // the four weight gradients share one shape (Eh x d, depth T): dWq, dWk, dWv from the three row blocks of
@@ -811,10 +842,10 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
     dw.name = "attn_dw";
     dw.M = Eh, dw.N = d, dw.K = T;
     dw.lda = ldt, dw.ldb = ldt;
-    if (!gathered) dw.a_gather = w.rows_o, dw.a_rows = E;
+    if (!gathered && !all_heads) dw.a_gather = w.rows_o, dw.a_rows = E;
     dw.epilogue = EPI_STORE;
     dw.ldc = d;
-    dw.c_scatter = dw_layout == SDP_DW_SCATTER ? w.rows_o : nullptr; // rows of the held heads inside each matrix
+    dw.c_scatter = dw_layout == SDP_DW_SCATTER && !all_heads ? w.rows_o : nullptr; // rows of the held heads inside each matrix
     const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : Eh) * d;
     dw.nbatch = 4;
     const size_t e = esize(dtype);
@@ -837,12 +868,5 @@ extern "C" int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, in
         }
     }
 
-    GemmDesc dx;
-    dx.name = "attn_dx";
-    dx.M = T, dx.N = d, dx.K = 3 * E;
-    dx.A = w.dQKV, dx.lda = 3 * E;
-    dx.B = w.Wc, dx.ldb = 3 * E;
-    dx.epilogue = EPI_STORE;
-    dx.C = dX, dx.ldc = d;
     return run(dtype, dx, s);
 }

@@ -74,6 +74,8 @@ struct Dev {
     const int32_t *ag, *bg, *cs;
     uint16_t *C, *C2, *C3;
     int64_t ldc;
+    const uint16_t* R; // STORE / DUAL_ACC, single problem: optional residual [M][ldr]
+    int64_t ldr;
     const uint16_t *Gin, *Uin;
     int64_t ldg;
     uint16_t *Ct, *Ct2, *Ct3; // SWIGLU_BWD: neuron-major (transposed) copies [column or rank][ldct], optional
@@ -544,11 +546,39 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         strip_fetch(gpre, g.Gin, g.ldg, 0);
         strip_fetch(upre, g.Uin, g.ldg, 0);
     }
+    // residual of a single-problem store (the skip connection of a block): fetched one fragment row ahead like G, U
+    constexpr bool kResidual = (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) && !kBatched;
+    u32x4 rpre[kResidual ? NLD : 1];
+    const bool has_r = kResidual && g.R != nullptr;
+    if constexpr (kResidual) {
+        if (has_r) strip_fetch(rpre, g.R, g.ldr, 0);
+    }
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         // keep the scheduler from pulling later fragment rows' work (and its registers) up here
         __builtin_amdgcn_sched_barrier(0);
         if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
+            if constexpr (kResidual) {
+                if (has_r) {
+                    // row chunks -> strip -> each lane's own accumulator positions; added in fp32
+                    strip_commit(strip0, rpre);
+                    if (i + 1 < FM) strip_fetch(rpre, g.R, g.ldr, i + 1);
+                    u32x2 rq[FN][4];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) rq[j][q] = strip_get(strip0, 32 * j, q);
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            acc[i][j][4 * q] += lo_bf16(rq[j][q][0]);
+                            acc[i][j][4 * q + 1] += hi_bf16(rq[j][q][0]);
+                            acc[i][j][4 * q + 2] += lo_bf16(rq[j][q][1]);
+                            acc[i][j][4 * q + 3] += hi_bf16(rq[j][q][1]);
+                        }
+                }
+            }
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -724,6 +754,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     g.A = (const uint16_t*)d.A, g.A2 = (const uint16_t*)d.A2, g.B = (const uint16_t*)d.B, g.B2 = (const uint16_t*)d.B2;
     g.lda = d.lda, g.ldb = d.ldb, g.ag = d.a_gather, g.bg = d.b_gather, g.cs = d.c_scatter;
     g.C = (uint16_t*)d.C, g.C2 = (uint16_t*)d.C2, g.C3 = (uint16_t*)d.C3, g.ldc = d.ldc;
+    g.R = (const uint16_t*)d.R, g.ldr = d.ldr;
     g.Gin = (const uint16_t*)d.Gin, g.Uin = (const uint16_t*)d.Uin, g.ldg = d.ldg;
     g.Ct = (uint16_t*)d.Ct, g.Ct2 = (uint16_t*)d.Ct2, g.Ct3 = (uint16_t*)d.Ct3, g.ldct = d.ldct;
     g.cidx = d.cidx, g.pc = d.pc;
@@ -874,6 +905,10 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.a_gather && (d.a_rows <= 0 || d.epilogue == EPI_DUAL_ACC)) return false;
     if ((d.b_rows > 0 ? d.b_rows : (int64_t)d.N) * d.ldb * 2 >= ((int64_t)1 << 32)) return false;
     if (d.b_gather && d.b_rows <= 0) return false;
+    if (d.R) {
+        if (d.nbatch > 0 || (d.epilogue != EPI_STORE && d.epilogue != EPI_DUAL_ACC)) return false;
+        if (!aligned16(d.R) || d.ldr % 8 || d.c_scatter) return false;
+    }
     if (d.nbatch > 0) {
         if (d.nbatch > kMaxBatch || d.epilogue != EPI_STORE) return false;
         for (int z = 0; z < d.nbatch; ++z)
@@ -897,8 +932,6 @@ bool gemm_mfma_supported(const GemmDesc& d) {
             if (!d.Ct2 || !d.Ct3 || !aligned16(d.Ct) || !aligned16(d.Ct2) || !aligned16(d.Ct3)) return false;
             if (d.ldct % 8 || d.M % 8 || d.ldct < d.M) return false;
             if (d.cidx && d.pc < 1) return false;
-        } else if (!d.C3) {
-            return false;
         }
     }
     return true;

@@ -47,6 +47,8 @@ struct Dev {
     int64_t ldcc;
     const int32_t* cidx;
     int pc;
+    const void* R; // STORE / DUAL_ACC: optional residual [M][ldr]
+    int64_t ldr;
 };
 
 // rank of column n in the ascending index list, or -1 if it is not listed
@@ -139,7 +141,8 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
             if (n >= g.N) continue;
             if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
                 const int64_t row = g.cs ? g.cs[m] : m;
-                st<T>((T*)g.C + row * g.ldc + n, acc[i][j]);
+                const float r = g.R ? ld<T>((const T*)g.R + (int64_t)m * g.ldr + n) : 0.f;
+                st<T>((T*)g.C + row * g.ldc + n, acc[i][j] + r);
             } else if (EPI == EPI_SWIGLU_FWD) {
                 const float gv = acc[i][j], uv = acc2[i][j];
                 st<T>((T*)g.C + (int64_t)m * g.ldc + n, gv);
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
 template <typename T, int EPI>
 int launch(const GemmDesc& d, hipStream_t s) {
     Dev g{d.M, d.N, d.K, d.A, d.A2, d.B, d.B2, d.lda, d.ldb, d.b_gather, d.c_scatter, d.a_km, d.a_gather,
-          d.C, d.C2, d.C3, d.ldc, d.Gin, d.Uin, d.ldg, d.Cc, d.Cc2, d.Cc3, d.ldcc, d.cidx, d.pc};
+          d.C, d.C2, d.C3, d.ldc, d.Gin, d.Uin, d.ldg, d.Cc, d.Cc2, d.Cc3, d.ldcc, d.cidx, d.pc, d.R, d.ldr};
     dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM);
     ProfileScope ps(d.name, s);
     gemm_simple_kernel<T, EPI><<<grid, NT, 0, s>>>(g);

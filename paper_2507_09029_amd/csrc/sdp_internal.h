@@ -72,6 +72,11 @@ struct GemmDesc {
     void* C3 = nullptr; // SWIGLU_FWD / SWIGLU_BWD: Act
     int64_t ldc = 0;
     const int32_t* c_scatter = nullptr;
+    // STORE / DUAL_ACC of a single problem: optional residual, C = acc + R[m][n] (added in fp32 before the
+    // result is rounded; R is indexed like C without the row scatter; R may be C itself: an element is read
+    // before it is written, by the same lane)
+    const void* R = nullptr;
+    int64_t ldr = 0;
     // SWIGLU_BWD inputs and optional compact copies
     const void* Gin = nullptr;
     const void* Uin = nullptr;
@@ -135,6 +140,27 @@ struct AttnCoreDesc {
 bool attn_plain_supported(const AttnCoreDesc& c);
 int attn_plain_fwd(int dtype, const AttnCoreDesc& c, hipStream_t s);
 int attn_plain_bwd(int dtype, const AttnCoreDesc& c, hipStream_t s);
+
+// ---- one worker's MLP / attention passes with the options the block-level calls need ----------------
+// As sdp_masked_mlp_fwd / _bwd and sdp_masked_attn_fwd / _bwd after argument checks, plus:
+//   residual     [T][d] or null: added to the output Y (forward) in the contraction's epilogue
+//   dx_residual  [T][d] or null: added to dX likewise (the gradient that arrives over the skip connection)
+//   want_dw      false: the weight gradients and everything only they need (transposed copies) are left out
+//   idx_k / head_idx_k null (forward masking with p = F; backward masking of heads): every neuron / head, in order
+int mlp_fwd_impl(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* W1, const void* W3,
+                 const void* W2T, const int32_t* idx_k, void* Y, void* G_save, void* U_save, const void* residual,
+                 void* ws, hipStream_t s);
+int mlp_bwd_impl(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* dY, const void* W1,
+                 const void* W3, const void* W2T, const int32_t* idx_k, const void* G_save, const void* U_save, void* dX,
+                 void* dW1, void* dW3, void* dW2T, int dw_layout, const void* dx_residual, bool want_dw, void* ws,
+                 hipStream_t s);
+int attn_fwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* Wqkv,
+                  const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save, void* O_save, float* LSE_save,
+                  const void* residual, void* ws, hipStream_t s);
+int attn_bwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X, const void* dY,
+                  const void* Wqkv, const void* WoT, const int32_t* head_idx_k, const void* QKV_save, const void* O_save,
+                  const float* LSE_save, void* dX, void* dWqkv, void* dWoT, int dw_layout, const void* dx_residual,
+                  bool want_dw, void* ws, hipStream_t s);
 
 // out[c][r] = in[rows ? rows[r] : r][c] for r < R, c < C: (gathered) transpose, element size 2 or 4.
 int transpose_rows(int elem_bytes, const void* in, int64_t ld_in, const int32_t* rows, int R, int C, void* out,

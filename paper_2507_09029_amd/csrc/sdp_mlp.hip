@@ -78,10 +78,17 @@ extern "C" int sdp_masked_mlp_fwd(int mode, int dtype, int T, int d, int F, int 
         if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_mlp_fwd_workspace_bytes(mode, dtype, T, d, F, p))
         return SDP_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+    return mlp_fwd_impl(mode, dtype, T, d, F, p, X, W1, W3, W2T, idx_k, Y, G_save, U_save, nullptr, ws,
+                        (hipStream_t)stream);
+}
+
+int sdp::mlp_fwd_impl(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* W1, const void* W3,
+                      const void* W2T, const int32_t* idx_k, void* Y, void* G_save, void* U_save, const void* residual,
+                      void* ws, hipStream_t s) {
+    if (mode == SDP_MASK_BACKWARD) p = F;
+    int rc;
     const int n = mode == SDP_MASK_FORWARD ? p : F;
     const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
-
     const size_t e = esize(dtype);
     char* w = (char*)ws;
     void* Act = w;
@@ -107,6 +114,7 @@ extern "C" int sdp_masked_mlp_fwd(int mode, int dtype, int T, int d, int F, int 
     dn.B = W2c, dn.ldb = n;
     dn.epilogue = EPI_STORE;
     dn.C = Y, dn.ldc = d;
+    dn.R = residual, dn.ldr = d;
     return run(dtype, dn, s);
 }
 
@@ -125,7 +133,15 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
         if (!aligned16(q)) return SDP_ERR_INVALID_ARG;
     if (!ws || !aligned16(ws) || ws_bytes < sdp_masked_mlp_bwd_workspace_bytes(mode, dtype, T, d, F, p))
         return SDP_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+    return mlp_bwd_impl(mode, dtype, T, d, F, p, X, dY, W1, W3, W2T, idx_k, G_save, U_save, dX, dW1, dW3, dW2T, dw_layout,
+                        nullptr, true, ws, (hipStream_t)stream);
+}
+
+int sdp::mlp_bwd_impl(int mode, int dtype, int T, int d, int F, int p, const void* X, const void* dY, const void* W1,
+                      const void* W3, const void* W2T, const int32_t* idx_k, const void* G_save, const void* U_save,
+                      void* dX, void* dW1, void* dW3, void* dW2T, int dw_layout, const void* dx_residual, bool want_dw,
+                      void* ws, hipStream_t s) {
+    int rc;
     const int n = mode == SDP_MASK_FORWARD ? p : F;
     const int32_t* gather = mode == SDP_MASK_FORWARD ? idx_k : nullptr;
     const size_t e = esize(dtype);
@@ -146,12 +162,12 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     const size_t nm_b = round_up((size_t)p * ld_tokens(T) * e, 256);
     void *dGn = w, *dUn = w + nm_b, *Actn = w + 2 * nm_b; // [p][T(+pad)]: neuron-major
 
-    // the four operand copies of the backward pass as one launch
+    // the four operand copies of the backward pass as one launch (X^T, dY^T only feed the weight gradients)
     const TransposeJob tj[4] = {{W1, W1c, d, n, gather, n, d},
                                 {W3, W3c, d, n, gather, n, d},
                                 {X, XT, d, ld_tokens(T), nullptr, T, d},
                                 {dY, dYT, d, ld_tokens(T), nullptr, T, d}};
-    rc = transpose_batch((int)e, tj, 4, "mlp_tr_bwd", s);
+    rc = transpose_batch((int)e, tj, want_dw ? 4 : 2, "mlp_tr_bwd", s);
     if (rc != SDP_OK) return rc;
 
     // weight-gradient contraction (set up first: whether it can take the MFMA path decides what the
@@ -183,11 +199,12 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     // weight-gradient contraction reads both operands depth-contiguous; act is not stored row-major.
     da.Ct = dGn, da.Ct2 = dUn, da.Ct3 = Actn, da.ldct = ld_tokens(T);
     if (mode == SDP_MASK_BACKWARD) da.cidx = idx_k, da.pc = p;
-    const bool fused = dtype == SDP_BF16 && p % 8 == 0 && T % 8 == 0 && gemm_mfma_supported(dw) && gemm_mfma_supported(da);
+    const bool fused = want_dw && dtype == SDP_BF16 && p % 8 == 0 && T % 8 == 0 && gemm_mfma_supported(dw) && gemm_mfma_supported(da);
     if (!fused) {
         da.Ct = da.Ct2 = da.Ct3 = nullptr, da.cidx = nullptr, da.pc = 0;
-        da.C3 = Act;
-        if (mode == SDP_MASK_BACKWARD) {
+        // without weight gradients nothing reads act: the MFMA kernel then skips its store, the plain one writes it anyway
+        if (want_dw || dtype != SDP_BF16 || !gemm_mfma_supported(da)) da.C3 = Act;
+        if (mode == SDP_MASK_BACKWARD && want_dw) {
             da.Cc = dGc, da.Cc2 = dUc, da.Cc3 = Actc, da.ldcc = p;
             da.cidx = idx_k, da.pc = p;
         }
@@ -206,10 +223,11 @@ extern "C" int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int 
     dx.B = W1c, dx.B2 = W3c, dx.ldb = n;
     dx.epilogue = EPI_DUAL_ACC;
     dx.C = dX, dx.ldc = d;
+    dx.R = dx_residual, dx.ldr = d;
     rc = run(dtype, dx, s);
     if (rc != SDP_OK) return rc;
 
-    if (fused) return SDP_OK;
+    if (fused || !want_dw) return SDP_OK;
     // plain path: read the left operands depth-major ([T][p]) as they are
     const void* lhs[3] = {dGc, dUc, Actc};
     dw.nbatch = 0;

@@ -64,3 +64,28 @@ def assert_close(got, ref, tol, what="", elem_tol=None):
         print(f"[err] {what}: elementwise {elem:.3e} normwise {norm:.3e} (tol {et:.0e} / {tol:.0e})", flush=True)
     assert elem <= et and norm <= tol, f"{what}: elementwise {elem:.3e} > {et:.1e} or normwise {norm:.3e} > {tol:.1e}"
     return elem, norm
+
+
+def assert_close_with_model(got, model, ref, tol, what="", elem_allow=None, rows=False, slack_elem=1.5, slack_norm=1.1):
+    """bf16 results whose distance from the exact result is set by the storage format.  `ref` is the oracle, `model`
+    the same arithmetic in fp64 with only the bf16 rounding points of the GPU path switched on
+    (tests/rounding_model.py).  Individual roundings of the two cannot be expected to coincide (an upstream
+    difference far below one bf16 ulp flips a later rounding), so the comparison is between error figures:
+
+      - `got` is no further from `ref` than the rounding points alone put `model`, up to slack_norm on the
+        normwise figure and slack_elem on the elementwise maximum (an extreme value over 10^4 - 10^6 elements);
+        the floor of both allowances is a quarter of tol, for tensors the model reproduces almost exactly;
+      - and within the fixed bounds: tol normwise, elem_allow (default tol) elementwise.
+
+    rows=True takes one scale per row."""
+    rep = err_report_rows if rows else err_report
+    eo, no = rep(got, ref)
+    e3, n3 = rep(model, ref)
+    ea = tol if elem_allow is None else elem_allow
+    if os.environ.get("SDP_TEST_VERBOSE"):
+        print(f"[err] {what}: vs oracle {eo:.2e} / {no:.2e} (bounds {ea:.0e} / {tol:.0e}); rounding model vs oracle "
+              f"{e3:.2e} / {n3:.2e}", flush=True)
+    assert eo <= max(slack_elem * e3, tol / 4) and no <= max(slack_norm * n3, tol / 4), (
+        f"{what}: {eo:.3e} / {no:.3e} from the oracle, but the bf16 rounding points alone give {e3:.3e} / {n3:.3e}")
+    assert eo <= ea and no <= tol, f"{what}: elementwise {eo:.3e} > {ea:.1e} or normwise {no:.3e} > {tol:.1e} from the oracle"
+    return eo, no

@@ -210,3 +210,19 @@ def test_attention_arguments_are_checked_on_the_host():
     assert L.sdp_masked_attn_bwd(*(bargs[:20] + [None, big, None])) == workspace
     assert L.sdp_masked_attn_bwd(*(bargs[:6] + [136] + bargs[7:])) == unsupported
     assert L.sdp_masked_attn_bwd(*([BM] + bargs[1:12] + [None] + bargs[13:])) == invalid  # the held heads are needed
+
+
+def test_block_argument_errors():
+    L = sdp.lib()
+    f = FAKE
+    big = ctypes.c_size_t(1 << 40)
+    args_f = [f] * 14
+    assert L.sdp_block_fwd(0, 2, 1, 1, 64, 64, 2, 32, 64, *args_f, big, None) == -1          # m not 0 / 1
+    assert L.sdp_block_fwd(3, 1, 1, 1, 64, 64, 2, 32, 64, *args_f, big, None) == -1          # unknown mode
+    assert L.sdp_block_fwd(0, 1, 1, 1, 64, 60, 2, 32, 64, *args_f, big, None) == -2          # d not a multiple of 8
+    assert L.sdp_block_fwd(0, 1, 1, 1, 64, 64, 2, 136, 64, *args_f, big, None) == -5         # head width beyond 128
+    assert L.sdp_block_fwd(0, 1, 1, 1, 64, 64, 2, 32, 64, *args_f, ctypes.c_size_t(0), None) == -1  # X, Y, Hm alias
+    g = ctypes.c_void_p(0x2000); h = ctypes.c_void_p(0x3000)
+    ok = [f, f, f, f, f, f, g, h, f, f, f, f, f, f]
+    assert L.sdp_block_fwd(0, 1, 1, 1, 64, 64, 2, 32, 64, *ok, ctypes.c_size_t(0), None) == -3      # workspace too small
+    assert L.sdp_block_bwd(1, 0, 7, 1, 1, 64, 64, 2, 32, 64, *([f] * 20), big, None) == -1   # unknown dx_rule

@@ -9,7 +9,8 @@ import pytest
 import torch
 
 import workloads
-from helpers import assert_close, assert_close_rows
+import rounding_model as rm
+from helpers import assert_close, assert_close_rows, assert_close_with_model
 from workloads import AttnWorkload
 
 pytestmark = pytest.mark.gpu
@@ -90,6 +91,11 @@ def run_case(sdp, orc, w, workers, dw_layout="compact", mode="fm"):
             assert np.isnan(g[:, off]).all() and np.isnan(go[off]).all(), "rows of heads not held must stay untouched"
             g, go = g[:, held], go[held]
         rows = held  # weight gradients exist for the held heads only, in both regimes
+        model = None
+        if w.dtype == "bf16" and w.S > 1:
+            # the same arithmetic with only the bf16 rounding points: the kernels' weight gradients may be no further
+            # from the oracle than this puts them (see helpers.assert_close_with_model)
+            model = rm.attn_model(w.Bt, w.S, w.hd, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64, mode=mode)
         for i, name in enumerate(("dWq", "dWk", "dWv")):
             if w.S == 1 and i < 2:
                 # a softmax over one key is constant: the exact gradient is zero, and what is left of the
@@ -97,8 +103,14 @@ def run_case(sdp, orc, w, workers, dw_layout="compact", mode="fm"):
                 assert not ref[name].any()
                 assert np.abs(g[i]).max() <= 1e-5 * np.sqrt(np.mean(ref["dWv"][rows] ** 2))
                 continue
-            assert_close(g[i], ref[name][rows], tol, name, elem_tol=tol_dw)
-        assert_close(go, ref["dWoT"][rows], tol, "dWoT", elem_tol=tol_dw)
+            if model is not None:
+                assert_close_with_model(g[i], model[name][rows], ref[name][rows], tol, name, elem_allow=tol_dw)
+            else:
+                assert_close(g[i], ref[name][rows], tol, name, elem_tol=tol_dw)
+        if model is not None:
+            assert_close_with_model(go, model["dWoT"][rows], ref["dWoT"][rows], tol, "dWoT", elem_allow=tol_dw)
+        else:
+            assert_close(go, ref["dWoT"][rows], tol, "dWoT", elem_tol=tol_dw)
 
 
 CASES = [

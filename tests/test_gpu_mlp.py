@@ -8,7 +8,8 @@ import pytest
 import torch
 
 import workloads
-from helpers import assert_close
+import rounding_model as rm
+from helpers import assert_close, assert_close_with_model
 from workloads import MlpWorkload
 
 pytestmark = pytest.mark.gpu
@@ -48,6 +49,7 @@ def run_case(sdp, orc, w, workers, dw_layout="compact", dw_elem_tol=None):
         torch.cuda.synchronize()
         ref = orc.worker_step(w.mode, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64)
         S = np.flatnonzero(want_mask[k])
+        model = None
         assert ref["nonzero_off_mask"] == 0
         assert_close(workloads.to_f64(Y), ref["Y"], tol, "Y")
         assert_close(workloads.to_f64(dX), ref["dX"], tol, "dX")
@@ -60,7 +62,13 @@ def run_case(sdp, orc, w, workers, dw_layout="compact", dw_elem_tol=None):
                 off = np.flatnonzero(want_mask[k] == 0)
                 assert np.isnan(g64[off]).all(), "rows off the mask must stay untouched"
                 g64 = g64[S]
-            assert_close(g64, ref[name][S], tol, name, elem_tol=dw_elem_tol)
+            if w.dtype == "bf16":
+                # no further from the oracle than the bf16 rounding points alone put the result (see helpers)
+                if model is None:
+                    model = rm.mlp_model(w.mode, want_mask[k], workloads.to_f64(X), workloads.to_f64(dY), *W64)
+                assert_close_with_model(g64, model[name][S], ref[name][S], tol, name, elem_allow=dw_elem_tol)
+            else:
+                assert_close(g64, ref[name][S], tol, name, elem_tol=dw_elem_tol)
 
 
 SMALL = [
