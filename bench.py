@@ -246,19 +246,20 @@ def bench_grad_avg_1b(sdp, torch, steps):
     return res
 
 
-def bench_attention(sdp, torch, steps):
+def bench_attention(sdp, torch, steps, w=None):
     """One worker's head-masked attention block (forward + backward) at the 500M-like width: not part of `value`."""
     import workloads
 
-    w = workloads.ATTN_500M
+    w = w or workloads.ATTN_500M
     Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(w))
     mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
     X, dY = (t.cuda() for t in workloads.attn_batch(w, 0))
     wsf = torch.empty(sdp.masked_attn_fwd_workspace_bytes("fm", X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
     wsb = torch.empty(sdp.masked_attn_bwd_workspace_bytes("fm", X.dtype, w.Bt, w.S, w.d, w.H, w.hd, w.ph), dtype=torch.uint8, device="cuda")
     E = w.ph * w.hd
-    fo = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), torch.empty((w.T, 3 * E), dtype=X.dtype, device="cuda"),
-          torch.empty((w.T, E), dtype=X.dtype, device="cuda"), torch.empty((w.Bt, w.ph, w.S), dtype=torch.float32, device="cuda"))
+    Es = w.ph * sdp.attn_saved_head_width(X.dtype, w.hd)  # saved tensors: narrow heads are padded to 64 columns
+    fo = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), torch.empty((w.T, 3 * Es), dtype=X.dtype, device="cuda"),
+          torch.empty((w.T, Es), dtype=X.dtype, device="cuda"), torch.empty((w.Bt, w.ph, w.S), dtype=torch.float32, device="cuda"))
     bo = (torch.empty((w.T, w.d), dtype=X.dtype, device="cuda"), torch.empty((3, E, w.d), dtype=X.dtype, device="cuda"),
           torch.empty((E, w.d), dtype=X.dtype, device="cuda"))
 
@@ -483,7 +484,8 @@ def main():
     L = sdp.lib()
     torch.cuda.set_device(0)
     if a.attention_only:
-        print(json.dumps({"attention": bench_attention(sdp, torch, max(2, a.steps // 4))}))
+        print(json.dumps({"attention": bench_attention(sdp, torch, max(2, a.steps // 4)),
+                          "attention_paper_width": bench_attention(sdp, torch, max(2, a.steps // 4), workloads.ATTN_500M_HD50)}))
         return
     w = workloads.MLP_CONFIGS[a.workload]
     res, x0 = bench_mlp(sdp, torch, w, a, a.steps, a.warmup)
@@ -526,6 +528,7 @@ def main():
         rec["grad_avg"] = bench_grad_avg_1b(sdp, torch, a.avg_steps)
     if not a.no_attention:
         rec["attention"] = bench_attention(sdp, torch, max(2, a.steps // 4))
+        rec["attention_paper_width"] = bench_attention(sdp, torch, max(2, a.steps // 4), workloads.ATTN_500M_HD50)
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
         rec["cpu_baselines_other"] = cpu_baselines_other()

@@ -195,14 +195,18 @@ int sdp_masked_mlp_bwd(int mode, int dtype, int T, int d, int F, int p, const vo
  *   O_h = P_h V_h;  Y = sum over the n heads of O_h WoT_h   (S = the held heads, or all of them).
  *   X [T][d] in;  head_idx_k [ph] i32 in (strictly ascending, in [0, H); trusted like idx_k above)
  *   Y [T][d] out
- *   QKV_save [T][3 n hd] out: Q | K | V of the n heads (head i of the list at columns i hd of each)
- *   O_save [T][n hd] out;  LSE_save [Bt][n][S] fp32 out: log2 of the softmax denominators, logits in
+ *   QKV_save [T][3 n hw] out: Q | K | V of the n heads (head i of the list at columns i hw of each)
+ *   O_save [T][n hw] out;  LSE_save [Bt][n][S] fp32 out: log2 of the softmax denominators, logits in
  *   base 2 -- kept for sdp_masked_attn_bwd.
+ *   hw = sdp_masked_attn_saved_head_width(dtype, hd): the columns a head takes in the saved tensors.  It is hd,
+ *   except for SDP_BF16 with hd < 64 (the paper's 500M / 1B models have hd = 50), where every head is padded to
+ *   64 columns of which the last 64 - hd hold zeros, so that the block runs on the MFMA core.
  *   ws: sdp_masked_attn_fwd_workspace_bytes(...).
- * Limits: hd <= 128 (else UNSUPPORTED); for SDP_BF16 d and hd multiples of 8 (16-byte rows); Bt, H <= 65535;
- * pointers 16-byte aligned.  bf16 with hd = 64 runs the MFMA attention core; fp32, and bf16 with any other
- * head width, run a plain fp32-arithmetic core.  Errors as for the MLP calls.
+ * Limits: hd <= 128 (else UNSUPPORTED); for SDP_BF16 d a multiple of 8 (16-byte rows), and hd a multiple of 8 when
+ * above 64; Bt, H <= 65535; pointers 16-byte aligned.  bf16 with hd <= 64 runs the MFMA attention core; fp32,
+ * and bf16 with wider heads, run a plain fp32-arithmetic core.  Errors as for the MLP calls.
  * ------------------------------------------------------------------------------------------- */
+int sdp_masked_attn_saved_head_width(int dtype, int hd);
 size_t sdp_masked_attn_fwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph);
 int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
                         const void* Wqkv, const void* WoT, const int32_t* head_idx_k, void* Y, void* QKV_save,
@@ -247,7 +251,8 @@ int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, int H, int hd
  *       SDP_BLOCK_DX_SKIP     dX = dY: the whole backward pass of the block is omitted, the gradient takes the
  *                             skip connection alone (the cost model of the 1.5 x iteration multiplier in Sec. 4)
  *   X, dY [T][d] in, T = Bt S;  Wqkv [3][H hd][d], WoT [H hd][d], W1, W3, W2T [F][d] in
- *   Y [T][d] out;  saved for the backward call: Hm_save [T][d], QKV_save [T][3 H hd], O_save [T][H hd],
+ *   Y [T][d] out;  saved for the backward call: Hm_save [T][d], QKV_save [T][3 H hw], O_save [T][H hw] (hw =
+ *   sdp_masked_attn_saved_head_width(dtype, hd)),
  *   LSE_save [Bt][H][S] fp32, G_save, U_save [T][F]
  *   dX [T][d] out;  dWqkv [3][H hd][d], dWoT [H hd][d], dW1, dW3, dW2T [F][d] out (m = 1 only; may be null otherwise)
  *   ws: sdp_block_fwd_workspace_bytes / sdp_block_bwd_workspace_bytes.

@@ -70,6 +70,8 @@ def lib():
     L.sdp_masked_mlp_fwd.argtypes = [i32] * 6 + [vp] * 9 + [sz, vp]
     L.sdp_masked_mlp_bwd.restype = i32
     L.sdp_masked_mlp_bwd.argtypes = [i32] * 6 + [vp] * 12 + [i32, vp, sz, vp]
+    L.sdp_masked_attn_saved_head_width.restype = i32
+    L.sdp_masked_attn_saved_head_width.argtypes = [i32, i32]
     L.sdp_masked_attn_fwd_workspace_bytes.restype = sz
     L.sdp_masked_attn_fwd_workspace_bytes.argtypes = [i32] * 8
     L.sdp_masked_attn_bwd_workspace_bytes.restype = sz
@@ -277,11 +279,26 @@ def masked_attn_bwd_workspace_bytes(mode, dtype, Bt, S, d, H, hd, ph):
     return int(lib().sdp_masked_attn_bwd_workspace_bytes(_MODES[mode], _DTYPES[dtype], Bt, S, d, H, hd, ph))
 
 
+def attn_saved_head_width(dtype, hd):
+    """Columns a head takes in QKV_save / O_save: hd, or 64 for bf16 heads narrower than 64 (padded with zeros)."""
+    return int(lib().sdp_masked_attn_saved_head_width(_DTYPES[dtype], hd))
+
+
+def attn_unpad(t, hd, parts=1):
+    """View of a saved tensor [T][parts n hw] without the padding columns: [T][parts n hd] (a copy when padded)."""
+    T, cols = t.shape
+    hw = attn_saved_head_width(t.dtype, hd)
+    if hw == hd:
+        return t
+    return t.reshape(T, cols // hw, hw)[:, :, :hd].reshape(T, -1)
+
+
 def masked_attn_fwd(mode, Bt, S, hd, X, Wqkv, WoT, head_idx_k, out=None, ws=None):
     """One worker's head-masked attention forward ('fm': the held heads only; 'bm': the dense block).
 
-    X [Bt S][d]; Wqkv [3][H hd][d]; WoT [H hd][d]; head_idx_k int32 [ph].  With n = ph ('fm') or H ('bm'):
-    returns (Y [T][d], QKV_save [T][3 n hd], O_save [T][n hd], LSE_save fp32 [Bt][n][S]).
+    X [Bt S][d]; Wqkv [3][H hd][d]; WoT [H hd][d]; head_idx_k int32 [ph].  With n = ph ('fm') or H ('bm') and
+    hw = attn_saved_head_width(dtype, hd): returns (Y [T][d], QKV_save [T][3 n hw], O_save [T][n hw],
+    LSE_save fp32 [Bt][n][S]).
     """
     m = _MODES[mode]
     dt = X.dtype
@@ -292,9 +309,10 @@ def masked_attn_fwd(mode, Bt, S, hd, X, Wqkv, WoT, head_idx_k, out=None, ws=None
     n = ph if m == MASK_FORWARD else H
     if T != Bt * S or tuple(Wqkv.shape) != (3, E_all, d) or tuple(WoT.shape) != (E_all, d) or H * hd != E_all:
         raise ValueError("attention shapes do not fit together")
+    hw = attn_saved_head_width(dt, hd)
     if out is None:
-        out = (torch.empty((T, d), dtype=dt, device=X.device), torch.empty((T, 3 * n * hd), dtype=dt, device=X.device),
-               torch.empty((T, n * hd), dtype=dt, device=X.device),
+        out = (torch.empty((T, d), dtype=dt, device=X.device), torch.empty((T, 3 * n * hw), dtype=dt, device=X.device),
+               torch.empty((T, n * hw), dtype=dt, device=X.device),
                torch.empty((Bt, n, S), dtype=torch.float32, device=X.device))
     Y, QKV, O, LSE = out
     if ws is None:
@@ -372,9 +390,10 @@ def block_fwd(mode, m, Bt, S, hd, X, Wqkv, WoT, W1, W3, W2T, out=None, ws=None):
                                  _dev(Y, dt, "Y"), None, None, None, None, None, None, None, 0, _stream())
         _check(st, "sdp_block_fwd")
         return Y, None
+    Es = H * attn_saved_head_width(dt, hd)
     if out is None:
         out = (torch.empty((T, d), dtype=dt, device=dev), torch.empty((T, d), dtype=dt, device=dev),
-               torch.empty((T, 3 * E), dtype=dt, device=dev), torch.empty((T, E), dtype=dt, device=dev),
+               torch.empty((T, 3 * Es), dtype=dt, device=dev), torch.empty((T, Es), dtype=dt, device=dev),
                torch.empty((Bt, H, S), dtype=torch.float32, device=dev), torch.empty((T, F), dtype=dt, device=dev),
                torch.empty((T, F), dtype=dt, device=dev))
     Y, Hm, QKV, O, LSE, G, U = out

@@ -569,9 +569,46 @@ __global__ void head_rows_kernel(const int32_t* __restrict__ head_idx, int ph, i
 
 int64_t ld_tokens(int64_t T) { return T + 64; } // see the MLP path: rows must not sit a power of two apart
 
-// the MFMA core takes bf16 with head width 64; everything else goes through the plain core
-bool mfma_core(int dtype, int hd) { return dtype == SDP_BF16 && hd == HD; }
+// Head width the core runs on.  The MFMA core takes bf16 heads of width 64; narrower bf16 heads (the paper's
+// 500M / 1B models have width 50) are padded to 64 with zero features: a zero feature of Q and K adds nothing to a
+// logit, a zero feature of V gives a zero feature of O, and every gradient of a zero feature is zero.  The padding
+// is made once, on the weights (pad_heads_kernel): the saved Q | K | V and O then carry 64 columns per head, of
+// which the last 64 - hd are zero.  Everything else (fp32, wider heads) goes through the plain core unpadded.
+int core_width(int dtype, int hd) { return dtype == SDP_BF16 && hd <= HD ? HD : hd; }
+bool mfma_core(int dtype, int hd) { return core_width(dtype, hd) == HD && dtype == SDP_BF16; }
 size_t esize(int dtype) { return dtype == SDP_F32 ? 4 : 2; }
+
+// out[(i hw + r)][:] = r < hd ? in[(heads ? heads[i] : i) hd + r][:] : 0 for i < n, r < hw, per stacked matrix
+// (blockIdx.y: matrix z of `in` [z][H hd][d] -> matrix z of `out` [z][n hw][d]); d % 8 == 0, 16 bytes per thread
+__global__ __launch_bounds__(256) void pad_heads_kernel(const uint16_t* __restrict__ in, const int32_t* __restrict__ heads,
+                                                        int n, int H, int hd, int hw, int d, uint16_t* __restrict__ out) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const int chunks = d / 8;
+    const int64_t total = (int64_t)n * hw * chunks;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int row = (int)(i / chunks), c = (int)(i % chunks);
+    const int head = row / hw, r = row % hw;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (r < hd) {
+        const int64_t src = (int64_t)blockIdx.y * H * hd + (int64_t)(heads ? heads[head] : head) * hd + r;
+        v = *(const u32x4_t*)(in + src * d + c * 8);
+    }
+    *(u32x4_t*)(out + ((int64_t)blockIdx.y * n * hw + row) * d + c * 8) = v;
+}
+
+// Row lists of the weight-gradient launch when heads are padded: for padded row m = i hw + r of the held heads
+//   gather[m]  = heads[i] hw + r            (row of the all-heads operand, backward masking)
+//   scatter[m] = r < hd ? (full ? heads[i] : i) hd + r : -1     (output row; padding rows are dropped)
+__global__ void pad_rows_kernel(const int32_t* __restrict__ heads, int ph, int hd, int hw, int full,
+                                int32_t* __restrict__ gather, int32_t* __restrict__ scatter) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= ph * hw) return;
+    const int i = m / hw, r = m % hw;
+    const int h = heads ? heads[i] : i;
+    gather[m] = h * hw + r;
+    scatter[m] = r < hd ? (full ? h : i) * hd + r : -1;
+}
 
 int check(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (mode != SDP_MASK_FORWARD && mode != SDP_MASK_BACKWARD) return SDP_ERR_INVALID_ARG;
@@ -579,11 +616,12 @@ int check(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (Bt < 1 || S < 1 || d < 1 || H < 1 || hd < 1) return SDP_ERR_INVALID_ARG;
     if (hd > 128) return SDP_ERR_UNSUPPORTED;
     if (ph < 1 || ph > H) return SDP_ERR_SHAPE;
-    if (dtype == SDP_BF16 && (d % 8 || hd % 8)) return SDP_ERR_SHAPE; // 16-byte rows
+    if (dtype == SDP_BF16 && (d % 8 || (hd > HD && hd % 8))) return SDP_ERR_SHAPE; // 16-byte rows; heads up to 64 are padded
     if (Bt > 65535 || H > 65535) return SDP_ERR_SHAPE;
-    if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)Bt * S * 3 * H * hd >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
+    const int hw = core_width(dtype, hd);
+    if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)Bt * S * 3 * H * hw >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
     // MFMA core: 32-bit byte offsets inside a sequence
-    if (mfma_core(dtype, hd) && (int64_t)S * 3 * H * hd * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE;
+    if (mfma_core(dtype, hd) && (int64_t)S * 3 * H * hw * 2 >= ((int64_t)1 << 32)) return SDP_ERR_SHAPE;
     return SDP_OK;
 }
 
@@ -592,28 +630,30 @@ int heads_run(int mode, int H, int ph) { return mode == SDP_MASK_FORWARD ? ph : 
 
 struct FwdWs {
     int32_t *rows_qkv, *rows_o;
-    void* WoC;
+    void *WoC, *Wp, *WoP; // Wp, WoP: padded copies of the run heads' rows of Wqkv / WoT (padded head widths only)
     size_t bytes;
 };
-FwdWs fwd_ws(char* w, size_t e, int d, int E) {
+FwdWs fwd_ws(char* w, size_t e, int d, int E, bool padded) {
     FwdWs r;
     size_t off = 0;
     auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
     r.rows_qkv = (int32_t*)take((size_t)3 * E * 4);
     r.rows_o = (int32_t*)take((size_t)E * 4);
     r.WoC = take((size_t)d * E * e);
+    r.Wp = padded ? take((size_t)3 * E * d * e) : nullptr;
+    r.WoP = padded ? take((size_t)E * d * e) : nullptr;
     r.bytes = off;
     return r;
 }
 
 struct BwdWs {
     int32_t *rows_qkv, *rows_o;
-    void *dO, *dQKV, *dQKVt, *Ot, *Xt, *dYt, *Wc, *split;
+    void *dO, *dQKV, *dQKVt, *Ot, *Xt, *dYt, *Wc, *split, *Wp, *WoP;
     float* delta;
     size_t bytes;
 };
-// E = width the core runs on, Eh = width of the held heads (equal under forward masking)
-BwdWs bwd_ws(char* w, size_t e, int64_t T, int d, int E, int Eh, int64_t stats) {
+// E = width the core runs on, Eh = width of the held heads (equal under forward masking), both in padded columns
+BwdWs bwd_ws(char* w, size_t e, int64_t T, int d, int E, int Eh, int64_t stats, bool padded) {
     BwdWs r;
     size_t off = 0;
     auto take = [&](size_t n) { char* p = w ? w + off : nullptr; off += round_up(n, 256); return p; };
@@ -629,8 +669,20 @@ BwdWs bwd_ws(char* w, size_t e, int64_t T, int d, int E, int Eh, int64_t stats) 
     r.Wc = take((size_t)d * 3 * E * e);
     const size_t sp = e == 2 ? gemm_split_ws_bytes(Eh, d, (int)T, 4) : 0; // partial sums of the batched weight-gradient launch
     r.split = sp ? take(sp) : nullptr;
+    r.Wp = padded ? take((size_t)3 * E * d * e) : nullptr;
+    r.WoP = padded ? take((size_t)E * d * e) : nullptr;
     r.bytes = off;
     return r;
+}
+
+// padded copies of the run heads' weight rows (heads == nullptr: all n = H heads in order)
+int pad_heads(const void* in, int nmat, const int32_t* heads, int n, int H, int hd, int hw, int d, void* out,
+              const char* name, hipStream_t s) {
+    ProfileScope ps(name, s);
+    const int64_t total = (int64_t)n * hw * (d / 8);
+    pad_heads_kernel<<<dim3((unsigned)((total + 255) / 256), nmat), 256, 0, s>>>((const uint16_t*)in, heads, n, H, hd, hw, d,
+                                                                                  (uint16_t*)out);
+    return launch_status();
 }
 
 int run(int dtype, const GemmDesc& g, hipStream_t s) {
@@ -650,15 +702,21 @@ int head_rows(const int32_t* head_idx, int ph, int H, int hd, int32_t* rows_qkv,
 
 using namespace sdp;
 
+extern "C" int sdp_masked_attn_saved_head_width(int dtype, int hd) {
+    if ((dtype != SDP_BF16 && dtype != SDP_F32) || hd < 1 || hd > 128) return 0;
+    return core_width(dtype, hd);
+}
+
 extern "C" size_t sdp_masked_attn_fwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (check(mode, dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
-    return fwd_ws(nullptr, esize(dtype), d, heads_run(mode, H, ph) * hd).bytes;
+    const int hw = core_width(dtype, hd);
+    return fwd_ws(nullptr, esize(dtype), d, heads_run(mode, H, ph) * hw, hw != hd).bytes;
 }
 
 extern "C" size_t sdp_masked_attn_bwd_workspace_bytes(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph) {
     if (check(mode, dtype, Bt, S, d, H, hd, ph) != SDP_OK) return 0;
-    const int hr = heads_run(mode, H, ph);
-    return bwd_ws(nullptr, esize(dtype), (int64_t)Bt * S, d, hr * hd, ph * hd, (int64_t)Bt * hr * S).bytes;
+    const int hr = heads_run(mode, H, ph), hw = core_width(dtype, hd);
+    return bwd_ws(nullptr, esize(dtype), (int64_t)Bt * S, d, hr * hw, ph * hw, (int64_t)Bt * hr * S, hw != hd).bytes;
 }
 
 extern "C" int sdp_masked_attn_fwd(int mode, int dtype, int Bt, int S, int d, int H, int hd, int ph, const void* X,
@@ -683,11 +741,19 @@ int sdp::attn_fwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
     if (mode == SDP_MASK_BACKWARD) ph = H;
     int rc;
     const bool gathered = mode == SDP_MASK_FORWARD;
-    const int T = Bt * S, E = ph * hd;
-    const FwdWs w = fwd_ws((char*)ws, esize(dtype), d, E);
+    const int hw = core_width(dtype, hd); // columns per head in the saved tensors
+    const bool padded = hw != hd;
+    const int T = Bt * S, E = ph * hw;
+    const FwdWs w = fwd_ws((char*)ws, esize(dtype), d, E, padded);
 
-    if (gathered) {
+    if (gathered && !padded) {
         rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
+        if (rc != SDP_OK) return rc;
+    }
+    if (padded) { // the run heads' rows of W_Q, W_K, W_V and W_O, each head padded to hw rows
+        rc = pad_heads(Wqkv, 3, gathered ? head_idx_k : nullptr, ph, H, hd, hw, d, w.Wp, "attn_pad_w", s);
+        if (rc != SDP_OK) return rc;
+        rc = pad_heads(WoT, 1, gathered ? head_idx_k : nullptr, ph, H, hd, hw, d, w.WoP, "attn_pad_w", s);
         if (rc != SDP_OK) return rc;
     }
 
@@ -695,8 +761,8 @@ int sdp::attn_fwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
     pj.name = "attn_qkv";
     pj.M = T, pj.N = 3 * E, pj.K = d;
     pj.A = X, pj.lda = d;
-    pj.B = Wqkv, pj.ldb = d;
-    if (gathered) pj.b_gather = w.rows_qkv, pj.b_rows = (int64_t)3 * H * hd;
+    pj.B = padded ? w.Wp : Wqkv, pj.ldb = d;
+    if (gathered && !padded) pj.b_gather = w.rows_qkv, pj.b_rows = (int64_t)3 * H * hd;
     pj.epilogue = EPI_STORE;
     pj.C = QKV_save, pj.ldc = 3 * E;
     rc = run(dtype, pj, s);
@@ -723,7 +789,8 @@ int sdp::attn_fwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
     }
     if (rc != SDP_OK) return rc;
 
-    rc = transpose_rows((int)esize(dtype), WoT, d, gathered ? w.rows_o : nullptr, E, d, w.WoC, E, "attn_wt_fwd", s);
+    rc = transpose_rows((int)esize(dtype), padded ? w.WoP : WoT, d, gathered && !padded ? w.rows_o : nullptr, E, d, w.WoC, E,
+                        "attn_wt_fwd", s);
     if (rc != SDP_OK) return rc;
     GemmDesc op;
     op.name = "attn_out";
@@ -761,12 +828,26 @@ int sdp::attn_bwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
     int rc;
     const bool gathered = mode == SDP_MASK_FORWARD;
     const int hr = heads_run(mode, H, ph);
-    const int T = Bt * S, E = hr * hd, Eh = ph * hd; // width the core runs on, width of the held heads
-    const BwdWs w = bwd_ws((char*)ws, esize(dtype), T, d, E, Eh, (int64_t)Bt * hr * S);
+    const int hw = core_width(dtype, hd);
+    const bool padded = hw != hd;
+    const int T = Bt * S, E = hr * hw, Eh = ph * hw; // width the core runs on, width of the held heads (padded columns)
+    const BwdWs w = bwd_ws((char*)ws, esize(dtype), T, d, E, Eh, (int64_t)Bt * hr * S, padded);
     // no list under backward masking: every head is held (ph = H), no row gather and no scatter are needed
     const bool all_heads = !gathered && head_idx_k == nullptr;
 
-    if (!all_heads) {
+    if (padded) {
+        rc = pad_heads(Wqkv, 3, gathered ? head_idx_k : nullptr, hr, H, hd, hw, d, w.Wp, "attn_pad_w", s);
+        if (rc != SDP_OK) return rc;
+        rc = pad_heads(WoT, 1, gathered ? head_idx_k : nullptr, hr, H, hd, hw, d, w.WoP, "attn_pad_w", s);
+        if (rc != SDP_OK) return rc;
+        if (want_dw) { // rows of the held heads in the padded operands, and where each of them goes (padding rows: nowhere)
+            ProfileScope ps("attn_rows", s);
+            pad_rows_kernel<<<(Eh + 255) / 256, 256, 0, s>>>(head_idx_k, ph, hd, hw, dw_layout == SDP_DW_SCATTER, w.rows_o,
+                                                             w.rows_qkv);
+            rc = launch_status();
+            if (rc != SDP_OK) return rc;
+        }
+    } else if (!all_heads) {
         rc = head_rows(head_idx_k, ph, H, hd, w.rows_qkv, w.rows_o, s);
         if (rc != SDP_OK) return rc;
     }
@@ -775,8 +856,8 @@ int sdp::attn_bwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
     go.name = "attn_dout";
     go.M = T, go.N = E, go.K = d;
     go.A = dY, go.lda = d;
-    go.B = WoT, go.ldb = d;
-    if (gathered) go.b_gather = w.rows_o, go.b_rows = (int64_t)H * hd;
+    go.B = padded ? w.WoP : WoT, go.ldb = d;
+    if (gathered && !padded) go.b_gather = w.rows_o, go.b_rows = (int64_t)H * hd;
     go.epilogue = EPI_STORE;
     go.C = w.dO, go.ldc = E;
     rc = run(dtype, go, s);
@@ -814,7 +895,8 @@ int sdp::attn_bwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
         if (rc != SDP_OK) return rc;
     }
 
-    rc = transpose_rows((int)esize(dtype), Wqkv, d, gathered ? w.rows_qkv : nullptr, 3 * E, d, w.Wc, 3 * E, "attn_wt_bwd", s);
+    rc = transpose_rows((int)esize(dtype), padded ? w.Wp : Wqkv, d, gathered && !padded ? w.rows_qkv : nullptr, 3 * E, d, w.Wc,
+                        3 * E, "attn_wt_bwd", s);
     if (rc != SDP_OK) return rc;
     GemmDesc dx;
     dx.name = "attn_dx";
@@ -846,7 +928,12 @@ int sdp::attn_bwd_impl(int mode, int dtype, int Bt, int S, int d, int H, int hd,
     dw.epilogue = EPI_STORE;
     dw.ldc = d;
     dw.c_scatter = dw_layout == SDP_DW_SCATTER && !all_heads ? w.rows_o : nullptr; // rows of the held heads inside each matrix
-    const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : Eh) * d;
+    if (padded) { // padded rows: w.rows_o = the held heads' rows of the operands, w.rows_qkv = output rows (-1: dropped)
+        if (gathered) dw.a_gather = nullptr;
+        else dw.a_gather = w.rows_o, dw.a_rows = E;
+        dw.c_scatter = w.rows_qkv;
+    }
+    const int64_t part = (int64_t)(dw_layout == SDP_DW_SCATTER ? H * hd : ph * hd) * d;
     dw.nbatch = 4;
     const size_t e = esize(dtype);
     for (int i = 0; i < 3; ++i) {

@@ -473,7 +473,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
             const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
             if (m < g.M && n < g.N) {
                 const int64_t orow = scatter ? scatter[m] : m;
-                *(u32x4*)(out + orow * ld + n) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                if (orow >= 0) *(u32x4*)(out + orow * ld + n) = u32x4{lo[0], lo[1], hi[0], hi[1]}; // a negative entry drops the row
             }
         }
     };
@@ -868,6 +868,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceArgs r) {
     }
     uint16_t* out = z == 0 ? r.Cb[0] : (z == 1 ? r.Cb[1] : (z == 2 ? r.Cb[2] : r.Cb[3]));
     const int64_t row = r.cs ? r.cs[m] : m;
+    if (row < 0) return; // dropped row
     *(u32x4*)(out + row * r.ldc + n) = u32x4{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3])};
 }
 

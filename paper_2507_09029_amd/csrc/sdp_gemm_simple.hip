@@ -141,6 +141,7 @@ __global__ __launch_bounds__(NT) void gemm_simple_kernel(Dev g) {
             if (n >= g.N) continue;
             if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
                 const int64_t row = g.cs ? g.cs[m] : m;
+                if (row < 0) continue; // dropped row
                 const float r = g.R ? ld<T>((const T*)g.R + (int64_t)m * g.ldr + n) : 0.f;
                 st<T>((T*)g.C + row * g.ldc + n, acc[i][j] + r);
             } else if (EPI == EPI_SWIGLU_FWD) {

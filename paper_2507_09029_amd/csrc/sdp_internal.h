@@ -41,7 +41,7 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // with a_gather (not together with a_km).
 // A second operand pair (A2, B2) with the same shapes and strides is used by two of the epilogues.
 enum Epilogue {
-    EPI_STORE = 0,       // C[rc(m) * ldc + n] = acc                      (rc: optional row scatter)
+    EPI_STORE = 0,       // C[rc(m) * ldc + n] = acc      (rc: optional row scatter; rc(m) < 0 drops row m)
     EPI_DUAL_ACC = 1,    // as STORE with acc = A.B + A2.B2
     EPI_SWIGLU_FWD = 2,  // g = A.B, u = A.B2: G = g, U = u, Act = silu(g) * u, all [M][N] (ld = ldc)
     EPI_SWIGLU_BWD = 3   // da = A.B; with g = Gin[m][n], u = Uin[m][n]  (ld = ldg):

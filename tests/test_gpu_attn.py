@@ -71,10 +71,14 @@ def run_case(sdp, orc, w, workers, dw_layout="compact", mode="fm"):
         # per-token tensors: one scale per row (a token's output averages over all earlier tokens, so the row
         # norms fall with the position); weight gradients: one scale per tensor
         assert_close_rows(workloads.to_f64(Y), ref["Y"], tol, "Y")
-        got_qkv = workloads.to_f64(QKV)
+        # narrow bf16 heads are saved padded to 64 columns: the padding must hold exact zeros
+        hw = sdp.attn_saved_head_width(QKV.dtype, w.hd)
+        if hw != w.hd:
+            assert not bool(QKV.reshape(w.T, -1, hw)[:, :, w.hd:].any()) and not bool(O.reshape(w.T, -1, hw)[:, :, w.hd:].any())
+        got_qkv = workloads.to_f64(sdp.attn_unpad(QKV, w.hd))
         for i, name in enumerate("QKV"):
             assert_close_rows(got_qkv[:, i * E:(i + 1) * E], ref[name][:, rows], tol, name)
-        assert_close_rows(workloads.to_f64(O), ref["O"][:, rows], tol, "O")
+        assert_close_rows(workloads.to_f64(sdp.attn_unpad(O, w.hd)), ref["O"][:, rows], tol, "O")
         # base-2 log-sum-exp of the scaled logits, from the oracle's Q and K
         q = ref["Q"][:, rows].reshape(w.Bt, w.S, -1, w.hd)
         kk = ref["K"][:, rows].reshape(w.Bt, w.S, -1, w.hd)
@@ -125,8 +129,12 @@ CASES = [
     AttnWorkload("f32_hd64", 2, 150, 96, 4, 64, 2, 4, 38, "f32"),
     AttnWorkload("f32_hd50_odd_sizes", 2, 93, 75, 3, 50, 2, 2, 39, "f32"),
     AttnWorkload("f32_hd128", 1, 70, 64, 2, 128, 1, 2, 40, "f32"),
-    AttnWorkload("bf16_hd32", 2, 130, 128, 4, 32, 2, 4, 42),
+    AttnWorkload("bf16_hd32", 2, 130, 128, 4, 32, 2, 4, 42),               # padded to 64: MFMA core
     AttnWorkload("bf16_hd96", 1, 100, 72, 3, 96, 2, 2, 43),
+    # the paper's 500M / 1B head width (hidden 1200 / 24 heads, 1600 / 32 heads): bf16 heads of 50 padded to 64
+    AttnWorkload("bf16_hd50", 2, 200, 200, 4, 50, 2, 4, 44),
+    AttnWorkload("bf16_hd50_all_heads_odd", 1, 333, 104, 3, 50, 3, 2, 45),
+    AttnWorkload("bf16_hd50_paper_500M_width", 1, 256, 1200, 24, 50, 12, 4, 46),
 ]
 
 
@@ -138,6 +146,13 @@ def test_attention_all_outputs(sdp, orc, w):
 def test_scatter_layout_leaves_other_heads_alone(sdp, orc):
     run_case(sdp, orc, CASES[2], [1], dw_layout="scatter")
     run_case(sdp, orc, CASES[5], [0], dw_layout="scatter", mode="bm")
+    run_case(sdp, orc, CASES[12], [1], dw_layout="scatter")            # padded heads: the padding rows go nowhere
+    run_case(sdp, orc, CASES[12], [0], dw_layout="scatter", mode="bm")
+
+
+def test_padded_heads_backward_masking(sdp, orc):
+    run_case(sdp, orc, CASES[12], [0, 1], mode="bm")
+    run_case(sdp, orc, CASES[13], [0], mode="bm")
 
 
 BM_CASES = [CASES[0], CASES[2], CASES[3], CASES[4], CASES[5], CASES[6], CASES[7], CASES[8], CASES[10]]
@@ -154,8 +169,8 @@ def test_argument_errors(sdp):
     Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(w))
     X, _ = workloads.attn_batch(w, 0)
     idx = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
-    with pytest.raises(sdp.SdpError):  # bf16 rows must be multiples of 16 bytes: head width 20 of 4 x 64 = 256 rows
-        sdp.masked_attn_fwd("fm", w.Bt, w.S, 20, X.cuda(), Wqkv[:, :240].contiguous(), WoT[:240].contiguous(), idx)
+    with pytest.raises(sdp.SdpError):  # bf16 heads wider than 64 are not padded: rows must be multiples of 16 bytes (3 x 84 = 252 rows)
+        sdp.masked_attn_fwd("fm", w.Bt, w.S, 84, X.cuda(), Wqkv[:, :252].contiguous(), WoT[:252].contiguous(), idx)
     with pytest.raises(sdp.SdpError):  # more held heads than heads
         sdp.masked_attn_fwd("fm", w.Bt, w.S, w.hd, X.cuda(), Wqkv, WoT, torch.arange(5, dtype=torch.int32, device="cuda"))
 

@@ -81,6 +81,8 @@ class AttnWorkload:
 
 
 ATTN_500M = AttnWorkload("attn_bf16_fm_500M", 4, 2048, 1536, 24, 64, 12, 4)
+# the paper's own 500M width (App. "Hyperparameters for LLM Architecture": hidden 1200, 24 heads, i.e. head width 50)
+ATTN_500M_HD50 = AttnWorkload("attn_bf16_fm_500M_paper_width", 4, 2048, 1200, 24, 50, 12, 4)
 
 CONFIG1 = MlpWorkload("config1_f32_fm", "f32", 256, 256, 1024, 512, 4, "fm")
 CONFIG2 = MlpWorkload("config2_bf16_fm_500M", "bf16", 8192, 1536, 4096, 2048, 4, "fm")
