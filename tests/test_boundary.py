@@ -188,7 +188,13 @@ def test_attention_arguments_are_checked_on_the_host():
     assert sdp.masked_attn_bwd_workspace_bytes("bm", torch.bfloat16, 4, 2048, 1536, 24, 64, 12) >= 8192 * 1536 * 2 * (1 + 3 + 3 + 1)
     assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.float32, 4, 2048, 1536, 24, 64, 12) > ws   # fp32 elements
     assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.float32, 4, 1024, 1200, 24, 50, 12) > 0    # the paper's head width
-    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 50, 12) == 0  # bf16: 16-byte rows
+    # bf16 heads up to 64 wide are padded to 64 (the paper's 50 included); wider ones must keep 16-byte rows
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1200, 24, 50, 12) > \
+        sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1200, 24, 64, 12)          # padded weight copies
+    assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 84, 12) == 0
+    assert L.sdp_masked_attn_saved_head_width(BF16, 50) == 64 and L.sdp_masked_attn_saved_head_width(BF16, 64) == 64
+    assert L.sdp_masked_attn_saved_head_width(BF16, 96) == 96 and L.sdp_masked_attn_saved_head_width(F32, 50) == 50
+    assert L.sdp_masked_attn_saved_head_width(BF16, 0) == 0 and L.sdp_masked_attn_saved_head_width(9, 64) == 0
     assert sdp.masked_attn_fwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1536, 24, 136, 12) == 0  # wider than 128
     assert sdp.masked_attn_bwd_workspace_bytes("fm", torch.bfloat16, 4, 2048, 1532, 24, 64, 12) == 0  # d % 8
     fwd = lambda *a: L.sdp_masked_attn_fwd(*a)
@@ -198,7 +204,7 @@ def test_attention_arguments_are_checked_on_the_host():
     assert fwd(*([2] + args[1:])) == invalid                   # unknown regime
     assert fwd(*(args[:1] + [7] + args[2:])) == invalid        # unknown dtype
     assert fwd(*(args[:6] + [136] + args[7:])) == unsupported  # head width beyond 128
-    assert fwd(*(args[:6] + [50] + args[7:])) == shape         # bf16 rows must be 16-byte multiples
+    assert fwd(*(args[:6] + [84] + args[7:])) == shape         # bf16 heads wider than 64: rows must be 16-byte multiples
     assert fwd(*(args[:7] + [5] + args[8:])) == shape          # more held heads than heads
     assert fwd(*(args[:2] + [0] + args[3:])) == invalid        # no sequence
     assert fwd(*(args[:8] + [None] + args[9:])) == invalid     # X missing
