@@ -461,8 +461,45 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     auto strip_get = [&](const unsigned char* strip, int cbase, int q) {
         return *(const u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2);
     };
-    // strip -> global: rows of `out` (leading dimension ld), optional row scatter
-    auto strip_store = [&](const unsigned char* strip, uint16_t* out, int64_t ld, const int32_t* scatter, int i) {
+    // Global accesses of the epilogue go through buffer resources whose base is this wave's corner of the tile and
+    // whose extent ends with the matrix's last row: for an offset at or beyond the extent the hardware returns zero
+    // to a load and drops a store.  A lane whose columns lie outside the matrix (or whose row is dropped) is given
+    // such an offset.  The accesses are then unconditional instructions, so the count of those in flight is known
+    // and the wait for the next fragment row's loads leaves this row's stores in flight (behind a branch per store
+    // the wait would be for everything).  Offsets inside a wave's part stay below 2^30 (see gemm_mfma_supported).
+    constexpr uint32_t kOutside = 0x80000000u;
+    const int wrow0 = m0 + WM * wm; // first output row of this wave
+    const int wrows = g.M - wrow0 < 0 ? 0 : (g.M - wrow0 > WM ? WM : g.M - wrow0); // its rows inside the matrix
+    // the base is the same in all lanes; saying so keeps the resource in scalar registers
+    auto uniform_rsrc = [](const uint16_t* base, uint32_t bytes) {
+        const uint64_t a = (uint64_t)base;
+        const uint64_t u = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(a >> 32)) << 32) |
+                           (uint32_t)__builtin_amdgcn_readfirstlane((int)a);
+        return __builtin_amdgcn_make_buffer_rsrc((void*)u, 0, (int)__builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
+    };
+    auto wave_rsrc = [&](const uint16_t* base, int64_t ld) {
+        return uniform_rsrc(base + (int64_t)wrow0 * ld + wcol0, (uint32_t)(wrows * ld * 2));
+    };
+    // byte offset of chunk c of fragment row 0 (rows of leading dimension ld); fragment row i lies 64 i ld bytes on
+    auto chunk_offset = [&](int c, int64_t ld) {
+        const int row = c / CPR, cc = c % CPR;
+        return (NCH % 64 == 0 || c < NCH) && wcol0 + cc * 8 < g.N ? (uint32_t)((row * ld + cc * 8) * 2) : kOutside;
+    };
+    // strip -> global: rows of `out` (leading dimension ld)
+    auto strip_store = [&](const unsigned char* strip, uint16_t* out, int64_t ld, int i) {
+        const __amdgpu_buffer_rsrc_t rs = wave_rsrc(out, ld);
+#pragma unroll
+        for (int it = 0; it < (NCH + 63) / 64; ++it) {
+            const int c = NCH % 64 == 0 || it * 64 + lane < NCH ? it * 64 + lane : 0;
+            const int row = c / CPR, cc = c % CPR;
+            const u32x2 lo = *(const u32x2*)(strip + row * RS + cc * 16);
+            const u32x2 hi = *(const u32x2*)(strip + row * RS + cc * 16 + 8);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{lo[0], lo[1], hi[0], hi[1]}, rs,
+                                                   chunk_offset(it * 64 + lane, ld) + (uint32_t)(64 * i * ld), 0, 0);
+        }
+    };
+    // the same with a row scatter (a negative entry drops the row): destination rows may lie anywhere, plain stores
+    auto strip_store_scatter = [&](const unsigned char* strip, uint16_t* out, int64_t ld, const int32_t* scatter, int i) {
 #pragma unroll
         for (int it = 0; it < (NCH + 63) / 64; ++it) {
             const int c = it * 64 + lane;
@@ -470,10 +507,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
             const int row = c / CPR, cc = c % CPR;
             const u32x2 lo = *(const u32x2*)(strip + row * RS + cc * 16);
             const u32x2 hi = *(const u32x2*)(strip + row * RS + cc * 16 + 8);
-            const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
+            const int m = wrow0 + 32 * i + row, n = wcol0 + cc * 8;
             if (m < g.M && n < g.N) {
-                const int64_t orow = scatter ? scatter[m] : m;
-                if (orow >= 0) *(u32x4*)(out + orow * ld + n) = u32x4{lo[0], lo[1], hi[0], hi[1]}; // a negative entry drops the row
+                const int64_t orow = scatter[m];
+                if (orow >= 0) *(u32x4*)(out + orow * ld + n) = u32x4{lo[0], lo[1], hi[0], hi[1]};
             }
         }
     };
@@ -481,14 +518,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // separate so that the loads of fragment row i + 1 fly while row i is computed and stored.
     constexpr int NLD = (NCH + 63) / 64;
     auto strip_fetch = [&](u32x4 (&v)[NLD], const uint16_t* in, int64_t ld, int i) {
+        const __amdgpu_buffer_rsrc_t rs = wave_rsrc(in, ld);
 #pragma unroll
-        for (int it = 0; it < NLD; ++it) {
-            const int c = it * 64 + lane;
-            const int row = c / CPR, cc = c % CPR;
-            const int m = m0 + WM * wm + 32 * i + row, n = wcol0 + cc * 8;
-            v[it] = u32x4{0u, 0u, 0u, 0u};
-            if ((NCH % 64 == 0 || c < NCH) && m < g.M && n < g.N) v[it] = *(const u32x4*)(in + (int64_t)m * ld + n);
-        }
+        for (int it = 0; it < NLD; ++it)
+            v[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, chunk_offset(it * 64 + lane, ld) + (uint32_t)(64 * i * ld), 0, 0);
     };
     auto strip_commit = [&](unsigned char* strip, const u32x4 (&v)[NLD]) {
 #pragma unroll
@@ -501,32 +534,37 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     };
 
-    // neuron-major copies: output row of each of this wave's SW strip columns.  Without an index list it
-    // is the column itself; with one (backward masking) it is the column's rank in the ascending list,
-    // or -1 for columns that are not listed.
+    // neuron-major copies: output row of each of this wave's SW strip columns, relative to trow0.  Without an
+    // index list it is the column itself; with one (backward masking) it is the column's rank in the ascending
+    // list, or -1 for columns that are not listed.
     int32_t* ranktab = (int32_t*)(strip0 + Geo::NSTRIP * Geo::STRIP);
+    int trow0 = wcol0; // output row of the first (listed) column of this wave
     if (EPI == EPI_SWIGLU_BWD && g.Ct) {
-        for (int c = lane; c < SW; c += 64) ranktab[c] = g.cidx ? -1 : (wcol0 + c < g.N ? wcol0 + c : -1);
         if (g.cidx) {
             int lo = 0, hi = g.pc; // first listed column >= wcol0
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
                 if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
             }
-            for (int t = lo + lane; t < g.pc; t += 64) {
+            trow0 = __builtin_amdgcn_readfirstlane(lo);
+        }
+        for (int c = lane; c < SW; c += 64) ranktab[c] = g.cidx ? -1 : (wcol0 + c < g.N ? c : -1);
+        if (g.cidx) {
+            for (int t = trow0 + lane; t < g.pc; t += 64) {
                 const int c = g.cidx[t] - wcol0;
                 if (c >= SW) break;
-                ranktab[c] = t;
+                ranktab[c] = t - trow0;
             }
         }
     }
-    // strip -> neuron-major global: out[ranktab[column]][token].  A transposing LDS read hands the lanes of
-    // a 16-lane block, for 4 adjacent strip columns, 4 consecutive rows each; two of them give every lane
+    // strip -> neuron-major global: out[trow0 + ranktab[column]][token].  A transposing LDS read hands the lanes
+    // of a 16-lane block, for 4 adjacent strip columns, 4 consecutive rows each; two of them give every lane
     // 8 consecutive tokens of one column, i.e. one 16-byte store, and 4 lanes cover the 32 tokens (64 bytes).
     auto strip_store_t = [&](const unsigned char* strip, uint16_t* out, int i) {
         const int gi = lane >> 4, li = lane & 15, q = li >> 2, cn = li & 3;
         const int src_row = 8 * (li & 3) + (li >> 2); // as source lane: rows 8 q' + e for the lanes that receive from it
-        const int m = m0 + WM * wm + 32 * i + 8 * q;
+        const bool m_in = 32 * i + 8 * q < wrows;
+        const __amdgpu_buffer_rsrc_t rs = uniform_rsrc(out + (int64_t)trow0 * g.ldct + wrow0, kOutside);
 #pragma unroll
         for (int it = 0; it < SW / 16; ++it) {
             const int c4 = 16 * it + 4 * gi;
@@ -534,18 +572,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
             const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
             const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * RS));
             const int row = ranktab[c4 + cn];
-            if (row >= 0 && m < g.M) {
-                const u32x2 a = __builtin_bit_cast(u32x2, h0), b = __builtin_bit_cast(u32x2, h1);
-                *(u32x4*)(out + (int64_t)row * g.ldct + m) = u32x4{a[0], a[1], b[0], b[1]};
-            }
+            const uint32_t off = row >= 0 && m_in ? (uint32_t)((row * g.ldct + 32 * i + 8 * q) * 2) : kOutside;
+            const u32x2 a = __builtin_bit_cast(u32x2, h0), b = __builtin_bit_cast(u32x2, h1);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{a[0], a[1], b[0], b[1]}, rs, off, 0, 0);
         }
     };
 
-    u32x4 gpre[NLD], upre[NLD]; // SWIGLU_BWD: G and U of the next fragment row, in flight
-    if (EPI == EPI_SWIGLU_BWD) {
-        strip_fetch(gpre, g.Gin, g.ldg, 0);
-        strip_fetch(upre, g.Uin, g.ldg, 0);
-    }
     // residual of a single-problem store (the skip connection of a block): fetched one fragment row ahead like G, U
     constexpr bool kResidual = (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) && !kBatched;
     u32x4 rpre[kResidual ? NLD : 1];
@@ -553,99 +585,115 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     if constexpr (kResidual) {
         if (has_r) strip_fetch(rpre, g.R, g.ldr, 0);
     }
+    // The fragment rows, one after the other.  kT: SWIGLU_BWD with the neuron-major copies; the loop exists once
+    // per case, so that between a row's loads and the next row's use of them the stores issued are the same on
+    // every path and can be left in flight.
+    auto rows = [&](auto with_t) __attribute__((always_inline)) {
+        constexpr bool kT = decltype(with_t)::value;
+        u32x4 gpre[NLD], upre[NLD]; // SWIGLU_BWD: G and U of the next fragment row, in flight
+        if (EPI == EPI_SWIGLU_BWD) {
+            strip_fetch(gpre, g.Gin, g.ldg, 0);
+            strip_fetch(upre, g.Uin, g.ldg, 0);
+        }
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        // keep the scheduler from pulling later fragment rows' work (and its registers) up here
-        __builtin_amdgcn_sched_barrier(0);
-        if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
-            if constexpr (kResidual) {
-                if (has_r) {
-                    // row chunks -> strip -> each lane's own accumulator positions; added in fp32
-                    strip_commit(strip0, rpre);
-                    if (i + 1 < FM) strip_fetch(rpre, g.R, g.ldr, i + 1);
-                    u32x2 rq[FN][4];
+        for (int i = 0; i < FM; ++i) {
+            // keep the scheduler from pulling later fragment rows' work (and its registers) up here
+            __builtin_amdgcn_sched_barrier(0);
+            if (EPI == EPI_STORE || EPI == EPI_DUAL_ACC) {
+                if constexpr (kResidual) {
+                    if (has_r) {
+                        // row chunks -> strip -> each lane's own accumulator positions; added in fp32
+                        strip_commit(strip0, rpre);
+                        if (i + 1 < FM) strip_fetch(rpre, g.R, g.ldr, i + 1);
+                        u32x2 rq[FN][4];
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
+                        for (int j = 0; j < FN; ++j)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) rq[j][q] = strip_get(strip0, 32 * j, q);
+                            for (int q = 0; q < 4; ++q) rq[j][q] = strip_get(strip0, 32 * j, q);
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
+                        for (int j = 0; j < FN; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                acc[i][j][4 * q] += lo_bf16(rq[j][q][0]);
+                                acc[i][j][4 * q + 1] += hi_bf16(rq[j][q][0]);
+                                acc[i][j][4 * q + 2] += lo_bf16(rq[j][q][1]);
+                                acc[i][j][4 * q + 3] += hi_bf16(rq[j][q][1]);
+                            }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        strip_put(strip0, 32 * j, q,
+                                  pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+                if (g.cs) strip_store_scatter(strip0, gC, g.ldc, g.cs, i); else strip_store(strip0, gC, g.ldc, i);
+            } else if (EPI == EPI_SWIGLU_FWD) {
+                // fragments 2 jj (gate) and 2 jj + 1 (up) cover the same 32 neurons
+#pragma unroll
+                for (int which = 0; which < 3; ++which) {
+#pragma unroll
+                    for (int jj = 0; jj < FN / 2; ++jj)
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            acc[i][j][4 * q] += lo_bf16(rq[j][q][0]);
-                            acc[i][j][4 * q + 1] += hi_bf16(rq[j][q][0]);
-                            acc[i][j][4 * q + 2] += lo_bf16(rq[j][q][1]);
-                            acc[i][j][4 * q + 3] += hi_bf16(rq[j][q][1]);
+                            float v[4];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
+                                v[r] = which == 0 ? gv : (which == 1 ? uv : swiglu_fwd<false>(gv, uv));
+                            }
+                            strip_put(strip0, 32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
                         }
+                    strip_store(strip0, which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, i);
                 }
-            }
+            } else { // EPI_SWIGLU_BWD: three strips per wave (dG, dU, Act)
+                unsigned char* strip1 = strip0 + Geo::STRIP;
+                unsigned char* strip2 = strip1 + Geo::STRIP;
+                strip_commit(strip0, gpre);
+                strip_commit(strip1, upre);
+                if (i + 1 < FM) {
+                    strip_fetch(gpre, g.Gin, g.ldg, i + 1);
+                    strip_fetch(upre, g.Uin, g.ldg, i + 1);
+                }
+                u32x2 gq[FN][4], uq[FN][4];
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    strip_put(strip0, 32 * j, q,
-                              pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
-            strip_store(strip0, gC, g.ldc, g.cs, i);
-        } else if (EPI == EPI_SWIGLU_FWD) {
-            // fragments 2 jj (gate) and 2 jj + 1 (up) cover the same 32 neurons
-#pragma unroll
-            for (int which = 0; which < 3; ++which) {
-#pragma unroll
-                for (int jj = 0; jj < FN / 2; ++jj)
+                for (int j = 0; j < FN; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        float v[4];
+                        gq[j][q] = strip_get(strip0, 32 * j, q);
+                        uq[j][q] = strip_get(strip1, 32 * j, q);
+                    }
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float dg[4], du[4], act[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
-                            v[r] = which == 0 ? gv : (which == 1 ? uv : swiglu_fwd<false>(gv, uv));
+                            const uint32_t gw = gq[j][q][r >> 1], uw = uq[j][q][r >> 1];
+                            const float gv = (r & 1) ? hi_bf16(gw) : lo_bf16(gw);
+                            const float uv = (r & 1) ? hi_bf16(uw) : lo_bf16(uw);
+                            swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg[r], du[r], act[r]);
                         }
-                        strip_put(strip0, 32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
+                        strip_put(strip0, 32 * j, q, pack4(dg[0], dg[1], dg[2], dg[3]));
+                        strip_put(strip1, 32 * j, q, pack4(du[0], du[1], du[2], du[3]));
+                        strip_put(strip2, 32 * j, q, pack4(act[0], act[1], act[2], act[3]));
                     }
-                strip_store(strip0, which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, nullptr, i);
-            }
-        } else { // EPI_SWIGLU_BWD: three strips per wave (dG, dU, Act)
-            unsigned char* strip1 = strip0 + Geo::STRIP;
-            unsigned char* strip2 = strip1 + Geo::STRIP;
-            strip_commit(strip0, gpre);
-            strip_commit(strip1, upre);
-            if (i + 1 < FM) {
-                strip_fetch(gpre, g.Gin, g.ldg, i + 1);
-                strip_fetch(upre, g.Uin, g.ldg, i + 1);
-            }
-            u32x2 gq[FN][4], uq[FN][4];
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    gq[j][q] = strip_get(strip0, 32 * j, q);
-                    uq[j][q] = strip_get(strip1, 32 * j, q);
+                strip_store(strip0, g.C, g.ldc, i);
+                strip_store(strip1, g.C2, g.ldc, i);
+                if (g.C3) strip_store(strip2, g.C3, g.ldc, i);
+                if constexpr (kT) {
+                    strip_store_t(strip0, g.Ct, i);
+                    strip_store_t(strip1, g.Ct2, i);
+                    strip_store_t(strip2, g.Ct3, i);
                 }
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float dg[4], du[4], act[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const uint32_t gw = gq[j][q][r >> 1], uw = uq[j][q][r >> 1];
-                        const float gv = (r & 1) ? hi_bf16(gw) : lo_bf16(gw);
-                        const float uv = (r & 1) ? hi_bf16(uw) : lo_bf16(uw);
-                        swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg[r], du[r], act[r]);
-                    }
-                    strip_put(strip0, 32 * j, q, pack4(dg[0], dg[1], dg[2], dg[3]));
-                    strip_put(strip1, 32 * j, q, pack4(du[0], du[1], du[2], du[3]));
-                    strip_put(strip2, 32 * j, q, pack4(act[0], act[1], act[2], act[3]));
-                }
-            strip_store(strip0, g.C, g.ldc, nullptr, i);
-            strip_store(strip1, g.C2, g.ldc, nullptr, i);
-            if (g.C3) strip_store(strip2, g.C3, g.ldc, nullptr, i);
-            if (g.Ct) {
-                strip_store_t(strip0, g.Ct, i);
-                strip_store_t(strip1, g.Ct2, i);
-                strip_store_t(strip2, g.Ct3, i);
             }
         }
+    };
+    if constexpr (EPI == EPI_SWIGLU_BWD) {
+        if (g.Ct) rows(std::true_type{}); else rows(std::false_type{});
+    } else {
+        rows(std::false_type{});
     }
 }
 
@@ -902,6 +950,10 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     // 16-byte global chunks, 16-deep MFMA steps, 32-bit byte offsets inside each operand
     if (d.K % 16 || d.lda % 8 || d.ldb % 8 || d.N % 8 || d.ldc % 8) return false;
     if (d.a_km) return false; // depth-major A goes through the transposing pre-pass or the plain kernel
+    // the epilogue addresses a wave's part of the tile (at most 128 rows) with 32-bit byte offsets below 2^31
+    constexpr int64_t kMaxLd = (int64_t)1 << 22;
+    if (d.ldc >= kMaxLd || (d.R && d.ldr >= kMaxLd)) return false;
+    if (d.epilogue == EPI_SWIGLU_BWD && (d.ldg >= kMaxLd || (d.Ct && d.ldct >= kMaxLd))) return false;
     if ((d.a_rows > 0 ? d.a_rows : (int64_t)d.M) * d.lda * 2 >= ((int64_t)1 << 32)) return false;
     if (d.a_gather && (d.a_rows <= 0 || d.epilogue == EPI_DUAL_ACC)) return false;
     if ((d.b_rows > 0 ? d.b_rows : (int64_t)d.N) * d.ldb * 2 >= ((int64_t)1 << 32)) return false;
