@@ -80,8 +80,7 @@ struct Dev {
     int64_t ldg;
     uint16_t *Ct, *Ct2, *Ct3; // SWIGLU_BWD: neuron-major (transposed) copies [column or rank][ldct], optional
     int64_t ldct;
-    const int32_t* cidx;
-    int pc;
+    const int32_t* crank; // encoded rank of every column, or null: every column is listed
     int tiles_m, tiles_n, ntot; // ntot = tiles of all problems of the launch
     int group_m, nbatch;
     int np0; // batched launches: > 0 = the first np0 problems share one B operand and the others another (see tile_of_shared)
@@ -215,6 +214,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     }
     const int m0 = tile_m * BM;
     const int n0 = kFwd ? tile_n * (BN / 2) : tile_n * BN; // SWIGLU_FWD: BN columns = BN/2 neurons x {gate, up}
+    // SWIGLU_BWD with neuron-major copies: the encoded rank of each of this wave's output columns (at most two
+    // per lane), fetched now so that the epilogue does not wait for it; a column outside the matrix counts as
+    // not listed
+    int crank_pre[2] = {-1, -1};
+    if (EPI == EPI_SWIGLU_BWD && g.Ct) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c = n0 + Geo::WN * wn + 64 * h + lane;
+            if (64 * h < Geo::WN && c < g.N) crank_pre[h] = g.crank ? g.crank[c] : c;
+        }
+    }
 
     // ---- depth steps; a partial last step (K % 64 in {16, 32, 48}) reads its missing chunks from a
     // zero buffer, so that every step issues the same loads and runs all four MFMA sub-steps ----
@@ -485,8 +495,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         const int row = c / CPR, cc = c % CPR;
         return (NCH % 64 == 0 || c < NCH) && wcol0 + cc * 8 < g.N ? (uint32_t)((row * ld + cc * 8) * 2) : kOutside;
     };
+    // cache policy of an epilogue access: kStream marks data this kernel touches once (non-temporal), so that it
+    // does not push the operand panels, which every tile of a row or column re-reads, out of the L2
+    constexpr int kKeep = 0, kStream = 2;
     // strip -> global: rows of `out` (leading dimension ld)
-    auto strip_store = [&](const unsigned char* strip, uint16_t* out, int64_t ld, int i) {
+    auto strip_store = [&](const unsigned char* strip, uint16_t* out, int64_t ld, int i, auto policy) {
         const __amdgpu_buffer_rsrc_t rs = wave_rsrc(out, ld);
 #pragma unroll
         for (int it = 0; it < (NCH + 63) / 64; ++it) {
@@ -495,7 +508,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
             const u32x2 lo = *(const u32x2*)(strip + row * RS + cc * 16);
             const u32x2 hi = *(const u32x2*)(strip + row * RS + cc * 16 + 8);
             __builtin_amdgcn_raw_buffer_store_b128(u32x4{lo[0], lo[1], hi[0], hi[1]}, rs,
-                                                   chunk_offset(it * 64 + lane, ld) + (uint32_t)(64 * i * ld), 0, 0);
+                                                   chunk_offset(it * 64 + lane, ld) + (uint32_t)(64 * i * ld), 0, decltype(policy)::value);
         }
     };
     // the same with a row scatter (a negative entry drops the row): destination rows may lie anywhere, plain stores
@@ -517,11 +530,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // global -> registers -> strip: the same chunk mapping, zero outside the matrix.  The two halves are
     // separate so that the loads of fragment row i + 1 fly while row i is computed and stored.
     constexpr int NLD = (NCH + 63) / 64;
-    auto strip_fetch = [&](u32x4 (&v)[NLD], const uint16_t* in, int64_t ld, int i) {
+    auto strip_fetch = [&](u32x4 (&v)[NLD], const uint16_t* in, int64_t ld, int i, auto policy) {
         const __amdgpu_buffer_rsrc_t rs = wave_rsrc(in, ld);
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
-            v[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, chunk_offset(it * 64 + lane, ld) + (uint32_t)(64 * i * ld), 0, 0);
+            v[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, chunk_offset(it * 64 + lane, ld) + (uint32_t)(64 * i * ld), 0,
+                                                           decltype(policy)::value);
     };
     auto strip_commit = [&](unsigned char* strip, const u32x4 (&v)[NLD]) {
 #pragma unroll
@@ -535,27 +549,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     };
 
     // neuron-major copies: output row of each of this wave's SW strip columns, relative to trow0.  Without an
-    // index list it is the column itself; with one (backward masking) it is the column's rank in the ascending
-    // list, or -1 for columns that are not listed.
+    // index list it is the column itself; with one (backward masking) it is the column's rank among the listed
+    // columns, or -1 for columns that are not listed.  The encoded ranks were fetched before the main loop.
     int32_t* ranktab = (int32_t*)(strip0 + Geo::NSTRIP * Geo::STRIP);
-    int trow0 = wcol0; // output row of the first (listed) column of this wave
+    int trow0 = 0; // output row of the first (listed) column of this wave
     if (EPI == EPI_SWIGLU_BWD && g.Ct) {
-        if (g.cidx) {
-            int lo = 0, hi = g.pc; // first listed column >= wcol0
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (g.cidx[mid] < wcol0) lo = mid + 1; else hi = mid;
-            }
-            trow0 = __builtin_amdgcn_readfirstlane(lo);
-        }
-        for (int c = lane; c < SW; c += 64) ranktab[c] = g.cidx ? -1 : (wcol0 + c < g.N ? c : -1);
-        if (g.cidx) {
-            for (int t = trow0 + lane; t < g.pc; t += 64) {
-                const int c = g.cidx[t] - wcol0;
-                if (c >= SW) break;
-                ranktab[c] = t - trow0;
-            }
-        }
+        const int first = __builtin_amdgcn_readfirstlane(crank_pre[0]);
+        trow0 = first >= 0 ? first : -1 - first;
+#pragma unroll
+        for (int h = 0; h < (SW + 63) / 64; ++h)
+            if (SW % 64 == 0 || 64 * h + lane < SW) ranktab[64 * h + lane] = crank_pre[h] >= 0 ? crank_pre[h] - trow0 : -1;
     }
     // strip -> neuron-major global: out[trow0 + ranktab[column]][token].  A transposing LDS read hands the lanes
     // of a 16-lane block, for 4 adjacent strip columns, 4 consecutive rows each; two of them give every lane
@@ -574,7 +577,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
             const int row = ranktab[c4 + cn];
             const uint32_t off = row >= 0 && m_in ? (uint32_t)((row * g.ldct + 32 * i + 8 * q) * 2) : kOutside;
             const u32x2 a = __builtin_bit_cast(u32x2, h0), b = __builtin_bit_cast(u32x2, h1);
-            __builtin_amdgcn_raw_buffer_store_b128(u32x4{a[0], a[1], b[0], b[1]}, rs, off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{a[0], a[1], b[0], b[1]}, rs, off, 0, kKeep); // read next, by the weight-gradient launch
         }
     };
 
@@ -583,7 +586,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     u32x4 rpre[kResidual ? NLD : 1];
     const bool has_r = kResidual && g.R != nullptr;
     if constexpr (kResidual) {
-        if (has_r) strip_fetch(rpre, g.R, g.ldr, 0);
+        if (has_r) strip_fetch(rpre, g.R, g.ldr, 0, std::integral_constant<int, kKeep>{});
     }
     // The fragment rows, one after the other.  kT: SWIGLU_BWD with the neuron-major copies; the loop exists once
     // per case, so that between a row's loads and the next row's use of them the stores issued are the same on
@@ -592,8 +595,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         constexpr bool kT = decltype(with_t)::value;
         u32x4 gpre[NLD], upre[NLD]; // SWIGLU_BWD: G and U of the next fragment row, in flight
         if (EPI == EPI_SWIGLU_BWD) {
-            strip_fetch(gpre, g.Gin, g.ldg, 0);
-            strip_fetch(upre, g.Uin, g.ldg, 0);
+            strip_fetch(gpre, g.Gin, g.ldg, 0, std::integral_constant<int, kStream>{});
+            strip_fetch(upre, g.Uin, g.ldg, 0, std::integral_constant<int, kStream>{});
         }
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
@@ -604,7 +607,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                     if (has_r) {
                         // row chunks -> strip -> each lane's own accumulator positions; added in fp32
                         strip_commit(strip0, rpre);
-                        if (i + 1 < FM) strip_fetch(rpre, g.R, g.ldr, i + 1);
+                        if (i + 1 < FM) strip_fetch(rpre, g.R, g.ldr, i + 1, std::integral_constant<int, kKeep>{});
                         u32x2 rq[FN][4];
 #pragma unroll
                         for (int j = 0; j < FN; ++j)
@@ -627,7 +630,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                     for (int q = 0; q < 4; ++q)
                         strip_put(strip0, 32 * j, q,
                                   pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
-                if (g.cs) strip_store_scatter(strip0, gC, g.ldc, g.cs, i); else strip_store(strip0, gC, g.ldc, i);
+                if (g.cs) strip_store_scatter(strip0, gC, g.ldc, g.cs, i); else strip_store(strip0, gC, g.ldc, i, std::integral_constant<int, kKeep>{});
             } else if (EPI == EPI_SWIGLU_FWD) {
                 // fragments 2 jj (gate) and 2 jj + 1 (up) cover the same 32 neurons
 #pragma unroll
@@ -644,7 +647,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                             }
                             strip_put(strip0, 32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
                         }
-                    strip_store(strip0, which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, i);
+                    strip_store(strip0, which == 0 ? g.C : (which == 1 ? g.C2 : g.C3), g.ldc, i, std::integral_constant<int, kKeep>{});
                 }
             } else { // EPI_SWIGLU_BWD: three strips per wave (dG, dU, Act)
                 unsigned char* strip1 = strip0 + Geo::STRIP;
@@ -652,8 +655,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                 strip_commit(strip0, gpre);
                 strip_commit(strip1, upre);
                 if (i + 1 < FM) {
-                    strip_fetch(gpre, g.Gin, g.ldg, i + 1);
-                    strip_fetch(upre, g.Uin, g.ldg, i + 1);
+                    strip_fetch(gpre, g.Gin, g.ldg, i + 1, std::integral_constant<int, kStream>{});
+                    strip_fetch(upre, g.Uin, g.ldg, i + 1, std::integral_constant<int, kStream>{});
                 }
                 u32x2 gq[FN][4], uq[FN][4];
 #pragma unroll
@@ -679,9 +682,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                         strip_put(strip1, 32 * j, q, pack4(du[0], du[1], du[2], du[3]));
                         strip_put(strip2, 32 * j, q, pack4(act[0], act[1], act[2], act[3]));
                     }
-                strip_store(strip0, g.C, g.ldc, i);
-                strip_store(strip1, g.C2, g.ldc, i);
-                if (g.C3) strip_store(strip2, g.C3, g.ldc, i);
+                strip_store(strip0, g.C, g.ldc, i, std::integral_constant<int, kStream>{});
+                strip_store(strip1, g.C2, g.ldc, i, std::integral_constant<int, kStream>{});
+                if (g.C3) strip_store(strip2, g.C3, g.ldc, i, std::integral_constant<int, kStream>{});
                 if constexpr (kT) {
                     strip_store_t(strip0, g.Ct, i);
                     strip_store_t(strip1, g.Ct2, i);
@@ -805,7 +808,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     g.R = (const uint16_t*)d.R, g.ldr = d.ldr;
     g.Gin = (const uint16_t*)d.Gin, g.Uin = (const uint16_t*)d.Uin, g.ldg = d.ldg;
     g.Ct = (uint16_t*)d.Ct, g.Ct2 = (uint16_t*)d.Ct2, g.Ct3 = (uint16_t*)d.Ct3, g.ldct = d.ldct;
-    g.cidx = d.cidx, g.pc = d.pc;
+    g.crank = d.crank;
     g.tiles_m = (d.M + BM - 1) / BM;
     const int ncols = EPI == EPI_SWIGLU_FWD ? BN / 2 : BN;
     g.tiles_n = (d.N + ncols - 1) / ncols;
@@ -984,7 +987,7 @@ bool gemm_mfma_supported(const GemmDesc& d) {
         if (d.Ct) {
             if (!d.Ct2 || !d.Ct3 || !aligned16(d.Ct) || !aligned16(d.Ct2) || !aligned16(d.Ct3)) return false;
             if (d.ldct % 8 || d.M % 8 || d.ldct < d.M) return false;
-            if (d.cidx && d.pc < 1) return false;
+            if (d.cidx && !d.crank) return false;
         }
     }
     return true;

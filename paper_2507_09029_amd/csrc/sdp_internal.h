@@ -87,6 +87,9 @@ struct GemmDesc {
     int64_t ldcc = 0;
     const int32_t* cidx = nullptr;
     int pc = 0;
+    // with cidx and Ct (MFMA kernel): crank[n], n < N: the number of listed columns below n if n is listed, else
+    // -1 - that number (see column_ranks); spares the kernel a search of cidx per wave
+    const int32_t* crank = nullptr;
     // SWIGLU_BWD, MFMA kernel only: neuron-major copies Ct / Ct2 / Ct3 of dG / dU / act, [rows][ldct] with
     // Ct[r(n)][m] = dG[m][n]; r(n) = n, or with cidx the rank of n in cidx (columns not listed are dropped).
     // With Ct set, C3 may be null (act is then not stored row-major).
@@ -176,5 +179,9 @@ struct TransposeJob {
     int R, C;
 };
 int transpose_batch(int elem_bytes, const TransposeJob* jobs, int n, const char* name, hipStream_t s);
+
+// crank[n] for n < N from the ascending list cidx[0 .. pc): the number of listed columns below n if n is listed,
+// else -1 - that number
+int column_ranks(const int32_t* cidx, int pc, int N, int32_t* crank, hipStream_t s);
 
 } // namespace sdp

@@ -42,12 +42,32 @@ int check_common(int mode, int dtype, int T, int d, int F, int p) {
     return SDP_OK;
 }
 
+// one thread per column n: lower bound of n in the ascending list
+__global__ __launch_bounds__(256) void column_ranks_kernel(const int32_t* __restrict__ cidx, int pc, int N,
+                                                           int32_t* __restrict__ crank) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    int lo = 0, hi = pc;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (cidx[mid] < n) lo = mid + 1; else hi = mid;
+    }
+    crank[n] = lo < pc && cidx[lo] == n ? lo : -1 - lo;
+}
+
 int run(int dtype, const GemmDesc& g, hipStream_t s) {
     if (dtype == SDP_BF16 && gemm_mfma_supported(g)) return gemm_mfma_bf16(g, s);
     return gemm_simple(dtype, g, s);
 }
 
 } // namespace
+
+int sdp::column_ranks(const int32_t* cidx, int pc, int N, int32_t* crank, hipStream_t s) {
+    if (!cidx || !crank || pc < 0 || N < 1) return SDP_ERR_INVALID_ARG;
+    ProfileScope ps("mlp_column_ranks", s);
+    column_ranks_kernel<<<(unsigned)((N + 255) / 256), 256, 0, s>>>(cidx, pc, N, crank);
+    return launch_status();
+}
 
 extern "C" size_t sdp_masked_mlp_fwd_workspace_bytes(int mode, int dtype, int T, int d, int F, int p) {
     if (check_common(mode, dtype, T, d, F, mode == SDP_MASK_BACKWARD ? F : p) != SDP_OK) return 0;
@@ -63,6 +83,7 @@ extern "C" size_t sdp_masked_mlp_bwd_workspace_bytes(int mode, int dtype, int T,
                    2 * round_up((size_t)d * ld_tokens(T) * e, 256);
     if (mode == SDP_MASK_BACKWARD) bytes += 3 * round_up((size_t)T * p * e, 256);
     bytes += 3 * round_up((size_t)p * ld_tokens(T) * e, 256); // neuron-major copies of dG, dU, Act on the mask
+    if (mode == SDP_MASK_BACKWARD) bytes += round_up((size_t)F * sizeof(int32_t), 256); // rank of every neuron in the list
     return bytes;
 }
 
@@ -161,6 +182,8 @@ int sdp::mlp_bwd_impl(int mode, int dtype, int T, int d, int F, int p, const voi
     }
     const size_t nm_b = round_up((size_t)p * ld_tokens(T) * e, 256);
     void *dGn = w, *dUn = w + nm_b, *Actn = w + 2 * nm_b; // [p][T(+pad)]: neuron-major
+    w += 3 * nm_b;
+    int32_t* ranks = (int32_t*)w; // backward masking: [F]
 
     // the four operand copies of the backward pass as one launch (X^T, dY^T only feed the weight gradients)
     const TransposeJob tj[4] = {{W1, W1c, d, n, gather, n, d},
@@ -198,16 +221,20 @@ int sdp::mlp_bwd_impl(int mode, int dtype, int T, int d, int F, int p, const voi
     // under backward masking only the worker's p columns), which is the layout in which the batched
     // weight-gradient contraction reads both operands depth-contiguous; act is not stored row-major.
     da.Ct = dGn, da.Ct2 = dUn, da.Ct3 = Actn, da.ldct = ld_tokens(T);
-    if (mode == SDP_MASK_BACKWARD) da.cidx = idx_k, da.pc = p;
+    if (mode == SDP_MASK_BACKWARD) da.cidx = idx_k, da.pc = p, da.crank = ranks;
     const bool fused = want_dw && dtype == SDP_BF16 && p % 8 == 0 && T % 8 == 0 && gemm_mfma_supported(dw) && gemm_mfma_supported(da);
     if (!fused) {
-        da.Ct = da.Ct2 = da.Ct3 = nullptr, da.cidx = nullptr, da.pc = 0;
+        da.Ct = da.Ct2 = da.Ct3 = nullptr, da.cidx = nullptr, da.pc = 0, da.crank = nullptr;
         // without weight gradients nothing reads act: the MFMA kernel then skips its store, the plain one writes it anyway
         if (want_dw || dtype != SDP_BF16 || !gemm_mfma_supported(da)) da.C3 = Act;
         if (mode == SDP_MASK_BACKWARD && want_dw) {
             da.Cc = dGc, da.Cc2 = dUc, da.Cc3 = Actc, da.ldcc = p;
             da.cidx = idx_k, da.pc = p;
         }
+    }
+    if (fused && mode == SDP_MASK_BACKWARD) {
+        rc = column_ranks(idx_k, p, F, ranks, s);
+        if (rc != SDP_OK) return rc;
     }
     rc = run(dtype, da, s);
     if (rc != SDP_OK) return rc;
