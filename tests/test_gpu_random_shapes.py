@@ -17,8 +17,11 @@ pytestmark = pytest.mark.gpu
 # with a bf16-rounded factor, so the rounding errors do not average out as they do over the thousands of tokens
 # of the benchmark shapes, and the largest of 10^4 - 10^5 entries lies further out (seen: up to 2.9e-2 of
 # max(rms, |ref|) at 32 - 250 tokens, 3.3e-3 normwise).  The stated 2e-2 stays the bound of the normwise error
-# and of every per-token tensor; the elementwise maximum of the weight gradients gets 4e-2 here.  An indexing
-# or tail mistake, which is what these cases are for, shows up as an error of order one.
+# and of every per-token tensor; the elementwise maximum of the weight gradients gets 4e-2 here.  On top of the
+# fixed bounds the shared run_case routines require every bf16 weight gradient to lie no further from the oracle
+# than the bf16 rounding points alone put it (rounding_model.py through helpers.assert_close_with_model), which is
+# what would catch a kernel that adds error of its own.  An indexing or tail mistake, which is what these cases
+# are for, shows up as an error of order one.
 DW_ELEM_TOL_BF16 = 4e-2
 
 
