@@ -300,6 +300,65 @@ def bench_attention(sdp, torch, steps, w=None):
     }
 
 
+def bench_block(sdp, torch, steps):
+    """One worker's pass through one residual block (attention + MLP) under block-level masking at the 500M-like
+    width: the running block (m = 1), the backward-masked block whose gradient still passes through it, and the
+    skipped block.  Not part of `value`."""
+    import workloads
+
+    a, m = workloads.ATTN_500M, workloads.CONFIG2
+    assert a.d == m.d and a.T == m.T
+    Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(a))
+    W1, W3, W2T = (t.cuda() for t in workloads.mlp_weights(m))
+    X, dY = (t.cuda() for t in workloads.attn_batch(a, 0))
+    dt = X.dtype
+    ws_f = torch.empty(sdp.block_fwd_workspace_bytes(dt, a.Bt, a.S, a.d, a.H, a.hd, m.F), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(sdp.block_bwd_workspace_bytes(dt, a.Bt, a.S, a.d, a.H, a.hd, m.F), dtype=torch.uint8, device="cuda")
+    Y, saved = sdp.block_fwd("bm", 1, a.Bt, a.S, a.hd, X, Wqkv, WoT, W1, W3, W2T, ws=ws_f)
+    fo = (Y,) + tuple(saved)
+    dX, grads = sdp.block_bwd("bm", 1, a.Bt, a.S, a.hd, X, dY, Wqkv, WoT, W1, W3, W2T, saved, ws=ws_b)
+    bo = (dX,) + tuple(grads)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def run(mode, bit, rule):
+        skipped_fwd = mode == "fm" and not bit  # nothing is saved then, and only Y is written
+
+        def f():
+            _, sv = sdp.block_fwd(mode, bit, a.Bt, a.S, a.hd, X, Wqkv, WoT, W1, W3, W2T, out=Y if skipped_fwd else fo, ws=ws_f)
+            sdp.block_bwd(mode, bit, a.Bt, a.S, a.hd, X, dY, Wqkv, WoT, W1, W3, W2T, sv, dx_rule=rule,
+                          out=bo if bit else (dX,), ws=ws_b)
+        return f
+
+    T, d, F, E = a.T, a.d, m.F, a.H * a.hd
+    proj = 2 * T * d * E
+    core_f, core_b = 2 * a.Bt * a.H * a.S * a.S * a.hd, 5 * a.Bt * a.H * a.S * a.S * a.hd
+    fwd = 4 * proj + core_f + 6 * T * d * F            # q, k, v, out projections; causal core; gate, up, down
+    bwd_dx = 4 * proj + core_b + 6 * T * d * F         # dout, dX of the projections, core backward; dact, dX of the MLP
+    bwd_dw = 4 * proj + 6 * T * d * F                  # the seven weight gradients
+    full = timed(run("bm", 1, "through"))
+    through = timed(run("bm", 0, "through"))
+    skip_bwd = timed(run("bm", 0, "skip"))
+    skipped = timed(run("fm", 0, "through"))
+    return {
+        "workload": f"block: {a.name} + dense MLP of {m.name}", "tokens": T, "d_model": d, "heads": a.H, "head_dim": a.hd, "d_ff": F,
+        "flop": {"forward": fwd, "backward_dx": bwd_dx, "backward_dw": bwd_dw},
+        "running_block_m1": {"ms": full, "tflops": (fwd + bwd_dx + bwd_dw) / (full * 1e-3) / 1e12},
+        "backward_masked_m0_dx_through": {"ms": through, "tflops": (fwd + bwd_dx) / (through * 1e-3) / 1e12},
+        "backward_masked_m0_dx_skip": {"ms": skip_bwd, "tflops": fwd / (skip_bwd * 1e-3) / 1e12},
+        "forward_masked_m0_skipped": {"ms": skipped, "note": "two copies of T x d"},
+        "unit": "ms per forward + backward of one block on one worker; TFLOP/s of the flops that case runs",
+    }
+
+
 def bench_mlp(sdp, torch, w, a, steps, warmup):
     """One MLP workload: W warm-up steps, an untimed per-kernel survey, then exactly `steps` timed steps."""
     import workloads
@@ -485,7 +544,8 @@ def main():
     torch.cuda.set_device(0)
     if a.attention_only:
         print(json.dumps({"attention": bench_attention(sdp, torch, max(2, a.steps // 4)),
-                          "attention_paper_width": bench_attention(sdp, torch, max(2, a.steps // 4), workloads.ATTN_500M_HD50)}))
+                          "attention_paper_width": bench_attention(sdp, torch, max(2, a.steps // 4), workloads.ATTN_500M_HD50),
+                          "block": bench_block(sdp, torch, max(2, a.steps // 4))}))
         return
     w = workloads.MLP_CONFIGS[a.workload]
     res, x0 = bench_mlp(sdp, torch, w, a, a.steps, a.warmup)
@@ -529,6 +589,7 @@ def main():
     if not a.no_attention:
         rec["attention"] = bench_attention(sdp, torch, max(2, a.steps // 4))
         rec["attention_paper_width"] = bench_attention(sdp, torch, max(2, a.steps // 4), workloads.ATTN_500M_HD50)
+        rec["block"] = bench_block(sdp, torch, max(2, a.steps // 4))
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
         rec["cpu_baselines_other"] = cpu_baselines_other()
