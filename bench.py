@@ -300,6 +300,34 @@ def bench_attention(sdp, torch, steps, w=None):
     }
 
 
+def vendor_gemm_yardstick(torch, w):
+    """What the vendor's bf16 contraction (torch.matmul, i.e. hipBLASLt / rocBLAS) reaches on this machine at the plain
+    shapes of this workload's launches, on data with the benchmark's statistics: context for the roofline
+    fractions, not part of the path (the library never calls it)."""
+    n = w.p if w.mode == "fm" else w.F
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    out = {}
+    for name, (M, N, K) in {"gate_up_shape": (w.T, 2 * n, w.d), "down_shape": (w.T, w.d, n), "dw_shape_one_problem": (w.p, w.d, w.T)}.items():
+        A = torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16)
+        B = (torch.randn((N, K), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        for _ in range(3):
+            C = A @ B.t()
+        torch.cuda.synchronize()
+        reps = 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            C = A @ B.t()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[name] = {"M": M, "N": N, "K": K, "ms": ms, "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12}
+        del A, B, C
+    out["note"] = "torch.matmul, bf16 in, fp32 accumulate, A [M][K] x B [N][K]^T, N(0,1) x N(0, 0.02^2) operands; 10 back-to-back calls"
+    return out
+
+
 def bench_block(sdp, torch, steps):
     """One worker's pass through one residual block (attention + MLP) under block-level masking at the 500M-like
     width: the running block (m = 1), the backward-masked block whose gradient still passes through it, and the
@@ -574,6 +602,7 @@ def main():
             "published_peak_tflops": PEAK_BF16_TFLOPS,
             "note": "v_mfma_f32_32x32x16_bf16 loop, 8 waves per CU, no memory traffic; measured live",
         }
+        rec["vendor_gemm_yardstick"] = vendor_gemm_yardstick(torch, w)
     del res, x0
     torch.cuda.empty_cache()
     # the other bf16 MLP workloads, measured the same way (their own steps; not part of `value`)
