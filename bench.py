@@ -43,14 +43,18 @@ def recorded_traffic(workload, kernel, shape):
     the launch configuration (`shape`, from sdp_profile_launch_shape; None for kernels that have none) differs."""
     try:
         with open(TRAFFIC_FILE) as f:
-            rec = json.load(f).get(workload, {}).get(kernel)
+            rec_all = json.load(f).get(workload, {})
     except (OSError, ValueError):
         return None
+    rec = rec_all.get(kernel)
     if not rec:
         return None
     if rec.get("launch") != shape:
         return None
-    return rec["fetch_bytes"] + rec["write_bytes"]
+    total = rec["fetch_bytes"] + rec["write_bytes"]
+    if kernel + "_reduce" in rec_all:  # the kernel that adds the partial tiles of a launch cut in depth
+        total += rec_all[kernel + "_reduce"]["fetch_bytes"] + rec_all[kernel + "_reduce"]["write_bytes"]
+    return total
 
 
 def parse():
@@ -520,7 +524,10 @@ def bench_mlp(sdp, torch, w, a, steps, warmup):
     if dominant and dominant in prof:
         calls, ms = prof[dominant]
         avg_ms = ms / calls
-        ach = flops_per_launch(dominant, w) / (avg_ms * 1e-3) / 1e12
+        # a weight-gradient launch whose last round is cut in depth is followed by the kernel that adds the partial
+        # tiles: its time (from the survey; it is not timed live) counts against the launch
+        reduce_ms = kernels.get(dominant + "_reduce", {}).get("avg_ms", 0.0)
+        ach = flops_per_launch(dominant, w) / ((avg_ms + reduce_ms) * 1e-3) / 1e12
         # the fp32 path (config 1, a correctness configuration) runs on the vector ALUs, not on the matrix cores
         bound, peak = ("mfma", PEAK_BF16_TFLOPS) if w.dtype == "bf16" else ("alu", PEAK_FP32_VECTOR_TFLOPS)
         shape = kernels[dominant].get("launch")
@@ -529,7 +536,7 @@ def bench_mlp(sdp, torch, w, a, steps, warmup):
                     "traffic": recorded_traffic(w.name, dominant, shape) if S == 1 else None,
                     "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 FETCH_SIZE + WRITE_SIZE, recorded for this "
                                     "launch configuration in profiles/hbm_traffic_recorded.json; null if none matches)",
-                    "launch": shape, "avg_launch_ms": avg_ms,
+                    "launch": shape, "avg_launch_ms": avg_ms, "reduce_kernel_ms": reduce_ms,
                     "launches_timed": calls, "flop_per_launch": flops_per_launch(dominant, w),
                     "share_of_step": ms / steps / ms_per_step}
 

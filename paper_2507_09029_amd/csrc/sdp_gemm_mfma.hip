@@ -91,6 +91,10 @@ struct Dev {
     // the launch and leaves its fp32 partial sums in partial[range][problem][M][N]
     int ksplit, ksteps;
     float* partial;
+    // OP_DW_TAIL: ids below n_head are whole tiles (a multiple of the CU count: the full rounds); the `tail` tiles of
+    // the last round follow as tail x ksplit items, range after range, each leaving an fp32 tile in
+    // partial[range][tail tile][BM][BN].  ntot counts tiles, not ids.
+    int n_head, tail;
 };
 
 // two fp32 -> packed bf16, round to nearest even (the hardware's v_cvt_pk_bf16_f32)
@@ -130,6 +134,20 @@ __host__ __device__ inline void tile_of_shared(int lin, int tiles_m, int tiles_n
     batch = range * nbatch + first_problem + v / tiles_m;
     tile_m = v % tiles_m;
     (void)ksplit;
+}
+
+// Linear-order position (see the kernel's workgroup -> tile mapping) of id `id` of the full rounds, and of the q-th
+// tile of the last round: XCD x owns positions [start_x, start_x + count_x), the first n_head / 8 of them run in
+// the full rounds, the rest are its tail tiles; tail tiles are numbered round-robin over the XCDs.
+__host__ __device__ inline int head_position(int id, int ntiles) {
+    const int x = id % NUM_XCD, j = id / NUM_XCD, base = ntiles / NUM_XCD, rem = ntiles % NUM_XCD;
+    return x * base + (x < rem ? x : rem) + j;
+}
+__host__ __device__ inline int tail_position(int q, int ntiles, int n_head) {
+    const int base = ntiles / NUM_XCD, rem = ntiles % NUM_XCD, jh = n_head / NUM_XCD, tb = base - jh;
+    const int x = q < NUM_XCD * tb ? q % NUM_XCD : q - NUM_XCD * tb;
+    const int i = q < NUM_XCD * tb ? q / NUM_XCD : tb;
+    return x * base + (x < rem ? x : rem) + jh + i;
 }
 
 // s_waitcnt vmcnt(n) alone (expcnt / lgkmcnt left at their maxima), gfx9 encoding
@@ -177,13 +195,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // of a linear order in which the problems of a batch vary fastest, then group_m tile-rows, then the
     // tile-columns: the tiles that run together on one XCD then form a compact block of (problems x
     // tile-rows x tile-columns) whose operand rows are fetched into that XCD's L2 once.
+    constexpr bool kTail = OP == OP_DW_TAIL;
     int bid = blockIdx.x;
-    {
-        const int x = bid % NUM_XCD, j = bid / NUM_XCD;
-        const int base = g.ntot / NUM_XCD, rem = g.ntot % NUM_XCD;
-        bid = x * base + (x < rem ? x : rem) + j;
+    bool cut = false;  // OP_DW_TAIL: this workgroup computes one depth range of a tile of the last round
+    int tail_part = 0, tail_q = 0;
+    if (kTail && bid >= g.n_head) {
+        cut = true;
+        tail_part = (bid - g.n_head) / g.tail, tail_q = (bid - g.n_head) % g.tail;
+        bid = tail_position(tail_q, g.ntot, g.n_head);
+    } else {
+        bid = head_position(bid, g.ntot);
     }
-    constexpr bool kBatched = OP == OP_DW || OP == OP_DW_SPLIT;
+    constexpr bool kBatched = OP == OP_DW || OP == OP_DW_SPLIT || kTail;
     constexpr bool kSplit = OP == OP_DW_SPLIT;
     const int nb = kBatched ? g.nbatch * (kSplit ? g.ksplit : 1) : 1;
     int tile_m, tile_n, batch;
@@ -203,8 +226,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     const uint16_t* gA = g.A;
     const uint16_t* gB = g.B;
     uint16_t* gC = g.C;
-    int kpart = 0; // depth range of this workgroup (OP_DW_SPLIT)
+    int kpart = 0; // depth range of this workgroup (OP_DW_SPLIT, and the cut tiles of OP_DW_TAIL)
     if (kSplit) kpart = batch / g.nbatch, batch -= kpart * g.nbatch;
+    if (kTail) kpart = tail_part;
     if (kBatched) {
         // selected by comparisons: a runtime index into a by-value kernel argument would go through scratch
         static_assert(kMaxBatch == 4, "one comparison per problem");
@@ -229,8 +253,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // ---- depth steps; a partial last step (K % 64 in {16, 32, 48}) reads its missing chunks from a
     // zero buffer, so that every step issues the same loads and runs all four MFMA sub-steps ----
     const int nk_all = (g.K + BK - 1) / BK;
-    const int kt0 = kSplit ? kpart * g.ksteps : 0; // first depth step of this workgroup
-    const int nk1 = kSplit ? (nk_all - kt0 < g.ksteps ? nk_all - kt0 : g.ksteps) : nk_all;
+    const bool ranged = kSplit || (kTail && cut);
+    const int kt0 = ranged ? kpart * g.ksteps : 0; // first depth step of this workgroup
+    const int nk1 = ranged ? (nk_all - kt0 < g.ksteps ? nk_all - kt0 : g.ksteps) : nk_all;
     const int nk = EPI == EPI_DUAL_ACC ? 2 * nk1 : nk1;
 
     // ---- per-lane global source of every slab this wave fills: byte offsets from a uniform base.
@@ -456,6 +481,22 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                 }
         }
         return;
+    }
+    if constexpr (kTail) {
+        if (cut) {
+            // fp32 partial tile of this depth range, tile-local [BM][BN]; rows and columns outside the matrix hold
+            // what the clamped operand rows gave and are never read back
+            float* P = g.partial + ((int64_t)tail_part * g.tail + tail_q) * (BM * BN);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *(f32x4*)(P + (WM * wm + 32 * i + l32) * BN + WN * wn + 32 * j + 8 * q + 4 * lhi) =
+                            f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            return;
+        }
     }
     __syncthreads(); // all waves are done with the operand tiles: LDS becomes per-wave strips
     constexpr int SW = Geo::SW, RS = Geo::RS;
@@ -709,6 +750,7 @@ struct Tuning {
     int force_tile = 0; // 0 = choose; 128 / 192 / 256
     int group_m = 0;    // 0 = choose
     bool plain_order = false;
+    int tail_parts = -1; // SDP_TAIL_PARTS: -1 = choose; 0 = no tail cut; n = cut into n ranges where a cut applies
 };
 const Tuning& tuning() {
     static const Tuning t = [] {
@@ -720,6 +762,7 @@ const Tuning& tuning() {
         }
         if (const char* e = getenv("SDP_GROUP_M")) v.group_m = atoi(e) > 0 ? atoi(e) : 0;
         v.plain_order = getenv("SDP_PLAIN_ORDER") != nullptr;
+        if (const char* e = getenv("SDP_TAIL_PARTS")) v.tail_parts = atoi(e) >= 0 && atoi(e) <= 8 ? atoi(e) : -1;
 #endif
         return v;
     }();
@@ -795,6 +838,63 @@ int choose_group_shared(int tiles_m, int tiles_n, int np0, int nbatch, int kspli
 std::mutex g_shape_mu;
 std::map<std::string, std::array<int, 4>> g_last_shape;
 
+// OP_DW_TAIL, second kernel: the depth ranges' fp32 tiles of every tile of the last round, added in range order,
+// rounded and stored (optional row scatter).  One thread per 8 columns of a tile row; the tile's place in its
+// problem comes from the same mapping as in the contraction kernel.
+struct TailReduceArgs {
+    const float* partial;
+    int parts, tail, ntiles, n_head;
+    int tiles_m, tiles_n, np0, nbatch, group_m;
+    int M, N;
+    uint16_t* Cb[kMaxBatch];
+    int64_t ldc;
+    const int32_t* cs;
+};
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void tail_reduce_kernel(TailReduceArgs r) {
+    constexpr int PER_TILE = BM * BN / 8 / 256; // workgroups per tile
+    const int q = blockIdx.x / PER_TILE;
+    const int e = (blockIdx.x % PER_TILE) * 256 + threadIdx.x;
+    const int row = e / (BN / 8), col = (e % (BN / 8)) * 8;
+    const int bid = tail_position(q, r.ntiles, r.n_head);
+    int batch, tile_m, tile_n;
+    if (r.np0 > 0) {
+        tile_of_shared(bid, r.tiles_m, r.tiles_n, r.np0, r.nbatch, 1, r.group_m, batch, tile_m, tile_n);
+    } else {
+        const int per_group = r.group_m * r.tiles_n * r.nbatch;
+        const int grp = bid / per_group;
+        const int first_m = grp * r.group_m;
+        const int gm = r.tiles_m - first_m < r.group_m ? r.tiles_m - first_m : r.group_m;
+        int in = bid - grp * per_group;
+        batch = in % r.nbatch;
+        in /= r.nbatch;
+        tile_m = first_m + in % gm;
+        tile_n = in / gm;
+    }
+    const int m = tile_m * BM + row, n = tile_n * BN + col;
+    if (m >= r.M || n >= r.N) return;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
+    for (int k = 0; k < r.parts; ++k) { // ranges in depth order
+        const float* p = r.partial + ((int64_t)k * r.tail + q) * (BM * BN) + row * BN + col;
+        a += *(const f32x4*)p;
+        b += *(const f32x4*)(p + 4);
+    }
+    uint16_t* out = batch == 0 ? r.Cb[0] : (batch == 1 ? r.Cb[1] : (batch == 2 ? r.Cb[2] : r.Cb[3]));
+    const int64_t orow = r.cs ? r.cs[m] : m;
+    if (orow < 0) return; // dropped row
+    *(u32x4*)(out + orow * r.ldc + n) = u32x4{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3])};
+}
+
+template <int BM, int BN>
+int tail_reduce(const Dev& g, const GemmDesc& d, hipStream_t s) {
+    TailReduceArgs r{g.partial, g.ksplit, g.tail, g.ntot, g.n_head, g.tiles_m, g.tiles_n, g.np0, g.nbatch, g.group_m,
+                     g.M, g.N, {}, g.ldc, g.cs};
+    for (int z = 0; z < kMaxBatch; ++z) r.Cb[z] = g.Cb[z];
+    ProfileScope ps(d.tail_name, s);
+    tail_reduce_kernel<BM, BN><<<(unsigned)(g.tail * (BM * BN / 8 / 256)), 256, 0, s>>>(r);
+    return launch_status();
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OP>
 int launch_cfg(const GemmDesc& d, hipStream_t s) {
     using Geo = Geometry<BM, BN, WAVES_M, WAVES_N, EPI>;
@@ -813,15 +913,22 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     const int ncols = EPI == EPI_SWIGLU_FWD ? BN / 2 : BN;
     g.tiles_n = (d.N + ncols - 1) / ncols;
     const int64_t ntiles = (int64_t)g.tiles_m * g.tiles_n;
-    constexpr bool kBatched = OP == OP_DW || OP == OP_DW_SPLIT;
+    constexpr bool kBatched = OP == OP_DW || OP == OP_DW_SPLIT || OP == OP_DW_TAIL;
     const int ksplit = OP == OP_DW_SPLIT ? d.ksplit : 1;
     const int nbatch = (kBatched ? d.nbatch : 1) * ksplit; // problems of the launch
     if (ntiles * nbatch > 0x7FFFFFFF) return SDP_ERR_SHAPE;
     g.ntot = (int)(ntiles * nbatch);
     g.nbatch = kBatched ? d.nbatch : 1;
-    g.ksplit = ksplit;
-    g.ksteps = ((d.K + BK - 1) / BK + ksplit - 1) / ksplit;
-    g.partial = (float*)d.split_ws;
+    g.ksplit = OP == OP_DW_TAIL ? d.ksplit : ksplit;
+    g.ksteps = ((d.K + BK - 1) / BK + g.ksplit - 1) / g.ksplit;
+    g.partial = (float*)(OP == OP_DW_TAIL ? d.tail_ws : d.split_ws);
+    g.n_head = g.ntot, g.tail = 0;
+    int64_t grid = (int64_t)g.ntot;
+    if (OP == OP_DW_TAIL) {
+        g.n_head = g.ntot / kNumCU * kNumCU, g.tail = g.ntot - g.n_head;
+        grid = (int64_t)g.n_head + (int64_t)g.tail * d.ksplit;
+        if (g.tail < 1 || d.ksplit < 2 || !d.tail_ws || grid > 0x7FFFFFFF) return SDP_ERR_INVALID_ARG;
+    }
     int na = 1, nbo = 1; // distinct A / B operands among the problems of a batch
     for (int z = 0; z < kMaxBatch; ++z) {
         g.Ab[z] = (const uint16_t*)d.Ab[z], g.Bb[z] = (const uint16_t*)d.Bb[z], g.Cb[z] = (uint16_t*)d.Cb[z];
@@ -862,10 +969,12 @@ int launch_cfg(const GemmDesc& d, hipStream_t s) {
     // microseconds on either side of it.
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (profile_launch_events(d.name, &ev0, &ev1))
-        hipExtLaunchKernelGGL(kern, dim3((unsigned)(ntiles * nbatch)), dim3(NTHREADS), (uint32_t)LDS, s, ev0, ev1, 0u, g);
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTHREADS), (uint32_t)LDS, s, ev0, ev1, 0u, g);
     else
-        kern<<<dim3((unsigned)(ntiles * nbatch)), NTHREADS, LDS, s>>>(g);
-    return launch_status();
+        kern<<<dim3((unsigned)grid), NTHREADS, LDS, s>>>(g);
+    const int rc = launch_status();
+    if (OP == OP_DW_TAIL && rc == SDP_OK) return tail_reduce<BM, BN>(g, d, s);
+    return rc;
 }
 
 // estimated time of a tile shape, in units of 256 x 256 tile-depths: rounds over the CUs times tile
@@ -876,23 +985,60 @@ double shape_cost(int M, int ncols_total, int nbatch, int bm, int bn, double pen
     return (double)rounds * bm * bn * penalty;
 }
 
-template <int EPI, int OP>
-int launch(const GemmDesc& d, hipStream_t s) {
+// tile shape of a launch: 256 (x 256), 192 (256 x 192) or 128 (x 128)
+template <int EPI>
+int choose_shape(const GemmDesc& d, int nbatch) {
     // columns of tile space (gate and up interleaved double the tile columns)
     const int ncols = EPI == EPI_SWIGLU_FWD ? 2 * d.N : d.N;
-    const int nbatch = OP == OP_DW ? d.nbatch : (OP == OP_DW_SPLIT ? d.nbatch * d.ksplit : 1);
     const double c256 = shape_cost(d.M, ncols, nbatch, 256, 256, 1.0);
     // the SwiGLU-forward epilogue pairs gate and up columns inside a tile and has no 192-wide variant
     const double c192 = EPI == EPI_SWIGLU_FWD ? 1e300 : shape_cost(d.M, ncols, nbatch, 256, 192, 1.08);
     const double c128 = shape_cost(d.M, ncols, nbatch, 128, 128, 1.6);
     const int force = tuning().force_tile ? tuning().force_tile : d.force_tile;
-    if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) {
-        return launch_cfg<256, 256, 2, 4, EPI, OP>(d, s);
-    }
+    if (force == 256 || (!force && c256 <= c192 && c256 <= c128)) return 256;
+    if (EPI != EPI_SWIGLU_FWD && (force == 192 || (!force && c192 <= c128))) return 192;
+    return 128;
+}
+
+template <int EPI, int OP>
+int launch(const GemmDesc& d, hipStream_t s) {
+    const int nbatch = OP == OP_DW || OP == OP_DW_TAIL ? d.nbatch : (OP == OP_DW_SPLIT ? d.nbatch * d.ksplit : 1);
+    const int shape = choose_shape<EPI>(d, nbatch);
+    if (shape == 256) return launch_cfg<256, 256, 2, 4, EPI, OP>(d, s);
     if constexpr (EPI != EPI_SWIGLU_FWD) {
-        if (force == 192 || (!force && c192 <= c128)) return launch_cfg<256, 192, 4, 2, EPI, OP>(d, s);
+        if (shape == 192) return launch_cfg<256, 192, 4, 2, EPI, OP>(d, s);
     }
     return launch_cfg<128, 128, 2, 2, EPI, OP>(d, s);
+}
+
+// Tail cut of a batched launch (OP_DW_TAIL).  With T tiles on 256 CUs the launch runs floor(T / 256) full rounds
+// and a last round of T mod 256 tiles; when that round leaves many CUs idle, each of its tiles is cut into
+// `parts` depth ranges that spread over all CUs (every range at least 32 steps deep), at the price of one fp32
+// tile per range written and read back.  Returns the number of ranges (0: no cut) for the shape choose_shape
+// picks; *tail_tiles and *tile_elems describe the scratch.
+int plan_tail(const GemmDesc& d, int* tail_tiles, int* tile_elems) {
+    if (d.nbatch < 1 || d.N % 8 || d.M < 1 || d.K < 1) return 0;
+    const int shape = choose_shape<EPI_STORE>(d, d.nbatch);
+    const int bm = shape == 128 ? 128 : 256, bn = shape == 256 ? 256 : (shape == 192 ? 192 : 128);
+    const int64_t tiles = (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.nbatch;
+    if (tiles > 0x7FFFFFFF) return 0;
+    const int head = (int)(tiles / kNumCU) * kNumCU, tail = (int)tiles - head;
+    if (head == 0 || tail == 0) return 0; // less than a round: the uniform depth cut (gemm_choose_ksplit) covers that case
+    const int nk = (d.K + BK - 1) / BK;
+    int best = 0;
+    double best_cost = 0.85; // a cut has to shorten the last round by at least 15 % (of a whole tile's time)
+    for (int parts = 2; parts <= 6 && nk / parts >= 32; ++parts) {
+        const int rounds = (tail * parts + kNumCU - 1) / kNumCU;
+        const double cost = (double)rounds / parts + 0.04 * parts; // the second term: traffic of the partial tiles
+        if (cost < best_cost) best_cost = cost, best = parts;
+    }
+    if (tuning().tail_parts >= 0) best = tuning().tail_parts >= 2 && nk / tuning().tail_parts >= 32 ? tuning().tail_parts : 0;
+    if (best == 0) return 0;
+    const int steps = (nk + best - 1) / best;
+    best = (nk + steps - 1) / steps; // no empty range
+    if (tail_tiles) *tail_tiles = tail;
+    if (tile_elems) *tile_elems = bm * bn;
+    return best;
 }
 
 // sum of the depth ranges' fp32 partial results -> bf16 rows of the problems' outputs (optional row scatter);
@@ -947,6 +1093,14 @@ size_t gemm_split_ws_bytes(int M, int N, int K, int nbatch) {
     return r > 1 ? (size_t)r * nbatch * M * N * sizeof(float) : 0;
 }
 
+size_t gemm_tail_ws_bytes(int M, int N, int K, int nbatch) {
+    GemmDesc d;
+    d.M = M, d.N = N, d.K = K, d.nbatch = nbatch;
+    int tail = 0, elems = 0;
+    const int parts = plan_tail(d, &tail, &elems);
+    return parts > 1 ? (size_t)parts * tail * elems * sizeof(float) : 0;
+}
+
 bool gemm_mfma_supported(const GemmDesc& d) {
     if (d.M < 1 || d.N < 1 || d.K < 1) return false;
     if (d.force_tile != 0 && d.force_tile != 128 && d.force_tile != 192 && d.force_tile != 256) return false;
@@ -998,6 +1152,14 @@ int gemm_mfma_bf16(const GemmDesc& d, hipStream_t s) {
     // OP only gives every call site its own kernel symbol, so that profiles name the step
     if (d.epilogue == EPI_STORE && d.nbatch > 0) {
         const int r = d.split_ws ? gemm_choose_ksplit(d.M, d.N, d.K, d.nbatch) : 1;
+        if (r < 2 && d.tail_ws) {
+            const int parts = plan_tail(d, nullptr, nullptr);
+            if (parts > 1) {
+                GemmDesc dt = d;
+                dt.ksplit = parts;
+                return launch<EPI_STORE, OP_DW_TAIL>(dt, s); // followed by its reduction
+            }
+        }
         if (r < 2) return launch<EPI_STORE, OP_DW>(d, s);
         GemmDesc ds = d;
         ds.ksplit = r;

@@ -110,10 +110,15 @@ struct GemmDesc {
     // kernel sums the ranges' partial results (gemm_choose_ksplit decides; 1 = no cut).
     void* split_ws = nullptr;
     int ksplit = 1; // set by gemm_mfma_bf16
+    // batched launches only: optional fp32 scratch of gemm_tail_ws_bytes(M, N, K, nbatch) bytes.  With it, a launch
+    // whose tiles fill the CUs more than once but leave the last round partly empty cuts the depth of that last
+    // round's tiles into ranges (gemm_choose_tail), which a second small kernel adds up.
+    void* tail_ws = nullptr;
+    const char* tail_name = "dw_tail_reduce"; // profile name of that second kernel
 };
 
 // tags that give each call site of the MFMA contraction its own kernel symbol
-enum GemmOp { OP_GATE_UP = 0, OP_DOWN = 1, OP_DACT = 2, OP_DX = 3, OP_DW = 4, OP_DW_SPLIT = 5 };
+enum GemmOp { OP_GATE_UP = 0, OP_DOWN = 1, OP_DACT = 2, OP_DX = 3, OP_DW = 4, OP_DW_SPLIT = 5, OP_DW_TAIL = 6 };
 
 // Plain LDS-tiled FMA contraction, any shape; element type float or bf16 (dtype as sdp_dtype).
 int gemm_simple(int dtype, const GemmDesc& g, hipStream_t s);
@@ -123,6 +128,8 @@ bool gemm_mfma_supported(const GemmDesc& g);
 // depth ranges a batched launch of nbatch problems of shape M x N x K would be cut into, and the scratch that takes
 int gemm_choose_ksplit(int M, int N, int K, int nbatch);
 size_t gemm_split_ws_bytes(int M, int N, int K, int nbatch);
+// scratch of the tail cut of a batched launch (0 when none is taken)
+size_t gemm_tail_ws_bytes(int M, int N, int K, int nbatch);
 
 // ---- attention core -----------------------------------------------------------------------------
 // Causal attention of n heads of width hd over Bt sequences of S tokens, on the saved projections:

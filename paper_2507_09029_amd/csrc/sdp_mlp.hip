@@ -84,6 +84,7 @@ extern "C" size_t sdp_masked_mlp_bwd_workspace_bytes(int mode, int dtype, int T,
     if (mode == SDP_MASK_BACKWARD) bytes += 3 * round_up((size_t)T * p * e, 256);
     bytes += 3 * round_up((size_t)p * ld_tokens(T) * e, 256); // neuron-major copies of dG, dU, Act on the mask
     if (mode == SDP_MASK_BACKWARD) bytes += round_up((size_t)F * sizeof(int32_t), 256); // rank of every neuron in the list
+    if (dtype == SDP_BF16) bytes += round_up(gemm_tail_ws_bytes(p, d, T, 3), 256); // depth ranges of the weight gradients' last round
     return bytes;
 }
 
@@ -184,6 +185,8 @@ int sdp::mlp_bwd_impl(int mode, int dtype, int T, int d, int F, int p, const voi
     void *dGn = w, *dUn = w + nm_b, *Actn = w + 2 * nm_b; // [p][T(+pad)]: neuron-major
     w += 3 * nm_b;
     int32_t* ranks = (int32_t*)w; // backward masking: [F]
+    if (mode == SDP_MASK_BACKWARD) w += round_up((size_t)F * sizeof(int32_t), 256);
+    void* tail_ws = dtype == SDP_BF16 && gemm_tail_ws_bytes(p, d, T, 3) > 0 ? w : nullptr;
 
     // the four operand copies of the backward pass as one launch (X^T, dY^T only feed the weight gradients)
     const TransposeJob tj[4] = {{W1, W1c, d, n, gather, n, d},
@@ -207,6 +210,7 @@ int sdp::mlp_bwd_impl(int mode, int dtype, int T, int d, int F, int p, const voi
     dw.c_scatter = dw_layout == SDP_DW_SCATTER ? idx_k : nullptr;
     dw.nbatch = 3;
     dw.lda = ld_tokens(T), dw.a_km = 0;
+    dw.tail_ws = tail_ws, dw.tail_name = "mlp_dw_reduce";
     for (int i = 0; i < 3; ++i) dw.Ab[i] = nmaj[i], dw.Bb[i] = rhs[i], dw.Cb[i] = outp[i];
 
     GemmDesc da;

@@ -27,7 +27,8 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_recorded.json")
 COPY_NAME = "__amd_rocclr_copyBuffer"
 
 # call-site name of each contraction <-> the <epilogue, op> template arguments of its kernel symbol
-SITE_OF = {(2, 0): "mlp_gate_up", (0, 1): "mlp_down", (3, 2): "mlp_dact", (1, 3): "mlp_dx", (0, 4): "mlp_dw"}
+SITE_OF = {(2, 0): "mlp_gate_up", (0, 1): "mlp_down", (3, 2): "mlp_dact", (1, 3): "mlp_dx", (0, 4): "mlp_dw",
+           (0, 6): "mlp_dw"}  # op 6: the weight-gradient launch with the tiles of its last round cut in depth
 
 
 def kernel_site(kernel_name):
@@ -37,6 +38,8 @@ def kernel_site(kernel_name):
         return COPY_NAME
     if "avg_rows_kernel<1, 0>" in kernel_name or "avg_rows_kernel<true, 0>" in kernel_name:
         return "coverage_grad_avg"
+    if "tail_reduce_kernel" in kernel_name:
+        return "mlp_dw_reduce"
     if "sdp_gemm_kernel<" in kernel_name:
         args = kernel_name.split("sdp_gemm_kernel<", 1)[1].split(">", 1)[0].split(",")
         try:
@@ -155,7 +158,7 @@ def run(what, workload_name, zeros):
             Y, G, U = sdp.masked_mlp_fwd(w.mode, X, *Wd, idx[0])
             sdp.masked_mlp_bwd(w.mode, X, dY, *Wd, idx[0], G, U)
         torch.cuda.synchronize()
-        for site in SITE_OF.values():
+        for site in set(SITE_OF.values()):
             shapes["launch"][site] = sdp.profile_launch_shape(site)
         sdp.profile_enable(False)
         print(f"{name}: one worker fwd+bwd x{reps}", flush=True)
