@@ -188,7 +188,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: keeps what derives from it scalar
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int l32 = lane & 31, lhi = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4; // the MFMA's lane coordinates: index along the 16 rows, depth / output quarter
 
     // ---- workgroup -> (problem of the batch, tile), XCD-aware ----
     // Ids congruent mod 8 share an XCD: XCD x is given the contiguous range [start_x, start_x + count_x)
@@ -324,13 +324,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
         }
     };
 
-    f32x16 acc[FM][FN];
+    // Accumulators: the wave's WM x WN outputs as 16 x 16 tiles of v_mfma_f32_16x16x32_bf16, grouped by 32 x 32
+    // blocks (i, j): acc[i][j][q] is the tile with rows 32 i + 16 (q >> 1) .. and columns 32 j + 16 (q & 1) ..
+    // (the 16 x 16 x 32 form sustains a higher clock than 32 x 32 x 16 on random operands: the same flops draw
+    // less power)
+    f32x4 acc[FM][FN][4];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int q = 0; q < 4; ++q) acc[i][j][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // B tile row where fragment j of this wave starts (wave-uniform)
     int bfrag[FN];
@@ -344,37 +348,42 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
 
     // ---- LDS read addresses.  Everything that depends on the lane is folded into a few byte
     // offsets; fragment index, depth sub-step and stage only add compile-time constants.
-    // row tile: chunk (r, c) at r*8 + (c ^ ((r >> 1) & 7)); for r = base + lane%32 with base a
-    // multiple of 32 the XOR term is (lane%32 >> 1) & 7 for every fragment.
-    int row_off[BK / 16];
+    // row tile: chunk (r, c) at r*8 + (c ^ ((r >> 1) & 7)); for r = base + lane%16 with base a
+    // multiple of 16 the XOR term is (lane%16 >> 1) & 7 for every fragment.  A fragment is 16 rows x 32 depth:
+    // lane (l16, lq) takes row l16, depth chunk 4 s + lq of the 32-deep sub-step s; the 16 lanes of one lq hit
+    // every 16-byte slot of a 256-byte bank row once.
+    int row_off[BK / 32];
 #pragma unroll
-    for (int s = 0; s < BK / 16; ++s) row_off[s] = (((2 * s + lhi) ^ ((l32 >> 1) & 7)) * 16) + l32 * 128;
+    for (int s = 0; s < BK / 32; ++s) row_off[s] = (((4 * s + lq) ^ ((l16 >> 1) & 7)) * 16) + l16 * 128;
     const int a_base = WM * wm * 128;
 
-    auto read_frags = [&](const unsigned char* sa, const unsigned char* sb, int s, bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
+    // fragments of sub-step s: fa[2 i + h] = rows 32 i + 16 h .. of the wave's A rows, fb[2 j + w] likewise for B
+    auto read_frags = [&](const unsigned char* sa, const unsigned char* sb, int s, bf16x8 (&fa)[2 * FM], bf16x8 (&fb)[2 * FN]) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
-            fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 32 * 128 + row_off[s]));
+        for (int i = 0; i < 2 * FM; ++i)
+            fa[i] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sa + a_base + i * 16 * 128 + row_off[s]));
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-            fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + bfrag[j] * 128 + row_off[s]));
+        for (int j = 0; j < 2 * FN; ++j)
+            fb[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(sb + (bfrag[j >> 1] + 16 * (j & 1)) * 128 + row_off[s]));
     };
-    // B fragment first: the accumulator tile is then indexed [n][m] in the MFMA's own layout, i.e.
-    // lane (l32, lhi) holds, for output row m = l32, columns n = 8 q + 4 lhi + r in element 4 q + r.
-    auto mfma_step = [&](const bf16x8 (&fa)[FM], const bf16x8 (&fb)[FN]) {
+    // B fragment first: the accumulator tile is then indexed [n][m] in the MFMA's own layout, i.e. lane (l16, lq)
+    // holds, for output row m = l16 of the tile, its columns n = 4 lq + r in element r.
+    auto mfma_step = [&](const bf16x8 (&fa)[2 * FM], const bf16x8 (&fb)[2 * FN]) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+        for (int i = 0; i < 2 * FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < 2 * FN; ++j) {
+                f32x4& c = acc[i >> 1][j >> 1][2 * (i & 1) + (j & 1)];
+                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], c, 0, 0, 0);
+            }
     };
 
     // ---- main loop: two wave groups in alternating phases.
     // Group 0 = the first half of the waves, group 1 = the second half; the hardware places wave w of
     // a workgroup on SIMD w % 4, so every SIMD holds one wave of each group.  A depth step is cut into
-    // two halves of two 16-deep sub-steps.  Each wave alternates a READ phase (the 2 (FM + FN) fragment
+    // two 32-deep halves.  Each wave alternates a READ phase (the 2 (FM + FN) fragment
     // reads of one half from LDS, plus its share of the direct loads of later steps) with a COMPUTE
-    // phase (the 2 FM FN MFMAs of that half, at raised priority), and the two groups are one phase
+    // phase (the 4 FM FN MFMAs of that half, at raised priority), and the two groups are one phase
     // apart: while one wave of a SIMD computes, the other one reads.  One wave alone keeps the matrix
     // core busy, so the MFMA stream never waits for LDS or for the load unit.  Every phase ends with a
     // workgroup barrier (plain s_barrier: the waits it needs are stated explicitly, and loads of later
@@ -389,15 +398,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     // barrier every wave waits until its loads for step k have landed (loads complete in issue
     // order; only the newest SB, B of step k + 1, may still be in flight).
     const int grp = wave / (NW / 2);
-    bf16x8 fa[2][FM], fb[2][FN];
-    auto read_half = [&](const unsigned char* sa, const unsigned char* sb, int h) {
-        read_frags(sa, sb, 2 * h, fa[0], fb[0]);
-        read_frags(sa, sb, 2 * h + 1, fa[1], fb[1]);
-    };
+    bf16x8 fa[2 * FM], fb[2 * FN];
+    auto read_half = [&](const unsigned char* sa, const unsigned char* sb, int h) { read_frags(sa, sb, h, fa, fb); };
     auto compute_half = [&]() {
         __builtin_amdgcn_s_setprio(1);
-        mfma_step(fa[0], fb[0]);
-        mfma_step(fa[1], fb[1]);
+        mfma_step(fa, fb);
         __builtin_amdgcn_s_setprio(0);
     };
     auto phase_end = [&]() {
@@ -462,22 +467,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     if (g.K % BK == 0) run(std::false_type{}); else run(std::true_type{});
 
     // ================================ epilogue ================================
-    // acc[i][j][4q + r] = C(m, n),  m = m0 + WM wm + 32 i + l32,
-    //                               n = n0 + (column base of fragment j) + 8 q + 4 lhi + r.
+    // acc[i][j][q][r] = C(m, n),  m = m0 + WM wm + 32 i + 16 (q >> 1) + l16,
+    //                             n = n0 + (column base of block j) + 16 (q & 1) + 4 lq + r.
     if constexpr (kSplit) {
         // fp32 partial sums of this depth range, 16 bytes (4 columns) per store; N % 8 == 0
         float* P = g.partial + ((int64_t)kpart * g.nbatch + batch) * g.M * g.N;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
-            const int m = m0 + WM * wm + 32 * i + l32;
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + WN * wn + 32 * j + 8 * q + 4 * lhi;
-                    if (m < g.M && n < g.N)
-                        *(f32x4*)(P + (int64_t)m * g.N + n) =
-                            f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    const int m = m0 + WM * wm + 32 * i + 16 * (q >> 1) + l16;
+                    const int n = n0 + WN * wn + 32 * j + 16 * (q & 1) + 4 * lq;
+                    if (m < g.M && n < g.N) *(f32x4*)(P + (int64_t)m * g.N + n) = acc[i][j][q];
                 }
         }
         return;
@@ -493,8 +496,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                 for (int j = 0; j < FN; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        *(f32x4*)(P + (WM * wm + 32 * i + l32) * BN + WN * wn + 32 * j + 8 * q + 4 * lhi) =
-                            f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        *(f32x4*)(P + (WM * wm + 32 * i + 16 * (q >> 1) + l16) * BN + WN * wn + 32 * j + 16 * (q & 1) + 4 * lq) =
+                            acc[i][j][q];
             return;
         }
     }
@@ -505,12 +508,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
     unsigned char* strip0 = smem + wave * Geo::WAVE_LDS;
     const int wcol0 = kFwd ? n0 + (WN / 2) * wn : n0 + WN * wn; // first output column of this wave's strips
 
-    // one packed 8-byte group of a strip: row l32, columns cbase + 8 q + 4 lhi ..
+    // one packed 8-byte group of a strip (this lane's 4 columns of tile q of a 32 x 32 block): row 16 (q >> 1) + l16,
+    // columns cbase + 16 (q & 1) + 4 lq ..
     auto strip_put = [&](unsigned char* strip, int cbase, int q, u32x2 v) {
-        *(u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2) = v;
+        *(u32x2*)(strip + (16 * (q >> 1) + l16) * RS + (cbase + 16 * (q & 1) + 4 * lq) * 2) = v;
     };
     auto strip_get = [&](const unsigned char* strip, int cbase, int q) {
-        return *(const u32x2*)(strip + l32 * RS + (cbase + 8 * q + 4 * lhi) * 2);
+        return *(const u32x2*)(strip + (16 * (q >> 1) + l16) * RS + (cbase + 16 * (q & 1) + 4 * lq) * 2);
     };
     // Global accesses of the epilogue go through buffer resources whose base is this wave's corner of the tile and
     // whose extent ends with the matrix's last row: for an offset at or beyond the extent the hardware returns zero
@@ -658,10 +662,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                         for (int j = 0; j < FN; ++j)
 #pragma unroll
                             for (int q = 0; q < 4; ++q) {
-                                acc[i][j][4 * q] += lo_bf16(rq[j][q][0]);
-                                acc[i][j][4 * q + 1] += hi_bf16(rq[j][q][0]);
-                                acc[i][j][4 * q + 2] += lo_bf16(rq[j][q][1]);
-                                acc[i][j][4 * q + 3] += hi_bf16(rq[j][q][1]);
+                                acc[i][j][q][0] += lo_bf16(rq[j][q][0]);
+                                acc[i][j][q][1] += hi_bf16(rq[j][q][0]);
+                                acc[i][j][q][2] += lo_bf16(rq[j][q][1]);
+                                acc[i][j][q][3] += hi_bf16(rq[j][q][1]);
                             }
                     }
                 }
@@ -670,7 +674,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         strip_put(strip0, 32 * j, q,
-                                  pack4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+                                  pack4(acc[i][j][q][0], acc[i][j][q][1], acc[i][j][q][2], acc[i][j][q][3]));
                 if (g.cs) strip_store_scatter(strip0, gC, g.ldc, g.cs, i); else strip_store(strip0, gC, g.ldc, i, std::integral_constant<int, kKeep>{});
             } else if (EPI == EPI_SWIGLU_FWD) {
                 // fragments 2 jj (gate) and 2 jj + 1 (up) cover the same 32 neurons
@@ -683,7 +687,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                             float v[4];
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                const float gv = acc[i][2 * jj][4 * q + r], uv = acc[i][2 * jj + 1][4 * q + r];
+                                const float gv = acc[i][2 * jj][q][r], uv = acc[i][2 * jj + 1][q][r];
                                 v[r] = which == 0 ? gv : (which == 1 ? uv : swiglu_fwd<false>(gv, uv));
                             }
                             strip_put(strip0, 32 * jj, q, pack4(v[0], v[1], v[2], v[3]));
@@ -717,7 +721,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void sdp_gemm_kernel(Dev 
                             const uint32_t gw = gq[j][q][r >> 1], uw = uq[j][q][r >> 1];
                             const float gv = (r & 1) ? hi_bf16(gw) : lo_bf16(gw);
                             const float uv = (r & 1) ? hi_bf16(uw) : lo_bf16(uw);
-                            swiglu_bwd<false>(acc[i][j][4 * q + r], gv, uv, dg[r], du[r], act[r]);
+                            swiglu_bwd<false>(acc[i][j][q][r], gv, uv, dg[r], du[r], act[r]);
                         }
                         strip_put(strip0, 32 * j, q, pack4(dg[0], dg[1], dg[2], dg[3]));
                         strip_put(strip1, 32 * j, q, pack4(du[0], du[1], du[2], du[3]));
