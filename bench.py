@@ -606,8 +606,10 @@ def main():
         rec["mfma_ceiling"] = {
             "random_operands_tflops": sdp.probe_mfma_tflops(rnd),
             "zero_operands_tflops": sdp.probe_mfma_tflops(torch.zeros_like(rnd)),
+            "random_operands_tflops_32x32x16": sdp.probe_mfma_tflops(rnd, shape=32),
             "published_peak_tflops": PEAK_BF16_TFLOPS,
-            "note": "v_mfma_f32_32x32x16_bf16 loop, 8 waves per CU, no memory traffic; measured live",
+            "note": "v_mfma_f32_16x16x32_bf16 loop (the instruction the contractions use; the 32x32x16 form for comparison), "
+                    "8 waves per CU, no memory traffic; measured live",
         }
         rec["vendor_gemm_yardstick"] = vendor_gemm_yardstick(torch, w)
     del res, x0

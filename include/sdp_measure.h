@@ -41,7 +41,9 @@ int sdp_profile_launch_shape(const char* name, int* tile_m, int* tile_n, int* gr
  * memory traffic inside the loop.  The clock the chip holds under MFMA load depends on the operand
  * values (power), so this is the practical ceiling that the contractions' rates can be read against.
  *   operands  device, sdp_probe_mfma_operand_bytes() bytes of bf16 values, 16-byte aligned
- *   blocks    workgroups of 512 lanes to launch (a few per CU), iters: 32 MFMAs per wave each
+ *   shape     16: v_mfma_f32_16x16x32_bf16 (the instruction the contractions use; sdp_probe_mfma_tflops measures
+ *             this one), 32: v_mfma_f32_32x32x16_bf16 (the same flops draw more power on random operands)
+ *   blocks    workgroups of 512 lanes to launch (a few per CU), iters: 1,048,576 flops per wave each
  *   sink      device scratch, sdp_probe_mfma_sink_bytes(blocks) bytes (written, never read)
  *   tflops    host out.  The call launches the loop twice, times the second launch with HIP events
  *             and synchronises `stream`.
@@ -49,6 +51,8 @@ int sdp_profile_launch_shape(const char* name, int* tile_m, int* tile_n, int* gr
 size_t sdp_probe_mfma_operand_bytes(void);
 size_t sdp_probe_mfma_sink_bytes(int blocks);
 int sdp_probe_mfma_tflops(const void* operands, int blocks, int iters, void* sink, double* tflops, void* stream);
+int sdp_probe_mfma_shape_tflops(int shape, const void* operands, int blocks, int iters, void* sink, double* tflops,
+                                void* stream);
 
 #ifdef __cplusplus
 }

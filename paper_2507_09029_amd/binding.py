@@ -112,6 +112,8 @@ def lib():
     L.sdp_probe_mfma_sink_bytes.argtypes = [i32]
     L.sdp_probe_mfma_tflops.restype = i32
     L.sdp_probe_mfma_tflops.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.sdp_probe_mfma_shape_tflops.restype = i32
+    L.sdp_probe_mfma_shape_tflops.argtypes = [i32, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = L
     return L
 
@@ -569,8 +571,9 @@ def profile_launch_shape(name):
     return {"tile": f"{v[0].value}x{v[1].value}", "group_m": v[2].value, "stacked": bool(v[3].value)}
 
 
-def probe_mfma_tflops(operands, blocks=1024, iters=500):
-    """Sustained bf16 MFMA rate (TFLOP/s) on the values of `operands` (bf16 tensor on the GPU)."""
+def probe_mfma_tflops(operands, blocks=1024, iters=500, shape=16):
+    """Sustained bf16 MFMA rate (TFLOP/s) on the values of `operands` (bf16 tensor on the GPU); shape 16 =
+    v_mfma_f32_16x16x32_bf16 (what the contractions use), 32 = v_mfma_f32_32x32x16_bf16."""
     L = lib()
     need = L.sdp_probe_mfma_operand_bytes()
     _dev(operands, torch.bfloat16, "operands")
@@ -578,6 +581,6 @@ def probe_mfma_tflops(operands, blocks=1024, iters=500):
         raise ValueError(f"operands: need at least {need} bytes")
     sink = torch.empty(L.sdp_probe_mfma_sink_bytes(blocks), dtype=torch.uint8, device=operands.device)
     out = ctypes.c_double(0.0)
-    _check(L.sdp_probe_mfma_tflops(operands.data_ptr(), blocks, iters, sink.data_ptr(), ctypes.byref(out), _stream()),
-           "sdp_probe_mfma_tflops")
+    _check(L.sdp_probe_mfma_shape_tflops(shape, operands.data_ptr(), blocks, iters, sink.data_ptr(), ctypes.byref(out), _stream()),
+           "sdp_probe_mfma_shape_tflops")
     return out.value

@@ -1,11 +1,11 @@
 // bf16 MFMA contraction for gfx950 (CDNA4) with the masked-MLP row gather and SwiGLU epilogues fused.
 //
-//   C[M][N] = sum_k A(m,k) B(k,n),  bf16 operands, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
+//   C[M][N] = sum_k A(m,k) B(k,n),  bf16 operands, fp32 accumulation in v_mfma_f32_16x16x32_bf16.
 //   A is stored [M][K], B is stored [N][K] (rows optionally gathered through an index table): both
 //   operands are read along the depth, 16 bytes (8 bf16) at a time.
 //
 // Tile: BM x BN outputs per workgroup, depth step 64, WAVES_M x WAVES_N waves of 64 lanes, each wave
-// owning (BM/WAVES_M) x (BN/WAVES_N) outputs as 32 x 32 MFMA tiles.  The flagship shape is
+// owning (BM/WAVES_M) x (BN/WAVES_N) outputs as 32 x 32 blocks of four 16 x 16 MFMA tiles.  The flagship shape is
 // 256 x 256 with 8 waves: 128 accumulator registers per lane, two waves per SIMD, one workgroup per CU.
 //
 // HBM/L2 -> LDS: direct loads (global_load_lds_dwordx4).  One wave instruction moves 64 chunks of
