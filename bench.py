@@ -300,8 +300,56 @@ def bench_attention(sdp, torch, steps, w=None):
                  "roofline": {"bound": "mfma", "achieved": (core_fwd + core_bwd) / (core_ms * 1e-3) / 1e12,
                               "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                               "frac": (core_fwd + core_bwd) / (core_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "traffic": None},
+                 "forward_backward_tflops": (core_fwd + core_bwd) / (core_ms * 1e-3) / 1e12,
                  "note": "causal: the half of the S x S products that is computed is counted (2 S^2 hd per head forward, 5 S^2 hd backward)"},
+        "vendor_attention_yardstick": vendor_attention_yardstick(torch, w) if w.hd % 8 == 0 else None,
     }
+
+
+def vendor_attention_yardstick(torch, w):
+    """What torch's own fused causal attention (scaled_dot_product_attention on its flash and memory-efficient
+    back ends) reaches on this machine at the core's shape (held heads only), flops counted like the core's: context
+    for the core's roofline fraction, not part of the path (the library never calls it)."""
+    import torch.nn.functional as F
+    from torch.nn.attention import SDPBackend, sdpa_kernel
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    shape = (w.Bt, w.ph, w.S, w.hd)
+    q, k, v = (torch.randn(shape, generator=gen, device="cuda").to(torch.bfloat16).requires_grad_(True) for _ in range(3))
+    do = torch.randn(shape, generator=gen, device="cuda").to(torch.bfloat16)
+    fwd_flop = 2 * w.Bt * w.ph * w.S * w.S * w.hd
+    out = {}
+    for name, backend in (("flash", SDPBackend.FLASH_ATTENTION), ("mem_efficient", SDPBackend.EFFICIENT_ATTENTION)):
+        def run(bwd):
+            with sdpa_kernel(backend):
+                o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
+            if bwd:
+                o.backward(do)
+                q.grad = k.grad = v.grad = None
+
+        try:
+            res = {}
+            for bwd in (False, True):
+                for _ in range(3):
+                    run(bwd)
+                torch.cuda.synchronize()
+                reps = 10
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    run(bwd)
+                e1.record()
+                torch.cuda.synchronize()
+                res["fwd_bwd_ms" if bwd else "fwd_ms"] = e0.elapsed_time(e1) / reps
+            res["forward_tflops"] = fwd_flop / (res["fwd_ms"] * 1e-3) / 1e12
+            res["forward_backward_tflops"] = 3.5 * fwd_flop / (res["fwd_bwd_ms"] * 1e-3) / 1e12
+            out[name] = res
+        except RuntimeError as e:  # a back end this torch build does not have for the shape
+            out[name] = {"unavailable": str(e)[:120]}
+    out["note"] = ("torch.nn.functional.scaled_dot_product_attention, bf16, causal, [sequences][held heads][S][head_dim]; "
+                   "10 back-to-back calls; flops: 2 S^2 hd per head forward, 5 S^2 hd backward (causal half)")
+    return out
 
 
 def vendor_gemm_yardstick(torch, w):
