@@ -196,6 +196,13 @@ def bench_grad_avg_1b(sdp, torch, steps):
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                      "traffic": recorded_traffic(c.name, "coverage_grad_avg", None)},
     }
+    # what plain streaming sustains on this machine (context for the fractions of the 8 TB/s figure; the library's path
+    # never runs these kernels): read-only over the first worker's gradient buffer, and a copy of it into `out`
+    res["hbm_streaming_ceiling"] = {
+        "read_only_gbs": sdp.probe_hbm_gbs(grads[0]), "copy_gbs": sdp.probe_hbm_gbs(grads[0], out),
+        "bytes": grads[0].numel() * 2,
+        "note": "16-byte non-temporal accesses, 5 launches each; copy = bytes read + bytes written per second",
+    }
     # the squared norm of the average alone (what gradient clipping needs before the fused update): reads the
     # covered gradient rows, writes nothing
     sq = torch.empty((1,), dtype=torch.float64, device="cuda")

@@ -54,6 +54,21 @@ int sdp_probe_mfma_tflops(const void* operands, int blocks, int iters, void* sin
 int sdp_probe_mfma_shape_tflops(int shape, const void* operands, int blocks, int iters, void* sink, double* tflops,
                                 void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Measurement aid (not a step of the method): the rate at which a plain streaming kernel moves data through
+ * HBM on this GPU, with the 16-byte non-temporal accesses the average kernels use.  The published 8 TB/s is
+ * a pin rate; reads alone and a mix of reads and writes sustain different fractions of it, and the
+ * HBM-bound kernels' rates can be read against these.
+ *   copy      0: read `bytes` from src (dst: at least 4 bytes, written only if the data hits one magic value);
+ *             1: copy `bytes` from src to dst
+ *   src, dst  device, 16-byte aligned, `bytes` each (dst: see above); bytes is rounded down to whole 16 KiB chunks
+ *             and should exceed the 256 MB of last-level cache many times
+ *   launches  timed launches (after one untimed)
+ *   gbs       host out: bytes moved (read + written) per second / 1e9.  Synchronises `stream`.
+ * Returns SDP_ERR_INVALID_ARG for null or misaligned pointers, launches < 1 or bytes below one chunk.
+ * ------------------------------------------------------------------------------------------- */
+int sdp_probe_hbm_gbs(int copy, const void* src, void* dst, size_t bytes, int launches, double* gbs, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

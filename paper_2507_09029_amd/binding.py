@@ -114,6 +114,8 @@ def lib():
     L.sdp_probe_mfma_tflops.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.sdp_probe_mfma_shape_tflops.restype = i32
     L.sdp_probe_mfma_shape_tflops.argtypes = [i32, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.sdp_probe_hbm_gbs.restype = i32
+    L.sdp_probe_hbm_gbs.argtypes = [i32, vp, vp, sz, i32, ctypes.POINTER(ctypes.c_double), vp]
     _lib = L
     return L
 
@@ -583,4 +585,25 @@ def probe_mfma_tflops(operands, blocks=1024, iters=500, shape=16):
     out = ctypes.c_double(0.0)
     _check(L.sdp_probe_mfma_shape_tflops(shape, operands.data_ptr(), blocks, iters, sink.data_ptr(), ctypes.byref(out), _stream()),
            "sdp_probe_mfma_shape_tflops")
+    return out.value
+
+
+def probe_hbm_gbs(src, dst=None, launches=5):
+    """GB/s a plain streaming kernel sustains over `src` (any contiguous GPU tensor): read-only if dst is None, else
+    a copy into dst (same size)."""
+    L = lib()
+    if not (isinstance(src, torch.Tensor) and src.is_cuda and src.is_contiguous()):
+        raise TypeError("src: expected a contiguous tensor on the GPU")
+    nbytes = src.numel() * src.element_size()
+    if dst is None:
+        sink = torch.zeros(16, dtype=torch.uint8, device=src.device)
+        target, copy = sink, 0
+    else:
+        if not (isinstance(dst, torch.Tensor) and dst.is_cuda and dst.is_contiguous()
+                and dst.numel() * dst.element_size() >= nbytes):
+            raise TypeError("dst: expected a contiguous GPU tensor at least as large as src")
+        target, copy = dst, 1
+    out = ctypes.c_double(0.0)
+    _check(L.sdp_probe_hbm_gbs(copy, src.data_ptr(), target.data_ptr(), nbytes, launches, ctypes.byref(out), _stream()),
+           "sdp_probe_hbm_gbs")
     return out.value

@@ -119,6 +119,9 @@ def test_argument_errors_are_caught_on_the_host():
     assert L.sdp_probe_mfma_tflops(None, 4, 4, FAKE, ctypes.byref(out), None) == -1
     assert L.sdp_probe_mfma_tflops(FAKE, 0, 4, FAKE, ctypes.byref(out), None) == -1
     assert L.sdp_probe_mfma_operand_bytes() == 6 * 512 * 16 and L.sdp_probe_mfma_sink_bytes(2) == 2 * 512 * 4
+    assert L.sdp_probe_hbm_gbs(0, None, FAKE, 1 << 20, 1, ctypes.byref(out), None) == -1
+    assert L.sdp_probe_hbm_gbs(0, FAKE, FAKE, 1 << 20, 0, ctypes.byref(out), None) == -1
+    assert L.sdp_probe_hbm_gbs(1, FAKE, FAKE, 1000, 1, ctypes.byref(out), None) == -1  # less than one chunk
     assert L.sdp_coverage_grad_avg(2, 4, 0, 1, ptrs, FAKE, FAKE, FAKE, None) == -1
     assert L.sdp_coverage_grad_avg(2, 4, 8, 7, ptrs, FAKE, FAKE, FAKE, None) == -1
     assert L.sdp_coverage_grad_avg(2, 4, 8, 1, None, FAKE, FAKE, FAKE, None) == -1

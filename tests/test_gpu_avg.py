@@ -125,3 +125,12 @@ def test_squared_norm_empty_and_errors(sdp):
     m = torch.ones((2, 4), dtype=torch.uint8, device="cuda")
     with pytest.raises(RuntimeError):
         sdp.coverage_grad_sqnorm([g, g], m, ws=torch.empty(16, dtype=torch.uint8, device="cuda")[:0])
+
+
+def test_hbm_streaming_probe_copies_and_reports_a_rate(sdp):
+    """The measurement aid: the copy form really copies (whole 16 KiB chunks), both forms report a positive rate."""
+    src = torch.randint(0, 255, (3 * 16384 + 100,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    assert sdp.probe_hbm_gbs(src, dst, launches=2) > 0
+    assert torch.equal(dst[: 3 * 16384], src[: 3 * 16384]) and int(dst[3 * 16384:].sum()) == 0
+    assert sdp.probe_hbm_gbs(src, launches=2) > 0
