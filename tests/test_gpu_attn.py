@@ -267,3 +267,41 @@ def test_forward_core_with_logits_that_keep_growing(sdp, orc):
     lse2 = zmax[..., 0] + np.log2(np.exp2(z - zmax).sum(axis=-1))
     assert np.abs(LSE.cpu().numpy() - lse2).max() <= 1e-4 * np.abs(lse2).max()
     assert_close_rows(workloads.to_f64(O), ref["O"], TOL, "O")
+
+
+def _filled(shape, dtype, fill):
+    t = torch.empty(shape, dtype=dtype, device="cuda")
+    t.view(torch.uint8).fill_({"zero": 0, "nan": 0xFF, "big": 0x46}[fill])
+    return t
+
+
+POISON = [w for w in CASES if w.name in ("two_heads_of_four", "ragged_depth", "several_blocks", "bf16_hd50", "f32_hd50_odd_sizes")]
+
+
+@pytest.mark.parametrize("mode", ["fm", "bm"])
+@pytest.mark.parametrize("w", POISON, ids=[w.name for w in POISON])
+def test_results_do_not_depend_on_what_workspace_and_outputs_held(sdp, w, mode):
+    """Nothing uninitialised is read: workspaces and output buffers pre-filled with NaN patterns, or with large
+    finite values, give the same bits as zeroed ones (the padding columns of the saved tensors included)."""
+    Wqkv, WoT = (t.cuda() for t in workloads.attn_weights(w))
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.H, w.ph, w.mask_seed, True)
+    k = w.K - 1
+    X, dY = (t.cuda() for t in workloads.attn_batch(w, k))
+    dt = X.dtype
+    n = w.ph if mode == "fm" else w.H
+    hw = sdp.attn_saved_head_width(dt, w.hd)
+    E = w.ph * w.hd
+    res = {}
+    for fill in ("zero", "nan", "big"):
+        wsf = _filled((sdp.masked_attn_fwd_workspace_bytes(mode, dt, w.Bt, w.S, w.d, w.H, w.hd, w.ph) + 256,), torch.uint8, fill)
+        wsb = _filled((sdp.masked_attn_bwd_workspace_bytes(mode, dt, w.Bt, w.S, w.d, w.H, w.hd, w.ph) + 256,), torch.uint8, fill)
+        fo = (_filled((w.T, w.d), dt, fill), _filled((w.T, 3 * n * hw), dt, fill), _filled((w.T, n * hw), dt, fill),
+              _filled((w.Bt, n, w.S), torch.float32, fill))
+        Y, QKV, O, LSE = sdp.masked_attn_fwd(mode, w.Bt, w.S, w.hd, X, Wqkv, WoT, idx[k], out=fo, ws=wsf)
+        bo = (_filled((w.T, w.d), dt, fill), _filled((3, E, w.d), dt, fill), _filled((E, w.d), dt, fill))
+        back = sdp.masked_attn_bwd(mode, w.Bt, w.S, w.hd, X, dY, Wqkv, WoT, idx[k], QKV, O, LSE, out=bo, ws=wsb)
+        torch.cuda.synchronize()
+        res[fill] = [t.clone().view(torch.uint8) for t in (Y, QKV, O, LSE) + tuple(back)]
+    for fill in ("nan", "big"):
+        for name, a, b in zip(("Y", "QKV", "O", "LSE", "dX", "dWqkv", "dWoT"), res["zero"], res[fill]):
+            assert torch.equal(a, b), f"{w.name} {mode}: {name} depends on the previous contents of a buffer ({fill})"

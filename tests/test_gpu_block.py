@@ -182,3 +182,37 @@ def test_k_worker_step_over_a_stack_of_blocks(sdp, orc):
     want, wc = orc.gated_average(refs, want_mask)
     assert (c.cpu().numpy() == wc).all() and (wc >= 1).all()
     assert_close(avg.cpu().numpy(), want, 1e-4, "coverage average over blocks")
+
+
+def _filled(shape, dtype, fill):
+    t = torch.empty(shape, dtype=dtype, device="cuda")
+    t.view(torch.uint8).fill_({"zero": 0, "nan": 0xFF, "big": 0x46}[fill])
+    return t
+
+
+@pytest.mark.parametrize("mode,m,rule", [("fm", 1, "through"), ("bm", 0, "through")])
+def test_results_do_not_depend_on_what_workspace_and_outputs_held(sdp, mode, m, rule):
+    """Nothing uninitialised is read: workspaces and output buffers pre-filled with NaN patterns, or with large
+    finite values, give the same bits as zeroed ones."""
+    Bt, S, d, H, hd, F = 2, 200, 256, 4, 64, 520
+    t = {n: v.cuda() for n, v in _setup(70, Bt, S, d, H, hd, F, "bf16").items()}
+    X, dY, Wqkv, WoT, W1, W3, W2T = (t[n] for n in ("X", "dY", "Wqkv", "WoT", "W1", "W3", "W2T"))
+    dt, T, E = X.dtype, Bt * S, H * hd
+    Es = H * sdp.attn_saved_head_width(dt, hd)
+    res = {}
+    for fill in ("zero", "nan", "big"):
+        wsf = _filled((sdp.block_fwd_workspace_bytes(dt, Bt, S, d, H, hd, F) + 256,), torch.uint8, fill)
+        wsb = _filled((sdp.block_bwd_workspace_bytes(dt, Bt, S, d, H, hd, F) + 256,), torch.uint8, fill)
+        fo = (_filled((T, d), dt, fill), _filled((T, d), dt, fill), _filled((T, 3 * Es), dt, fill), _filled((T, Es), dt, fill),
+              _filled((Bt, H, S), torch.float32, fill), _filled((T, F), dt, fill), _filled((T, F), dt, fill))
+        Y, saved = sdp.block_fwd(mode, m, Bt, S, hd, X, Wqkv, WoT, W1, W3, W2T, out=fo, ws=wsf)
+        bo = (_filled((T, d), dt, fill),)
+        if m:
+            bo += (_filled((3, E, d), dt, fill), _filled((E, d), dt, fill)) + tuple(_filled((F, d), dt, fill) for _ in range(3))
+        dX, grads = sdp.block_bwd(mode, m, Bt, S, hd, X, dY, Wqkv, WoT, W1, W3, W2T, saved, dx_rule=rule, out=bo, ws=wsb)
+        torch.cuda.synchronize()
+        res[fill] = [t.clone().view(torch.uint8) for t in (Y,) + tuple(saved) + (dX,) + (tuple(grads) if grads else ())]
+    for fill in ("nan", "big"):
+        assert len(res[fill]) == len(res["zero"])
+        for i, (a, b) in enumerate(zip(res["zero"], res[fill])):
+            assert torch.equal(a, b), f"block {mode} m={m}: tensor {i} depends on the previous contents of a buffer ({fill})"

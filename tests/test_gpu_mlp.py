@@ -151,3 +151,39 @@ def test_fp32_path_and_bf16_path_agree_on_the_same_inputs(sdp, mode):
     for got, ref, what in zip(outs["bf16"], outs["f32"], ("Y", "G", "U", "dX", "dW1", "dW3", "dW2T")):
         elem, norm = err_report(got, ref)
         assert norm <= 1e-2 and elem <= 2e-2, f"{what}: elementwise {elem:.3e}, normwise {norm:.3e}"
+
+
+def _filled(shape, dtype, fill):
+    """A GPU tensor whose bytes are all zero, all 0xFF (NaN in bf16 and fp32) or all 0x46 (about 1.3e4 in both)."""
+    t = torch.empty(shape, dtype=dtype, device="cuda")
+    t.view(torch.uint8).fill_({"zero": 0, "nan": 0xFF, "big": 0x46}[fill])
+    return t
+
+
+POISON = [w for w in SMALL if w.name in ("ragged_f32_fm", "tiles_bf16_fm", "tiles_bf16_bm", "aligned_bf16_bm", "tiny_bf16_fm")] + [
+    MlpWorkload("mixed_paths_bf16_fm", "bf16", 552, 440, 1536, 1312, 4, "fm", 23),  # depth 440: plain kernels beside MFMA ones
+]
+
+
+@pytest.mark.parametrize("w", POISON, ids=[w.name for w in POISON])
+def test_results_do_not_depend_on_what_workspace_and_outputs_held(sdp, w):
+    """Nothing uninitialised is read: the same calls with the workspaces and every output buffer pre-filled with
+    NaN patterns, or with large finite values, give the bits they give over zeroed buffers."""
+    Wd = [t.cuda() for t in workloads.mlp_weights(w)]
+    mask, idx, pos, cov = sdp.make_masks(w.K, w.F, w.p, w.mask_seed, True)
+    k = w.K - 1
+    X, dY = (t.cuda() for t in workloads.mlp_batch(w, k))
+    n = w.p if w.mode == "fm" else w.F
+    res = {}
+    for fill in ("zero", "nan", "big"):
+        wsf = _filled((sdp.masked_mlp_fwd_workspace_bytes(w.mode, X.dtype, w.T, w.d, w.F, w.p) + 256,), torch.uint8, fill)
+        wsb = _filled((sdp.masked_mlp_bwd_workspace_bytes(w.mode, X.dtype, w.T, w.d, w.F, w.p) + 256,), torch.uint8, fill)
+        fo = (_filled((w.T, w.d), X.dtype, fill), _filled((w.T, n), X.dtype, fill), _filled((w.T, n), X.dtype, fill))
+        Y, G, U = sdp.masked_mlp_fwd(w.mode, X, *Wd, idx[k], out=fo, ws=wsf)
+        bo = (_filled((w.T, w.d), X.dtype, fill),) + tuple(_filled((w.p, w.d), X.dtype, fill) for _ in range(3))
+        back = sdp.masked_mlp_bwd(w.mode, X, dY, *Wd, idx[k], G, U, out=bo, ws=wsb)
+        torch.cuda.synchronize()
+        res[fill] = [t.clone().view(torch.uint8) for t in (Y, G, U) + tuple(back)]
+    for fill in ("nan", "big"):
+        for name, a, b in zip(("Y", "G", "U", "dX", "dW1", "dW3", "dW2T"), res["zero"], res[fill]):
+            assert torch.equal(a, b), f"{w.name}: {name} depends on the previous contents of a buffer ({fill})"
