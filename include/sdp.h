@@ -256,8 +256,8 @@ int sdp_masked_attn_bwd(int mode, int dtype, int Bt, int S, int d, int H, int hd
  *   LSE_save [Bt][H][S] fp32, G_save, U_save [T][F]
  *   dX [T][d] out;  dWqkv [3][H hd][d], dWoT [H hd][d], dW1, dW3, dW2T [F][d] out (m = 1 only; may be null otherwise)
  *   ws: sdp_block_fwd_workspace_bytes / sdp_block_bwd_workspace_bytes.
- * Limits as for the attention and MLP calls (bf16: d, hd, F multiples of 8, T a multiple of 8 in the backward call;
- * hd <= 128).  Y, Hm_save and X must be three different buffers, dX and dY two.
+ * Limits as for the attention and MLP calls (bf16: d and F multiples of 8, hd any value up to 64 (narrower heads are
+ * padded to 64 inside, as in the attention calls) or a multiple of 8 up to 128, T a multiple of 8 in the backward call).  Y, Hm_save and X must be three different buffers, dX and dY two.
  * Errors: INVALID_ARG (null, misaligned, aliasing, m not 0 / 1, unknown mode / dx_rule), SHAPE, WORKSPACE, UNSUPPORTED, HIP.
  * ------------------------------------------------------------------------------------------- */
 typedef enum { SDP_BLOCK_DX_THROUGH = 0, SDP_BLOCK_DX_SKIP = 1 } sdp_block_dx_rule;

@@ -49,7 +49,8 @@ int check_block(int mode, int m, int dtype, int Bt, int S, int d, int H, int hd,
     if ((int64_t)Bt * S >= ((int64_t)1 << 31) || (int64_t)H * hd >= ((int64_t)1 << 24)) return SDP_ERR_SHAPE;
     if ((int64_t)Bt * S * F >= ((int64_t)1 << 40)) return SDP_ERR_SHAPE;
     if (hd > 128) return SDP_ERR_UNSUPPORTED;
-    if (dtype == SDP_BF16 && (d % 8 || hd % 8 || F % 8)) return SDP_ERR_SHAPE;
+    // as for the attention block alone: heads up to 64 wide are padded to 64 inside, wider ones need 16-byte rows
+    if (dtype == SDP_BF16 && (d % 8 || (hd > 64 && hd % 8) || F % 8)) return SDP_ERR_SHAPE;
     return SDP_OK;
 }
 

@@ -58,6 +58,7 @@ CASES = [
     ("bf16", 2, 256, 256, 4, 64, 512),  # MFMA contractions and MFMA attention core
     ("bf16", 1, 200, 128, 2, 64, 264),  # ragged sequence and hidden width
     ("bf16", 2, 96, 64, 2, 32, 128),    # head width the MFMA core does not take: plain core
+    ("bf16", 2, 200, 200, 4, 50, 520),  # the paper's head width (padded to 64 inside), ragged everything
 ]
 
 
