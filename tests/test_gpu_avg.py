@@ -90,6 +90,7 @@ def test_avg_empty_input_and_binding_errors(sdp):
 @pytest.mark.parametrize("K,R,D,p,dtype", [
     (4, 300, 256, 150, "bf16"), (8, 1000, 2048, 690, "bf16"), (8, 257, 1536, 100, "f32"), (5, 40, 13, 20, "f32"),
     (5, 40, 7, 20, "bf16"), (1, 10, 512, 4, "bf16"), (8, 40000, 512, 27600, "bf16"),
+    (20, 700, 1032, 90, "bf16"), (64, 33, 1024, 3, "f32"),  # more workers than one batch of mask bytes
 ])
 def test_squared_norm_of_the_average_matches_oracle(sdp, orc, K, R, D, p, dtype):
     """sdp_coverage_grad_sqnorm against the oracle's fp64 sum; NaN in rows nobody covers is never read; the value
